@@ -1,0 +1,446 @@
+"""Pins for the CPU oracle: everything here checks oracle/laud_oracle.py against something
+other than itself -- an independent per-output-element evaluator written with explicit
+loops and bounds checks, closed forms, invariants the paper states, library routines for
+the special cases that reduce to one, and the one set of values the paper prints."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import laud_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- #
+# independent brute-force evaluator (pure Python floats, no numpy arithmetic)
+# --------------------------------------------------------------------------- #
+def _rand_params(rng, c_in, m, c_out, relu_out=False):
+    return O.BottleneckParams(
+        w1=rng.standard_normal((m, c_in)), w2=rng.standard_normal((m, 3, 3, m)) * 0.5,
+        w3=rng.standard_normal((c_out, m)),
+        s1=1 + 0.3 * rng.standard_normal(m), t1=0.5 * rng.standard_normal(m),
+        s2=1 + 0.3 * rng.standard_normal(m), t2=0.5 * rng.standard_normal(m),
+        s3=1 + 0.3 * rng.standard_normal(c_out), t3=0.5 * rng.standard_normal(c_out),
+        relu_out=relu_out)
+
+
+def _bf_h1(x, p, n, y, xx, i):
+    """conv1 output channel i at pixel (y, xx); ZERO outside the image (the 3x3's padding
+    is on its own input, not on x)."""
+    H, W, C = len(x[0]), len(x[0][0]), len(x[0][0][0])
+    if y < 0 or y >= H or xx < 0 or xx >= W:
+        return 0.0
+    acc = 0.0
+    for c in range(C):
+        acc += p["w1"][i][c] * x[n][y][xx][c]
+    v = p["s1"][i] * acc + p["t1"][i]
+    return v if v > 0.0 else 0.0
+
+
+def _bf_h2(x, p, n, y, xx, j, cm=None):
+    m = len(p["w1"])
+    acc = 0.0
+    for ky in range(3):
+        for kx in range(3):
+            for i in range(m):
+                h1 = _bf_h1(x, p, n, y + ky - 1, xx + kx - 1, i)
+                if cm is not None:
+                    h1 *= cm[i]
+                acc += p["w2"][j][ky][kx][i] * h1
+    v = p["s2"][j] * acc + p["t2"][j]
+    v = v if v > 0.0 else 0.0
+    if cm is not None:
+        v *= cm[j]
+    return v
+
+
+def _bf_out(x, p, n, y, xx, o, relu_out, cm=None):
+    m = len(p["w1"])
+    acc = 0.0
+    for j in range(m):
+        acc += p["w3"][o][j] * _bf_h2(x, p, n, y, xx, j, cm)
+    v = x[n][y][xx][o] + p["s3"][o] * acc + p["t3"][o]
+    if relu_out and v < 0.0:
+        v = 0.0
+    return v
+
+
+def _as_lists(p):
+    return {k: np.asarray(getattr(p, k), np.float64).tolist()
+            for k in ("w1", "w2", "w3", "s1", "t1", "s2", "t2", "s3", "t3")}
+
+
+def brute_force_dyn(x, p, S, mask):
+    xl = np.asarray(x, np.float64).tolist()
+    pl = _as_lists(p)
+    N, H, W, C = np.shape(x)
+    out = np.array(x, np.float64)
+    for n in range(N):
+        for y in range(H):
+            for xx in range(W):
+                if mask[n][y // S][xx // S]:
+                    for o in range(C):
+                        out[n, y, xx, o] = _bf_out(xl, pl, n, y, xx, o, p.relu_out)
+    return out
+
+
+@pytest.mark.parametrize("S", [1, 2, 4])
+@pytest.mark.parametrize("relu_out", [False, True])
+def test_dyn_block_vs_bruteforce_all_masks(S, relu_out):
+    rng = np.random.default_rng(100 + S)
+    N, H, W, c_in, m = 1, 4, 4, 4, 2
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_in, relu_out)
+    hp = H // S
+    cells = N * hp * hp
+    if cells <= 4:
+        masks = list(itertools.product([0, 1], repeat=cells))
+    else:  # S = 1: 2^16 masks is too many; all single-cell masks, their complements, and random ones
+        eye = [tuple(int(i == j) for i in range(cells)) for j in range(cells)]
+        comp = [tuple(1 - v for v in e) for e in eye]
+        rnd = [tuple(rng.integers(0, 2, cells).tolist()) for _ in range(8)]
+        masks = eye + comp + rnd + [tuple([0] * cells), tuple([1] * cells)]
+    # the dense branch does not depend on the mask: evaluate the brute force once, all-active
+    full = brute_force_dyn(x, p, S, np.ones((N, hp, hp), int).tolist())
+    for bits in masks:
+        mk = np.array(bits, np.uint8).reshape(N, hp, hp)
+        want = np.where(O.upsample_mask(mk, S).astype(bool)[..., None], full, x)
+        got = O.dyn_bottleneck(x, p, S, mk)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_dyn_block_vs_bruteforce_batched_random_masks():
+    rng = np.random.default_rng(7)
+    N, H, W, c_in, m, S = 2, 6, 4, 3, 2, 2
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_in, relu_out=True)
+    for _ in range(3):
+        mk = rng.integers(0, 2, (N, H // S, W // S)).astype(np.uint8)
+        np.testing.assert_allclose(O.dyn_bottleneck(x, p, S, mk),
+                                   brute_force_dyn(x, p, S, mk.tolist()), rtol=1e-12, atol=1e-12)
+
+
+def test_border_padding_is_on_h1_not_on_x():
+    """With a non-zero conv1 shift, zero-padding x (instead of h1) would feed relu(t1) != 0 into
+    the 3x3 at the border; the brute force pads h1.  A single active corner patch isolates it."""
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((1, 4, 4, 3))
+    p = _rand_params(rng, 3, 2, 3)
+    p.t1 = np.array([0.9, 1.3])  # strictly positive shift
+    mk = np.zeros((1, 2, 2), np.uint8)
+    mk[0, 0, 0] = 1
+    np.testing.assert_allclose(O.dyn_bottleneck(x, p, 2, mk), brute_force_dyn(x, p, 2, mk.tolist()),
+                               rtol=1e-12, atol=1e-12)
+    # and the wrong reading is measurably different, so the test above has teeth
+    xpad = np.zeros((1, 6, 6, 3))
+    xpad[:, 1:5, 1:5] = x
+    wrong = O.static_bottleneck(xpad, p)[:, 1:5, 1:5]
+    assert np.abs(wrong[0, 0, 0] - O.static_bottleneck(x, p)[0, 0, 0]).max() > 1e-3
+
+
+# --------------------------------------------------------------------------- #
+# closed forms
+# --------------------------------------------------------------------------- #
+def test_conv3x3_box_filter_counts_neighbours():
+    """All-ones 3x3 kernel on an all-ones image counts in-bounds neighbours: 4 / 6 / 9."""
+    h = np.ones((1, 5, 6, 1))
+    out = O.conv3x3(h, np.ones((1, 3, 3, 1)))[0, :, :, 0]
+    assert out[0, 0] == out[0, -1] == out[-1, 0] == out[-1, -1] == 4
+    assert (out[0, 1:-1] == 6).all() and (out[-1, 1:-1] == 6).all()
+    assert (out[1:-1, 0] == 6).all() and (out[1:-1, -1] == 6).all()
+    assert (out[1:-1, 1:-1] == 9).all()
+
+
+@pytest.mark.parametrize("ky,kx", list(itertools.product(range(3), range(3))))
+def test_conv3x3_tap_orientation(ky, kx):
+    """Cross-correlation: an impulse at (y0,x0) seen through the single tap (ky,kx) lands at
+    (y0-(ky-1), x0-(kx-1)); channel routing in -> out as indexed."""
+    h = np.zeros((1, 5, 5, 2))
+    h[0, 2, 2, 1] = 3.0
+    w = np.zeros((3, 3, 3, 2))
+    w[2, ky, kx, 1] = 2.0
+    out = O.conv3x3(h, w)
+    want = np.zeros((1, 5, 5, 3))
+    want[0, 2 - (ky - 1), 2 - (kx - 1), 2] = 6.0
+    np.testing.assert_array_equal(out, want)
+
+
+def test_conv1x1_one_hot():
+    x = np.zeros((1, 2, 2, 3))
+    x[0, 1, 0, 2] = 5.0
+    w = np.arange(12, dtype=float).reshape(4, 3)
+    out = O.conv1x1(x, w)
+    want = np.zeros((1, 2, 2, 4))
+    want[0, 1, 0, :] = 5.0 * w[:, 2]
+    np.testing.assert_array_equal(out, want)
+
+
+def test_branch_is_affine_in_s3_t3_and_linear_in_w3():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((1, 4, 4, 4))
+    p = _rand_params(rng, 4, 3, 4)
+    f0 = O.bottleneck_branch(x, p)
+    q = _rand_params(rng, 4, 3, 4)
+    q.__dict__.update({k: getattr(p, k) for k in ("w1", "w2", "s1", "t1", "s2", "t2")})
+    q.w3, q.s3, q.t3 = 2.0 * p.w3, p.s3, p.t3
+    np.testing.assert_allclose(O.bottleneck_branch(x, q) - p.t3, 2.0 * (f0 - p.t3), rtol=1e-12, atol=1e-12)
+    q.w3, q.s3, q.t3 = p.w3, 3.0 * p.s3, p.t3 + 1.0
+    np.testing.assert_allclose(O.bottleneck_branch(x, q), 3.0 * (f0 - p.t3) + p.t3 + 1.0, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- #
+# library special case: activation ratio 1 is a standard bottleneck
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("relu_out", [False, True])
+def test_ratio_one_equals_torch_conv2d_bottleneck(relu_out):
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(21)
+    N, H, W, c_in, m = 2, 8, 12, 16, 8
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_in, relu_out)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).double()
+    xt = t(x).permute(0, 3, 1, 2)
+    ch = lambda v: t(v).view(1, -1, 1, 1)
+    h1 = F.relu(F.conv2d(xt, t(p.w1)[:, :, None, None]) * ch(p.s1) + ch(p.t1))
+    h2 = F.relu(F.conv2d(h1, t(p.w2).permute(0, 3, 1, 2), padding=1) * ch(p.s2) + ch(p.t2))
+    y = xt + F.conv2d(h2, t(p.w3)[:, :, None, None]) * ch(p.s3) + ch(p.t3)
+    if relu_out:
+        y = F.relu(y)
+    want = y.permute(0, 2, 3, 1).numpy()
+    got = O.dyn_bottleneck(x, p, 4, np.ones((N, H // 4, W // 4), np.uint8))
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(O.static_bottleneck(x, p), want, rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# invariants of mask-then-select (Sec. 3.1; Fig. 2 caption)
+# --------------------------------------------------------------------------- #
+def test_ratio_zero_is_identity_and_single_flip_is_local():
+    rng = np.random.default_rng(5)
+    N, H, W, c, S = 2, 8, 8, 4, 2
+    x = rng.standard_normal((N, H, W, c))
+    p = _rand_params(rng, c, 2, c, relu_out=True)
+    zero = np.zeros((N, H // S, W // S), np.uint8)
+    out0 = O.dyn_bottleneck(x, p, S, zero)
+    assert np.array_equal(out0, x)
+    static = O.static_bottleneck(x, p)
+    for (n, py, px) in [(0, 0, 0), (1, 3, 2), (0, 1, 3)]:
+        mk = zero.copy()
+        mk[n, py, px] = 1
+        out = O.dyn_bottleneck(x, p, S, mk)
+        changed = np.any(out != x, axis=-1)
+        want = np.zeros((N, H, W), bool)
+        want[n, py * S:(py + 1) * S, px * S:(px + 1) * S] = True
+        assert np.array_equal(changed, want)
+        assert np.array_equal(out[want], static[want])
+
+
+def test_S_equal_H_is_layer_skipping():
+    """S = feature resolution turns the spatial block into layer skipping (Sec. 3.2)."""
+    rng = np.random.default_rng(6)
+    N, H, c = 3, 4, 4
+    x = rng.standard_normal((N, H, H, c))
+    p = _rand_params(rng, c, 2, c, relu_out=True)
+    keep = np.array([1, 0, 1], np.uint8)
+    a = O.dyn_bottleneck(x, p, H, keep.reshape(N, 1, 1))
+    b = O.layer_skip_bottleneck(x, p, keep)
+    assert np.array_equal(a, b)
+    assert np.array_equal(b[1], x[1])
+    assert np.array_equal(O.layer_skip_bottleneck(x, p, np.ones(N, np.uint8)), O.static_bottleneck(x, p))
+    assert np.array_equal(O.layer_skip_bottleneck(x, p, np.zeros(N, np.uint8)), x)
+    mk = rng.integers(0, 2, (N, 2, 2)).astype(np.uint8)
+    both = O.layer_skip_bottleneck(x, p, keep, 2, mk)
+    assert np.array_equal(both, O.dyn_bottleneck(x, p, 2, mk * keep[:, None, None]))
+    # one logit per sample when S = H
+    assert O.mask_logits(x, H, rng.standard_normal(c), 0.1).shape == (N, 1, 1)
+
+
+# --------------------------------------------------------------------------- #
+# masker (Sec. 3.2; App. B eq.)
+# --------------------------------------------------------------------------- #
+def test_two_logit_argmax_equals_one_channel_difference():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((3, 8, 8, 16))
+    for S in (1, 2, 4, 8):
+        w2 = rng.standard_normal((2, 16))
+        b2 = rng.standard_normal(2)
+        l2 = O.masker_two_logits(x, S, w2, b2)
+        one = O.mask_logits(x, S, w2[0] - w2[1], b2[0] - b2[1])
+        assert np.abs(one).min() > 1e-9  # no ties in this draw
+        assert np.array_equal(O.mask_from_two_logits(l2), O.threshold(one))
+        np.testing.assert_allclose(one, l2[..., 0] - l2[..., 1], rtol=1e-12, atol=1e-12)
+
+
+def test_masker_pool_and_1x1_commute():
+    """Pooling and a 1x1 conv are both linear and share the input (App. B), so the masker
+    logit equals the S x S mean of the per-pixel projection."""
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((2, 8, 12, 6))
+    w = rng.standard_normal(6)
+    per_pixel = O.conv1x1(x, w[None, :])  # [N,H,W,1]
+    for S in (1, 2, 4):
+        want = O.pool_patches(per_pixel, S)[..., 0] + 0.25
+        np.testing.assert_allclose(O.mask_logits(x, S, w, 0.25), want, rtol=1e-12, atol=1e-12)
+
+
+def test_mask_logits_hand_example_and_threshold_ties():
+    # 1 sample, 2x2 image, 2 channels, S=2: mean over the four pixels, then dot with w, plus bias
+    x = np.array([[[[1.0, 10.0], [2.0, 20.0]], [[3.0, 30.0], [6.0, 40.0]]]])
+    got = O.mask_logits(x, 2, np.array([2.0, -0.5]), 1.5)
+    assert got.shape == (1, 1, 1)
+    assert got[0, 0, 0] == pytest.approx(2.0 * 3.0 - 0.5 * 25.0 + 1.5)
+    assert O.threshold(np.array([0.0, -0.0, 1e-30, -1e-30, np.nan, np.inf])).tolist() == [0, 0, 1, 0, 0, 1]
+
+
+def test_valid_granularities_match_the_paper():
+    with open(os.path.join(GOLDEN, "valid_S_56.txt")) as f:
+        vals = [int(v) for line in f if not line.startswith("#") for v in line.split()]
+    x = np.zeros((1, 56, 56, 1))
+    ok = []
+    for S in range(1, 57):
+        try:
+            O.pool_patches(x, S)
+            ok.append(S)
+        except ValueError:
+            pass
+    assert ok == vals
+
+
+# --------------------------------------------------------------------------- #
+# index generation and gather
+# --------------------------------------------------------------------------- #
+def test_compact_definition():
+    rng = np.random.default_rng(10)
+    mk = rng.integers(0, 2, (5, 7, 7)).astype(np.uint8)
+    mk[2] = 0
+    mk[3] = 1
+    idx = O.compact(mk)
+    assert idx.dtype == np.int32
+    assert np.array_equal(idx, np.flatnonzero(mk.reshape(-1)))
+    assert len(idx) == int(mk.sum()) and np.all(np.diff(idx) > 0)
+    off = O.sample_offsets(mk)
+    assert off[0] == 0 and off[-1] == len(idx) and off[3] - off[2] == 0 and off[4] - off[3] == 49
+    for n in range(5):
+        seg = idx[off[n]:off[n + 1]]
+        assert np.all(seg // 49 == n)
+    assert O.compact(np.zeros((2, 3, 3), np.uint8)).size == 0
+    # any non-zero byte counts as set
+    assert O.compact(np.array([0, 2, 0, 255], np.uint8)).tolist() == [1, 3]
+
+
+def test_gather_all_active_halo0_is_a_retiling():
+    rng = np.random.default_rng(12)
+    N, H, W, C, S = 2, 8, 12, 3, 4
+    x = rng.standard_normal((N, H, W, C)).astype(np.float32)
+    idx = O.compact(np.ones((N, H // S, W // S), np.uint8))
+    g = O.gather_patches(x, S, 0, idx)
+    want = x.reshape(N, H // S, S, W // S, S, C).transpose(0, 1, 3, 2, 4, 5).reshape(-1, S, S, C)
+    assert g.dtype == x.dtype and np.array_equal(g, want)
+
+
+def test_gather_halo1_matches_padded_slices():
+    rng = np.random.default_rng(13)
+    N, H, W, C, S = 2, 6, 6, 2, 2
+    x = rng.standard_normal((N, H, W, C))
+    mk = rng.integers(0, 2, (N, 3, 3)).astype(np.uint8)
+    mk[0, 0, 0] = mk[1, 2, 2] = 1  # corners: zero fill on two sides
+    idx = O.compact(mk)
+    g = O.gather_patches(x, S, 1, idx)
+    xp = np.pad(x, ((0, 0), (1, 1), (1, 1), (0, 0)))
+    for p, q in enumerate(idx):
+        n, r = divmod(int(q), 9)
+        py, px = divmod(r, 3)
+        assert np.array_equal(g[p], xp[n, py * S:py * S + S + 2, px * S:px * S + S + 2])
+    assert np.all(g[0, 0, :, :] == 0) and np.all(g[0, :, 0, :] == 0)
+
+
+# --------------------------------------------------------------------------- #
+# channel skipping (Fig. 2 caption; Sec. 3.2)
+# --------------------------------------------------------------------------- #
+def test_channel_skip_special_cases_and_independent_formulation():
+    rng = np.random.default_rng(14)
+    N, H, c, m, D = 4, 5, 6, 8, 4
+    x = rng.standard_normal((N, H, H, c))
+    p = _rand_params(rng, c, m, c, relu_out=True)
+    ones = np.ones((N, D), np.uint8)
+    np.testing.assert_allclose(O.channel_skip_bottleneck(x, p, ones), O.static_bottleneck(x, p), rtol=1e-12)
+    zeros = np.zeros((N, D), np.uint8)
+    np.testing.assert_allclose(O.channel_skip_bottleneck(x, p, zeros), np.maximum(x + p.t3, 0), rtol=1e-12)
+    cm = rng.integers(0, 2, (N, D)).astype(np.uint8)
+    cm[0] = [1, 0, 0, 1]
+    got = O.channel_skip_bottleneck(x, p, cm)
+    G = m // D
+    for n in range(N):
+        # the same block with dropped channels removed from the weights: rows of W1, rows and
+        # columns of W2, columns of W3, and the shifts t1, t2 of dropped channels set to zero
+        k = np.repeat(cm[n].astype(bool), G)
+        q = _rand_params(rng, c, m, c, relu_out=True)
+        q.w1 = np.where(k[:, None], p.w1, 0.0)
+        q.w2 = np.where(k[:, None, None, None] & k[None, None, None, :], p.w2, 0.0)
+        q.w3 = np.where(k[None, :], p.w3, 0.0)
+        q.s1, q.s2, q.s3, q.t3 = p.s1, p.s2, p.s3, p.t3
+        q.t1 = np.where(k, p.t1, 0.0)
+        q.t2 = np.where(k, p.t2, 0.0)
+        np.testing.assert_allclose(got[n:n + 1], O.static_bottleneck(x[n:n + 1], q), rtol=1e-11, atol=1e-11)
+
+
+def test_channel_skip_vs_bruteforce():
+    rng = np.random.default_rng(15)
+    N, H, c, m, D = 2, 3, 3, 4, 2
+    x = rng.standard_normal((N, H, H, c))
+    p = _rand_params(rng, c, m, c)
+    cm = np.array([[1, 0], [0, 1]], np.uint8)
+    got = O.channel_skip_bottleneck(x, p, cm)
+    xl, pl = x.tolist(), _as_lists(p)
+    for n in range(N):
+        cvec = np.repeat(cm[n], m // D).astype(float).tolist()
+        for y in range(H):
+            for xx in range(H):
+                for o in range(c):
+                    assert got[n, y, xx, o] == pytest.approx(_bf_out(xl, pl, n, y, xx, o, False, cvec), abs=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# complexity closed forms (Sec. 3.2 "Computational complexity")
+# --------------------------------------------------------------------------- #
+def test_flop_ratios_closed_forms():
+    for c_in, m in [(256, 64), (512, 128), (1024, 256), (2048, 512)]:
+        f1, f2, f3 = O.conv_macs_per_pixel(c_in, m, c_in)
+        assert (f1, f2, f3) == (4 * m * m, 9 * m * m, 4 * m * m)
+        for r in (0.0, 0.25, 0.6, 1.0):
+            assert O.spatial_flops_ratio(r, r, c_in, m, c_in) == pytest.approx(r)
+            assert O.spatial_flops_ratio(r, 1.0, c_in, m, c_in) == pytest.approx((4 + 13 * r) / 17)
+            assert O.channel_flops_ratio(r, c_in, m, c_in) == pytest.approx((8 * r + 9 * r * r) / 17)
+            assert O.channel_flops_ratio(r, c_in, m, c_in) <= r + 1e-15
+    # every identity bottleneck of ResNet-50/101 at 224^2 costs the same: 17 m^2 * H*W MACs
+    assert {17 * m * m * hw * hw for m, hw in [(64, 56), (128, 28), (256, 14), (512, 7)]} == {218365952}
+
+
+def test_activation_and_dilated_ratio():
+    mk = np.zeros((1, 4, 4), np.uint8)
+    assert O.activation_ratio(mk) == 0 and O.dilated_ratio(mk, 2) == 0
+    mk[0, 1, 2] = 1
+    assert O.activation_ratio(mk) == 1 / 16
+    assert O.dilated_ratio(mk, 2) == pytest.approx(16 / 64)   # (S+2)^2 pixels of an 8x8 map
+    assert O.dilated_ratio(mk, 1) == pytest.approx(9 / 16)
+    mk[:] = 1
+    assert O.activation_ratio(mk) == 1 and O.dilated_ratio(mk, 2) == 1
+    # brute force on a random mask
+    rng = np.random.default_rng(16)
+    mk = rng.integers(0, 2, (2, 3, 3)).astype(np.uint8)
+    S = 2
+    cnt = 0
+    for n in range(2):
+        for y in range(6):
+            for x in range(6):
+                hit = False
+                for dy in (-1, 0, 1):
+                    for dx in (-1, 0, 1):
+                        yy, xx = y + dy, x + dx
+                        if 0 <= yy < 6 and 0 <= xx < 6 and mk[n, yy // S, xx // S]:
+                            hit = True
+                cnt += hit
+    assert O.dilated_ratio(mk, S) == pytest.approx(cnt / 72)
