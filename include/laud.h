@@ -1,0 +1,160 @@
+/*
+ * laud.h -- C ABI of the MI355X (gfx950) dynamic-bottleneck library.
+ *
+ * The library implements the inference hot path of the LAUDNet block (Sec. 3.1-3.2,
+ * Fig. 2): a spatial masker scores coarse S x S patches, the active patches are turned
+ * into an index list, and the residual bottleneck (1x1 -> 3x3 -> 1x1) is evaluated on
+ * those patches only and added back into the feature map in place of the skip value.
+ * Channel skipping and layer skipping (Sec. 3.1) use the same compaction machinery.
+ *
+ * Conventions that hold for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or keeps them.  Scratch memory is a caller-owned device workspace
+ *     sized with laud_workspace_size(); its contents are undefined between calls.
+ *   - Feature maps are dense NHWC: element (n,y,x,c) at ((n*H + y)*W + x)*C + c.  One
+ *     pixel's channel vector is contiguous.  dtype is LAUD_F32 or LAUD_BF16; C, c_in,
+ *     c_mid and c_out must be multiples of 8 and every tensor base 16-byte aligned.
+ *   - Weights have the feature map's dtype: w1 [c_mid][c_in], w2 [c_mid][3][3][c_mid]
+ *     (out, ky, kx, in; stride 1, zero padding 1, cross-correlation), w3 [c_out][c_mid].
+ *     The per-channel affine (folded BN, Sec. 3.4) is float32: s1,t1,s2,t2 [c_mid],
+ *     s3,t3 [c_out].  Accumulation, affine and the residual add are float32; h1, h2 and
+ *     the output are rounded (nearest-even) to dtype.
+ *   - Patch p of an H x W map with granularity S (S divides H and W; Hp = H/S, Wp = W/S)
+ *     has flat index (n*Hp + py)*Wp + px and covers pixels [py*S, py*S+S) x [px*S, px*S+S).
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and never synchronises.  Data-dependent counts stay on the device.
+ *   - Return value: LAUD_OK or a negative laud_status.  Arguments are validated on the
+ *     host before anything is launched; on error nothing has been launched.
+ */
+#ifndef LAUD_H
+#define LAUD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LAUD_OK = 0,
+  LAUD_ERR_INVALID_ARG = -1, /* null pointer, non-positive dim, S not dividing H/W, D not dividing c_mid */
+  LAUD_ERR_UNSUPPORTED = -2, /* dtype/shape outside what the kernels cover (e.g. channels % 8 != 0) */
+  LAUD_ERR_WORKSPACE = -3,   /* workspace missing or smaller than laud_workspace_size() */
+  LAUD_ERR_HIP = -4          /* a HIP launch failed */
+} laud_status;
+
+typedef enum { LAUD_F32 = 0, LAUD_BF16 = 1 } laud_dtype;
+
+typedef enum {
+  LAUD_OP_MASK_GEN = 0,
+  LAUD_OP_COMPACT = 1,
+  LAUD_OP_GATHER = 2,
+  LAUD_OP_DYN_BOTTLENECK = 3,
+  LAUD_OP_CHANNEL_SKIP = 4
+} laud_op;
+
+/* Shape of a dense NHWC feature map. */
+typedef struct {
+  int32_t N, H, W, C;
+  int32_t dtype; /* laud_dtype */
+} laud_fmap;
+
+/* Folded parameters of one residual bottleneck (Fig. 2(a); Sec. 3.4). Device pointers. */
+typedef struct {
+  int32_t c_in, c_mid, c_out; /* c_out must equal c_in (identity shortcut) */
+  const void* w1;
+  const void* w2;
+  const void* w3;
+  const float* s1;
+  const float* t1;
+  const float* s2;
+  const float* t2;
+  const float* s3;
+  const float* t3;
+  int32_t relu_out; /* non-zero: ReLU after the residual add, on computed pixels only */
+} laud_bottleneck;
+
+/* Human-readable name of a status code (static storage). */
+const char* laud_status_string(int status);
+
+/* Library ABI version (increments when a signature changes). */
+int laud_abi_version(void);
+
+/*
+ * Workspace bytes an entry point needs for the given shapes.  `op` is a laud_op; `p` may be
+ * NULL for ops that take no bottleneck; `S_or_D` is the spatial granularity S (mask-gen,
+ * gather, dyn-bottleneck), the element count n (compact) or the number of channel groups D
+ * (channel-skip).  Returns 0 for invalid arguments.
+ */
+size_t laud_workspace_size(int op, laud_fmap fx, const laud_bottleneck* p, int S_or_D);
+
+/*
+ * Spatial masker + index generation (Sec. 3.2 "Masker design"; App. B, operator fusion
+ * items 1-2).  For every patch:  logit = bias + sum_c w[c] * mean over the S x S patch of
+ * x[...,c]  (the one-channel form W_0 - W_1 of the two-logit masker), mask = logit > 0
+ * (strict; 0 and NaN are inactive), optionally AND-ed with a per-sample layer gate.  Then
+ * the ascending list of active flat patch indices and its length are produced.
+ *   x        [N,H,W,C] dtype                      in
+ *   w        [C] float32                          in
+ *   keep     [N] bytes or NULL: sample n's patches are all inactive when keep[n] == 0
+ *   mask     [N*Hp*Wp] bytes (0/1)                out
+ *   idx      [N*Hp*Wp] int32, first *count valid  out
+ *   count    [1] int32                            out
+ *   sample_offsets [N+1] int32 or NULL: number of active patches before sample n  out
+ *   logits   [N*Hp*Wp] float32 or NULL            out
+ */
+int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w, float bias,
+                  const uint8_t* keep, uint8_t* mask, int32_t* idx, int32_t* count,
+                  int32_t* sample_offsets, float* logits,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stable compaction of a byte mask (Sec. 3.1 layer gates; App. B item 2 for patch masks
+ * supplied from outside): idx = ascending positions i in [0,n) with keep[i] != 0,
+ * *count = their number.  idx has capacity n.  n == 0 writes *count = 0.
+ */
+int laud_layer_skip_compact(const uint8_t* keep, int n, int32_t* idx, int32_t* count,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stand-alone gather (Sec. 3.1, step 1 of the three-step schedule): for p < *count,
+ * out[p][dy][dx][:] = x[n][py*S - halo + dy][px*S - halo + dx][:] if that pixel is inside
+ * the image, else 0, with (n,py,px) decoded from idx[p]; halo is 0 or 1 (1 = the
+ * neighbours a 3x3 kernel needs).  out is [cap][S+2*halo][S+2*halo][C] dtype with
+ * cap >= *count (N*Hp*Wp always suffices); entries p >= *count are not written.
+ */
+int laud_gather_patches(const void* x, laud_fmap fx, int S, int halo,
+                        const int32_t* idx, const int32_t* count, void* out, void* stream);
+
+/*
+ * Spatially adaptive bottleneck (Fig. 2(b); Sec. 3.4; App. B items 2-3).  For every pixel of
+ * an active patch:  out = act(x + s3*conv1x1(h2;w3) + t3),  h2 = relu(s2*conv3x3(h1;w2) + t2),
+ * h1 = relu(s1*conv1x1(x;w1) + t1) evaluated from the true x on the patch and its one-pixel
+ * halo, with h1 := 0 outside the image (the padding is the 3x3's).  Pixels of inactive
+ * patches: out == x bit for bit.  act = ReLU iff p->relu_out.
+ *   idx/count  ascending active patch indices and their number (device), as produced by
+ *              laud_mask_gen or laud_layer_skip_compact; with S == H == W the indices are
+ *              sample ids and the call is layer skipping.
+ *   out        [N,H,W,C]; may be the same pointer as x (in place, the scatter-add of
+ *              App. B item 3); partial overlap is not allowed.
+ */
+int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                        const int32_t* idx, const int32_t* count, void* out,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Channel-skipping bottleneck (Fig. 2(c); Sec. 3.1-3.2).  cmask is [N][D] bytes; group g of
+ * sample n covers mid channels [g*G, (g+1)*G), G = c_mid / D.  The mask multiplies the input
+ * and the output of the 3x3 conv; dropped channels are never computed (the weight gather is
+ * fused into the convs).  out = act(x + s3*conv1x1(h2 masked; w3) + t3) on every pixel; with
+ * all groups dropped out = act(x + t3).  out may be the same pointer as x.
+ */
+int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                           const uint8_t* cmask, int D, void* out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAUD_H */

@@ -1,0 +1,9 @@
+"""MI355X-native dynamic residual bottleneck (LAUDNet hot path): HIP kernels behind a C ABI
+(include/laud.h, built into liblaud.so) and a thin ctypes binding.  Importing the package
+does not load the library; the first call does, and raises if it has not been built."""
+from . import inputs  # noqa: F401
+from .binding import (  # noqa: F401
+    BF16, F32, Bottleneck, Fmap, LaudError, abi_version, fmap_of, laud_channel_skip_conv,
+    laud_dyn_bottleneck, laud_gather_patches, laud_layer_skip_compact, laud_mask_gen, load,
+    make_bottleneck, status_string, workspace_size,
+)

@@ -1,0 +1,159 @@
+"""Thin ctypes binding of liblaud.so: argument marshalling only.
+
+Every function below has the name and the meaning of the C entry point declared in
+include/laud.h; tensors are torch CUDA tensors used purely as device memory, the
+stream is torch's current stream.  There is no CPU fallback: if the library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "liblaud.so")
+
+F32, BF16 = 0, 1
+OP_MASK_GEN, OP_COMPACT, OP_GATHER, OP_DYN_BOTTLENECK, OP_CHANNEL_SKIP = range(5)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
+           "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
+           "laud_channel_skip_conv"]
+
+
+class Fmap(C.Structure):
+    _fields_ = [("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("dtype", C.c_int32)]
+
+
+class Bottleneck(C.Structure):
+    _fields_ = [("c_in", C.c_int32), ("c_mid", C.c_int32), ("c_out", C.c_int32),
+                ("w1", C.c_void_p), ("w2", C.c_void_p), ("w3", C.c_void_p),
+                ("s1", C.c_void_p), ("t1", C.c_void_p), ("s2", C.c_void_p), ("t2", C.c_void_p),
+                ("s3", C.c_void_p), ("t3", C.c_void_p), ("relu_out", C.c_int32)]
+
+
+class LaudError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads liblaud.so (once).  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2308_15949_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+    lib.laud_status_string.restype = C.c_char_p
+    lib.laud_status_string.argtypes = [i32]
+    lib.laud_abi_version.restype = i32
+    lib.laud_abi_version.argtypes = []
+    lib.laud_workspace_size.restype = sz
+    lib.laud_workspace_size.argtypes = [i32, Fmap, C.POINTER(Bottleneck), i32]
+    lib.laud_mask_gen.restype = i32
+    lib.laud_mask_gen.argtypes = [vp, Fmap, i32, vp, C.c_float, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.laud_layer_skip_compact.restype = i32
+    lib.laud_layer_skip_compact.argtypes = [vp, i32, vp, vp, vp, sz, vp]
+    lib.laud_gather_patches.restype = i32
+    lib.laud_gather_patches.argtypes = [vp, Fmap, i32, i32, vp, vp, vp, vp]
+    lib.laud_dyn_bottleneck.restype = i32
+    lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
+    lib.laud_channel_skip_conv.restype = i32
+    lib.laud_channel_skip_conv.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, i32, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().laud_status_string(int(status)).decode()
+
+
+def abi_version() -> int:
+    return int(load().laud_abi_version())
+
+
+# ----- marshalling helpers ---------------------------------------------------------------
+def _ptr(t):
+    """Device (or raw integer) pointer of a tensor; None -> NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise LaudError(status, where)
+
+
+def fmap_of(x, dtype: int | None = None) -> Fmap:
+    """Fmap of an [N,H,W,C] tensor (float32 or bfloat16)."""
+    import torch
+    if dtype is None:
+        dtype = BF16 if x.dtype == torch.bfloat16 else F32
+    n, h, w, c = x.shape
+    return Fmap(int(n), int(h), int(w), int(c), int(dtype))
+
+
+def make_bottleneck(w1, w2, w3, s1, t1, s2, t2, s3, t3, relu_out: bool) -> Bottleneck:
+    """Bottleneck descriptor over device tensors w1 [m,Cin], w2 [m,3,3,m], w3 [Cout,m] and
+    float32 affine vectors.  The caller keeps the tensors alive."""
+    return Bottleneck(int(w1.shape[1]), int(w1.shape[0]), int(w3.shape[0]),
+                      w1.data_ptr(), w2.data_ptr(), w3.data_ptr(),
+                      s1.data_ptr(), t1.data_ptr(), s2.data_ptr(), t2.data_ptr(),
+                      s3.data_ptr(), t3.data_ptr(), 1 if relu_out else 0)
+
+
+def workspace_size(op: int, fx: Fmap, p: Bottleneck | None, s_or_d: int) -> int:
+    return int(load().laud_workspace_size(int(op), fx, C.byref(p) if p is not None else None, int(s_or_d)))
+
+
+def _ws_args(ws):
+    if ws is None:
+        return None, 0
+    return _ptr(ws), int(ws.numel() * ws.element_size())
+
+
+# ----- entry points (same names as the C ABI) ---------------------------------------------
+def laud_mask_gen(x, fx: Fmap, S: int, w, bias: float, keep, mask, idx, count, sample_offsets, logits, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_mask_gen(_ptr(x), fx, int(S), _ptr(w), float(bias), _ptr(keep), _ptr(mask), _ptr(idx),
+                                _ptr(count), _ptr(sample_offsets), _ptr(logits), wp, wb, _stream()),
+           "laud_mask_gen")
+
+
+def laud_layer_skip_compact(keep, n: int, idx, count, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_layer_skip_compact(_ptr(keep), int(n), _ptr(idx), _ptr(count), wp, wb, _stream()),
+           "laud_layer_skip_compact")
+
+
+def laud_gather_patches(x, fx: Fmap, S: int, halo: int, idx, count, out) -> None:
+    _check(load().laud_gather_patches(_ptr(x), fx, int(S), int(halo), _ptr(idx), _ptr(count), _ptr(out), _stream()),
+           "laud_gather_patches")
+
+
+def laud_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
+                                      wp, wb, _stream()), "laud_dyn_bottleneck")
+
+
+def laud_channel_skip_conv(x, fx: Fmap, p: Bottleneck, cmask, D: int, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_channel_skip_conv(_ptr(x), fx, C.byref(p), _ptr(cmask), int(D), _ptr(out),
+                                         wp, wb, _stream()), "laud_channel_skip_conv")

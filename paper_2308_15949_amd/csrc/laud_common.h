@@ -1,0 +1,76 @@
+// Shared host/device helpers of the gfx950 dynamic-bottleneck library (internal header).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "laud.h"
+
+namespace laud {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// ---- workspace carving: every sub-buffer starts on a 256-byte boundary ------------------
+__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- element types -----------------------------------------------------------------------
+// bf16 is stored as its 16-bit pattern; arithmetic is always float32.
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round-to-nearest-even, quiet NaN preserved.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename ET> struct elem;
+template <> struct elem<float> {
+  static constexpr int per16 = 4;  // elements per 16-byte chunk
+  __device__ static __forceinline__ float load(const float* p) { return *p; }
+  __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct elem<bf16_t> {
+  static constexpr int per16 = 8;
+  __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- wave-level primitives ---------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+// Number of set bits of a 64-bit ballot below the calling lane.
+__device__ __forceinline__ int ballot_prefix(unsigned long long b) {
+  return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// ---- host-side launch checking -----------------------------------------------------------
+inline int check_launch() { return hipGetLastError() == hipSuccess ? LAUD_OK : LAUD_ERR_HIP; }
+
+inline bool valid_fmap(const laud_fmap& f) {
+  return f.N > 0 && f.H > 0 && f.W > 0 && f.C > 0 && (f.dtype == LAUD_F32 || f.dtype == LAUD_BF16);
+}
+inline size_t elem_bytes(int dtype) { return dtype == LAUD_BF16 ? 2 : 4; }
+
+// Compaction works on blocks of this many mask bytes.
+constexpr int kCompactBlock = 4096;
+inline size_t compact_ws_bytes(long long n) {
+  long long nb = (n + kCompactBlock - 1) / kCompactBlock;
+  return align_up((size_t)(nb > 0 ? nb : 1) * sizeof(int32_t), 256);
+}
+
+// Launches the ordered compaction of `n` mask bytes on `stream` (see laud_compact.hip).
+int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int32_t* sample_offsets,
+                   int per_sample, int32_t* block_counts, hipStream_t stream);
+
+}  // namespace laud

@@ -1,0 +1,617 @@
+// The three convolutions of the dynamic bottleneck as gathered implicit GEMMs on gfx950 MFMA.
+//
+// One kernel template, k_gemm<MODE, ET, BM, BN>, computes a BM x BN output tile with four
+// waves (2 x 2) of 32x32 MFMA tiles; A (activations) and B (weights, [N][K] K-contiguous) are
+// staged through LDS in 128-byte K slices.  What differs per MODE is only where a row of A
+// comes from and where a row of the result goes:
+//
+//   CONV1  rows = pixels of the dilated active set (list of pixel ids): the gather is fused
+//          into the first 1x1 (Sec. 3.4 "Fusing gather and dynamic convolution"); result
+//          h1 = relu(s1*acc + t1) stored at the pixel's own position.
+//   CONV2  rows = (active patch, pixel in patch); the K loop runs over the nine taps, the A row
+//          of tap (ky,kx) is h1 at the shifted pixel, or zeros outside the image (App. B item 2:
+//          fetch by index, output patches stored densely); result h2 dense, patch-major.
+//   CONV3  rows = the dense h2 rows; epilogue reads the residual at the patch's position, adds,
+//          and stores at that position (Sec. 3.4 "Fusing scatter and add"; App. B item 3).
+//   CS1..3 the same three convs for channel skipping (Fig. 2(c)): one sample per blockIdx.y,
+//          output channels / reduction channels gathered through the sample's kept-group list,
+//          i.e. the weight gather is fused into the conv (Sec. 3.4).
+//
+// Accumulation is float32 (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32).
+#include "laud_common.h"
+
+#include <cstdio>
+#include <cstdlib>
+
+namespace laud {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5 };
+
+constexpr int kMaxGroups = 1024;  // channel-skip decisions per sample the kernels can hold in LDS
+
+struct GemmArgs {
+  const void* A;         // activations the rows are gathered from
+  const void* Wt;        // weights [Ncols][ldw]
+  const float* scale;    // per-output-channel affine
+  const float* shift;
+  void* Out;
+  const void* Res;       // residual (CONV3 / CS3); may alias Out
+  const int32_t* count;  // device: number of units (pixels for CONV1, patches for CONV2/3)
+  const int32_t* list;   // device: pixel ids (CONV1) or active patch ids (CONV2/3)
+  const uint8_t* cmask;  // CS: [N][D]
+  int K;                 // reduction length per tap (full width)
+  int ldw;               // weight row stride, elements
+  int Ncols;             // output channels (full width)
+  int H, W, S;
+  int lda;               // A row stride, elements
+  int ldo;               // Out/Res row stride, elements
+  int relu;
+  int D, G;              // CS: groups per sample, channels per group
+  int row_tiles, col_tiles;
+};
+
+// ---- one 16-byte fragment pair -> MFMA ------------------------------------------------------
+template <typename ET>
+__device__ __forceinline__ void mma16(f32x16& acc, const uint4& a, const uint4& b) {
+  if constexpr (sizeof(ET) == 2) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc,
+                                                  0, 0, 0);
+  } else {
+    // Four k-steps of the 32x32x2 fp32 MFMA; lane group l/32 holds k-slots {4h..4h+3} of this
+    // 8-wide K group for A and B alike, so the pairing of A and B elements is consistent.
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  }
+}
+
+template <typename ET>
+__device__ __forceinline__ uint4 gather_elems(const ET* w, const int* kgrp, int G, int k0, int kend) {
+  // Element-wise form of the kept-channel gather for group widths that do not fill a 16-byte chunk.
+  constexpr int EPC = elem<ET>::per16;
+  ET tmp[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) {
+    const int k = k0 + e;
+    tmp[e] = (k < kend) ? w[kgrp[k / G] * G + (k % G)] : (ET)0;
+  }
+  uint4 r;
+  __builtin_memcpy(&r, tmp, 16);
+  return r;
+}
+
+// Zeroes the elements of a 16-byte chunk from position `nvalid` on.
+template <typename ET>
+__device__ __forceinline__ uint4 mask_tail(uint4 v, int nvalid) {
+  constexpr int EPC = elem<ET>::per16;
+  ET tmp[EPC];
+  __builtin_memcpy(tmp, &v, 16);
+#pragma unroll
+  for (int e = 0; e < EPC; ++e)
+    if (e >= nvalid) tmp[e] = (ET)0;
+  __builtin_memcpy(&v, tmp, 16);
+  return v;
+}
+
+template <int MODE, typename ET, int BM, int BN>
+__global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
+  constexpr int EPC = elem<ET>::per16;   // elements per 16-byte chunk
+  constexpr int BKE = 8 * EPC;           // K elements per LDS slice (128 bytes per row)
+  constexpr int LSTR = 144;              // LDS row stride in bytes (128 + 16 pad)
+  constexpr int AR = BM / 32, BR = BN / 32;
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2);
+  constexpr bool CS = (MODE >= M_CS1);
+
+  __shared__ __align__(16) unsigned char sA[BM * LSTR];
+  __shared__ __align__(16) unsigned char sB[BN * LSTR];
+  __shared__ int s_row[BM];
+  __shared__ int s_kgrp[CS ? kMaxGroups : 1];
+  __shared__ int s_nkept;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int HW = a.H * a.W, SS = a.S * a.S;
+  const int Hp = a.H / a.S, Wp = a.W / a.S;
+  const ET* __restrict__ Ap = (const ET*)a.A;
+  const ET* __restrict__ Wp_ = (const ET*)a.Wt;
+
+  // ---- which tile ---------------------------------------------------------------------------
+  int rt, ct, sample = 0, M;
+  if constexpr (!CS) {
+    // XCD-aware decode: consecutive workgroup ids go round-robin over the 8 XCDs, so the column
+    // tiles of one row tile (same A rows) are given to the same XCD, one after the other.
+    const int L = blockIdx.x, xcd = L & 7, s = L >> 3;
+    rt = (s / a.col_tiles) * 8 + xcd;
+    ct = s % a.col_tiles;
+    if (rt >= a.row_tiles) return;
+    const int cnt = *a.count;
+    M = (MODE == M_CONV1) ? cnt : cnt * SS;
+  } else {
+    rt = blockIdx.x % a.row_tiles;
+    ct = blockIdx.x / a.row_tiles;
+    sample = blockIdx.y;
+    M = HW;
+  }
+  const int row0 = rt * BM, col0 = ct * BN;
+  if (row0 >= M) return;
+
+  // ---- channel skipping: kept-group list of this sample (ballot + prefix, one wave) ----------
+  int ncols = a.Ncols, keff = a.K;
+  if constexpr (CS) {
+    if (wave == 0) {
+      int base = 0;
+      for (int g0 = 0; g0 < a.D; g0 += kWave) {
+        const int g = g0 + lane;
+        const bool f = g < a.D && a.cmask[(size_t)sample * a.D + g] != 0;
+        const unsigned long long b = __ballot(f);
+        if (f) s_kgrp[base + ballot_prefix(b)] = g;
+        base += __popcll(b);
+      }
+      if (lane == 0) s_nkept = base;
+    }
+    __syncthreads();
+    const int kw = s_nkept * a.G;
+    if (MODE != M_CS3) ncols = kw;
+    if (MODE != M_CS1) keff = kw;
+    if (col0 >= ncols) return;
+  }
+
+  // ---- row descriptors ------------------------------------------------------------------------
+  const int cc = tid & 7;    // 16-byte chunk within the 128-byte K slice
+  const int lr = tid >> 3;   // 0..31: first row this thread loads
+  size_t abase[AR];          // A row offset in elements (modes without taps)
+  int ry[AR], rx[AR], rn[AR];  // pixel coordinates / sample pixel base (modes with taps)
+  bool rvalid[AR];
+#pragma unroll
+  for (int i = 0; i < AR; ++i) {
+    const int rho = row0 + lr + 32 * i;
+    rvalid[i] = rho < M;
+    abase[i] = 0; ry[i] = -4; rx[i] = -4; rn[i] = 0;
+    if (rvalid[i]) {
+      if constexpr (MODE == M_CONV1) {
+        abase[i] = (size_t)a.list[rho] * a.lda;
+      } else if constexpr (MODE == M_CONV3) {
+        abase[i] = (size_t)rho * a.lda;
+      } else if constexpr (MODE == M_CONV2) {
+        const int p = rho / SS, j = rho - p * SS;
+        const int q = a.list[p];
+        const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
+        const int py = r2 / Wp, px = r2 - py * Wp;
+        ry[i] = py * a.S + j / a.S;
+        rx[i] = px * a.S + j % a.S;
+        rn[i] = n * HW;
+      } else if constexpr (MODE == M_CS2) {
+        ry[i] = rho / a.W;
+        rx[i] = rho - ry[i] * a.W;
+        rn[i] = sample * HW;
+      } else {  // CS1, CS3
+        abase[i] = ((size_t)sample * HW + rho) * a.lda;
+      }
+    }
+  }
+  if (tid < BM) {
+    const int rho = row0 + tid;
+    int o = -1;
+    if (rho < M) {
+      if constexpr (MODE == M_CONV1) {
+        o = a.list[rho];
+      } else if constexpr (MODE == M_CONV2) {
+        o = rho;
+      } else if constexpr (MODE == M_CONV3) {
+        const int p = rho / SS, j = rho - p * SS;
+        const int q = a.list[p];
+        const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
+        const int py = r2 / Wp, px = r2 - py * Wp;
+        o = n * HW + (py * a.S + j / a.S) * a.W + (px * a.S + j % a.S);
+      } else {
+        o = sample * HW + rho;
+      }
+    }
+    s_row[tid] = o;
+  }
+
+  // ---- weight-row descriptors -----------------------------------------------------------------
+  size_t wbase[BR];
+  bool cvalid[BR];
+#pragma unroll
+  for (int i = 0; i < BR; ++i) {
+    const int c = col0 + lr + 32 * i;
+    cvalid[i] = c < ncols;
+    int wr = c;
+    if constexpr (MODE == M_CS1 || MODE == M_CS2) {
+      if (cvalid[i]) wr = s_kgrp[c / a.G] * a.G + (c % a.G);
+    }
+    wbase[i] = cvalid[i] ? (size_t)wr * a.ldw : 0;
+  }
+
+  const int kchunks = (keff + BKE - 1) / BKE;
+  const int KT = (TAPS ? 9 : 1) * kchunks;
+  const bool kvec = (a.G % EPC) == 0;  // kept-channel gather can use 16-byte loads
+
+  uint4 ra[AR], rb[BR];
+  auto load_slice = [&](int it) {
+    int tap = 0, kc = it;
+    if constexpr (TAPS) { tap = it / kchunks; kc = it - tap * kchunks; }
+    const int ke = kc * BKE + cc * EPC;  // first (compact) K element of this thread's chunk
+    const bool kv = ke < keff;
+    const int ky = tap / 3 - 1, kx = tap % 3 - 1;
+#pragma unroll
+    for (int i = 0; i < AR; ++i) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if constexpr (TAPS) {
+        const int yy = ry[i] + ky, xx = rx[i] + kx;
+        if (kv && rvalid[i] && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
+          v = *reinterpret_cast<const uint4*>(Ap + ((size_t)(rn[i] + yy * a.W + xx)) * a.lda + ke);
+      } else {
+        if (kv && rvalid[i]) v = *reinterpret_cast<const uint4*>(Ap + abase[i] + ke);
+      }
+      if constexpr (MODE == M_CS2 || MODE == M_CS3) {
+        // compact rows are valid up to keff only; what lies beyond in the scratch buffer is undefined
+        if (!kvec && ke + EPC > keff) v = mask_tail<ET>(v, keff - ke);
+      }
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < BR; ++i) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (kv && cvalid[i]) {
+        const ET* wrow = Wp_ + wbase[i] + (size_t)tap * a.K;
+        if constexpr (MODE == M_CS2 || MODE == M_CS3) {
+          if (kvec) v = *reinterpret_cast<const uint4*>(wrow + s_kgrp[ke / a.G] * a.G + (ke % a.G));
+          else v = gather_elems<ET>(wrow, s_kgrp, a.G, ke, keff);
+        } else {
+          v = *reinterpret_cast<const uint4*>(wrow + ke);
+        }
+      }
+      rb[i] = v;
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  if (KT > 0) load_slice(0);
+  for (int it = 0; it < KT; ++it) {
+#pragma unroll
+    for (int i = 0; i < AR; ++i) *reinterpret_cast<uint4*>(sA + (lr + 32 * i) * LSTR + cc * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(sB + (lr + 32 * i) * LSTR + cc * 16) = rb[i];
+    __syncthreads();
+    if (it + 1 < KT) load_slice(it + 1);  // global loads fly while the MFMAs run
+    const unsigned char* pa = sA + (wm * (BM / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
+    const unsigned char* pb = sB + (wn * (BN / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg) {
+      uint4 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const uint4*>(pa + i * 32 * LSTR + kg * 32);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const uint4*>(pb + j * 32 * LSTR + kg * 32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) mma16<ET>(acc[i][j], fa[i], fb[j]);
+    }
+    __syncthreads();
+  }
+  if (KT == 0) __syncthreads();  // s_row must be visible before the epilogue
+
+  // ---- epilogue ---------------------------------------------------------------------------------
+  // 32x32 accumulator layout: lane l holds column l%32, rows 8*(e/4) + 4*(l/32) + e%4.
+  ET* Op = (ET*)a.Out;
+  const ET* Rp = (const ET*)a.Res;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
+    if (col >= ncols) continue;
+    int ch = col;
+    if constexpr (MODE == M_CS1 || MODE == M_CS2) ch = s_kgrp[col / a.G] * a.G + (col % a.G);
+    const float sc = a.scale[ch], sh = a.shift[ch];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const int orow = s_row[rl];
+        if (orow < 0) continue;
+        const size_t off = (size_t)orow * a.ldo + col;
+        float v = acc[i][j][e] * sc + sh;
+        if constexpr (MODE == M_CONV3 || MODE == M_CS3) {
+          v += elem<ET>::load(Rp + off);
+          if (a.relu) v = fmaxf(v, 0.f);
+        } else {
+          v = fmaxf(v, 0.f);
+        }
+        elem<ET>::store(Op + off, v);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dilated active set: which pixels need conv1 (the patch pixels and their one-pixel halo)
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int lower_bound_dev(const int32_t* v, int n, int key) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (v[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// One block per sample.  WRITE = false: count the sample's needed pixels; WRITE = true: write their
+// ids in ascending order at the exclusive prefix of the counts (ordered, no atomics) and, in the
+// last block, the total.  The sample's patch mask is rebuilt in LDS from the sorted index list.
+template <bool WRITE>
+__global__ __launch_bounds__(256) void k_need(const int32_t* __restrict__ idx, const int32_t* __restrict__ count,
+                                              int N, int H, int W, int S, int32_t* __restrict__ need_counts,
+                                              int32_t* __restrict__ pix, int32_t* __restrict__ total) {
+  extern __shared__ unsigned char s_pm[];  // [Hp*Wp] patch mask of this sample
+  __shared__ int wcnt[4], woff[4], s_tot, s_base;
+  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Hp = H / S, Wp = W / S, pps = Hp * Wp, HW = H * W;
+  const int cnt = *count;
+  for (int i = tid; i < pps; i += 256) s_pm[i] = 0;
+  if (WRITE && tid < 64) {
+    int part = 0;
+    for (int b = tid; b < n; b += 64) part += need_counts[b];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+    if (tid == 0) s_base = part;
+  }
+  __syncthreads();
+  const int lo = lower_bound_dev(idx, cnt, n * pps), hi = lower_bound_dev(idx, cnt, (n + 1) * pps);
+  for (int i = lo + tid; i < hi; i += 256) s_pm[idx[i] - n * pps] = 1;
+  __syncthreads();
+  int running = WRITE ? s_base : 0;
+  for (int p0 = 0; p0 < HW; p0 += 256) {
+    const int pp = p0 + tid;
+    bool need = false;
+    if (pp < HW) {
+      const int y = pp / W, x = pp - y * W;
+      const int py0 = max(y - 1, 0) / S, py1 = min(y + 1, H - 1) / S;
+      const int px0 = max(x - 1, 0) / S, px1 = min(x + 1, W - 1) / S;
+      for (int py = py0; py <= py1; ++py)
+        for (int px = px0; px <= px1; ++px) need |= s_pm[py * Wp + px] != 0;
+    }
+    const unsigned long long b = __ballot(need);
+    if (lane == 0) wcnt[wave] = __popcll(b);
+    __syncthreads();
+    if (tid == 0) {
+      int t = 0;
+      for (int w = 0; w < 4; ++w) { woff[w] = t; t += wcnt[w]; }
+      s_tot = t;
+    }
+    __syncthreads();
+    if (WRITE && need) pix[running + woff[wave] + ballot_prefix(b)] = n * HW + pp;
+    running += s_tot;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    if (!WRITE) need_counts[n] = running;
+    else if (n == N - 1) *total = running;
+  }
+}
+
+// Out-of-place call: pixels of inactive patches are copied bit for bit.  One block per patch.
+__global__ __launch_bounds__(256) void k_copy_inactive(const uint4* __restrict__ x, uint4* __restrict__ out, int H,
+                                                       int W, int S, int cpp, const int32_t* __restrict__ idx,
+                                                       const int32_t* __restrict__ count) {
+  const int q = blockIdx.x, cnt = *count;
+  const int pos = lower_bound_dev(idx, cnt, q);
+  if (pos < cnt && idx[pos] == q) return;  // active: the conv3 epilogue writes it
+  const int Hp = H / S, Wp = W / S;
+  const int n = q / (Hp * Wp), r = q - n * (Hp * Wp);
+  const int py = r / Wp, px = r - py * Wp;
+  const int total = S * S * cpp;
+  for (int c = threadIdx.x; c < total; c += 256) {
+    const int j = c / cpp, cv = c - j * cpp;
+    const size_t off = (((size_t)n * H + (py * S + j / S)) * W + (px * S + j % S)) * cpp + cv;
+    out[off] = x[off];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct Tile { int bm, bn; };
+
+// Tile choice.  LAUD_TILE=BMxBN (64x64, 64x128, 128x128) overrides it for tuning runs.
+static Tile pick_tile(int ncols) {
+  static int env_bm = -1, env_bn = -1;
+  if (env_bm < 0) {
+    env_bm = 0; env_bn = 0;
+    if (const char* e = std::getenv("LAUD_TILE")) {
+      int bm = 0, bn = 0;
+      if (std::sscanf(e, "%dx%d", &bm, &bn) == 2 &&
+          ((bm == 64 && bn == 64) || (bm == 64 && bn == 128) || (bm == 128 && bn == 128))) {
+        env_bm = bm; env_bn = bn;
+      }
+    }
+  }
+  if (env_bm > 0) return {env_bm, env_bn};
+  return {64, ncols >= 128 ? 128 : 64};
+}
+
+template <int MODE, typename ET, int BM, int BN>
+static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream_t st) {
+  constexpr bool CS = (MODE >= M_CS1);
+  a.row_tiles = (int)((cap_rows + BM - 1) / BM);
+  a.col_tiles = (a.Ncols + BN - 1) / BN;
+  dim3 grid;
+  if (!CS) grid = dim3((unsigned)(((a.row_tiles + 7) / 8) * 8 * a.col_tiles));
+  else grid = dim3((unsigned)(a.row_tiles * a.col_tiles), (unsigned)nsamples);
+  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN>), grid, dim3(256), 0, st, a);
+  return check_launch();
+}
+
+template <int MODE, typename ET>
+static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
+  const Tile t = pick_tile(a.Ncols);
+  if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128>(a, cap_rows, nsamples, st);
+  if (t.bn == 128) return launch_gemm_t<MODE, ET, 64, 128>(a, cap_rows, nsamples, st);
+  return launch_gemm_t<MODE, ET, 64, 64>(a, cap_rows, nsamples, st);
+}
+
+template <int MODE>
+static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
+  return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
+                            : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
+}
+
+static int validate_block(const void* x, const laud_fmap& fx, const laud_bottleneck* p, const void* out) {
+  if (!x || !out || !p || !valid_fmap(fx)) return LAUD_ERR_INVALID_ARG;
+  if (!p->w1 || !p->w2 || !p->w3 || !p->s1 || !p->t1 || !p->s2 || !p->t2 || !p->s3 || !p->t3)
+    return LAUD_ERR_INVALID_ARG;
+  if (p->c_in <= 0 || p->c_mid <= 0 || p->c_out <= 0 || p->c_in != fx.C) return LAUD_ERR_INVALID_ARG;
+  if (p->c_out != p->c_in) return LAUD_ERR_UNSUPPORTED;
+  if (p->c_in % 8 || p->c_mid % 8) return LAUD_ERR_UNSUPPORTED;
+  if ((long long)fx.N * fx.H * fx.W > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (x != out) {  // partial overlap is not allowed
+    const size_t bytes = (size_t)fx.N * fx.H * fx.W * fx.C * elem_bytes(fx.dtype);
+    const char *a = (const char*)x, *b = (const char*)out;
+    if ((a < b && a + bytes > b) || (b < a && b + bytes > a)) return LAUD_ERR_INVALID_ARG;
+  }
+  return LAUD_OK;
+}
+
+struct DynWs { size_t need_counts, total, pix, h1, h2, bytes; };
+static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
+  const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
+  DynWs w;
+  size_t o = 0;
+  w.need_counts = o; o += align_up((size_t)fx.N * 4, 256);
+  w.total = o;       o += 256;
+  w.pix = o;         o += align_up(npix * 4, 256);
+  w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
+  w.h2 = o;          o += align_up(npix * c_mid * eb, 256);
+  w.bytes = o;
+  return w;
+}
+
+struct CsWs { size_t h1, h2, bytes; };
+static CsWs cs_ws_layout(const laud_fmap& fx, int c_mid) {
+  const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
+  CsWs w;
+  w.h1 = 0;
+  w.h2 = align_up(npix * c_mid * eb, 256);
+  w.bytes = 2 * w.h2;
+  return w;
+}
+
+}  // namespace laud
+
+using namespace laud;
+
+extern "C" size_t laud_workspace_size(int op, laud_fmap fx, const laud_bottleneck* p, int S_or_D) {
+  switch (op) {
+    case LAUD_OP_MASK_GEN: {
+      if (!valid_fmap(fx) || S_or_D <= 0 || fx.H % S_or_D || fx.W % S_or_D) return 0;
+      return compact_ws_bytes((long long)fx.N * (fx.H / S_or_D) * (fx.W / S_or_D));
+    }
+    case LAUD_OP_COMPACT:
+      return S_or_D >= 0 ? compact_ws_bytes(S_or_D) : 0;
+    case LAUD_OP_GATHER:
+      return 0;
+    case LAUD_OP_DYN_BOTTLENECK:
+      if (!valid_fmap(fx) || !p || p->c_mid <= 0) return 0;
+      return dyn_ws_layout(fx, p->c_mid).bytes;
+    case LAUD_OP_CHANNEL_SKIP:
+      if (!valid_fmap(fx) || !p || p->c_mid <= 0) return 0;
+      return cs_ws_layout(fx, p->c_mid).bytes;
+    default:
+      return 0;
+  }
+}
+
+extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S, const int32_t* idx,
+                                   const int32_t* count, void* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_block(x, fx, p, out);
+  if (rc != LAUD_OK) return rc;
+  if (!idx || !count || S <= 0 || fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
+  const int Hp = fx.H / S, Wp = fx.W / S;
+  if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
+  const DynWs L = dyn_ws_layout(fx, p->c_mid);
+  if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = (char*)ws;
+  int32_t* need_counts = (int32_t*)(wsb + L.need_counts);
+  int32_t* total = (int32_t*)(wsb + L.total);
+  int32_t* pix = (int32_t*)(wsb + L.pix);
+  void* h1 = wsb + L.h1;
+  void* h2 = wsb + L.h2;
+  const long long npix = (long long)fx.N * fx.H * fx.W;
+  const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+
+  if (x != out) {
+    hipLaunchKernelGGL(k_copy_inactive, dim3((unsigned)(fx.N * Hp * Wp)), dim3(256), 0, st, (const uint4*)x,
+                       (uint4*)out, fx.H, fx.W, S, cpp, idx, count);
+    if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  }
+  const size_t pm_bytes = align_up((size_t)Hp * Wp, 16);
+  hipLaunchKernelGGL((k_need<false>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
+                     need_counts, pix, total);
+  hipLaunchKernelGGL((k_need<true>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
+                     need_counts, pix, total);
+  if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.cmask = nullptr;
+  // conv1: gathered 1x1 over the dilated active set -> h1 at pixel positions
+  a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
+  a.count = total; a.list = pix; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
+  a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
+  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
+  a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
+  a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
+  a.lda = p->c_mid; a.ldo = p->c_mid;
+  if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  // conv3: 1x1 on dense h2 with the scatter-add epilogue
+  a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
+  a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
+  a.relu = p->relu_out ? 1 : 0;
+  return launch_gemm<M_CONV3>(fx.dtype, a, npix, 1, st);
+}
+
+extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p, const uint8_t* cmask,
+                                      int D, void* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_block(x, fx, p, out);
+  if (rc != LAUD_OK) return rc;
+  if (!cmask || D <= 0 || p->c_mid % D) return LAUD_ERR_INVALID_ARG;
+  if (D > kMaxGroups || fx.N > 65535) return LAUD_ERR_UNSUPPORTED;
+  const CsWs L = cs_ws_layout(fx, p->c_mid);
+  if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  void* h1 = (char*)ws + L.h1;
+  void* h2 = (char*)ws + L.h2;
+  const long long hw = (long long)fx.H * fx.W;
+
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = 1; a.D = D; a.G = p->c_mid / D; a.cmask = cmask;
+  a.count = nullptr; a.list = nullptr;
+  // conv1 with the kept output kernels only -> compact h1
+  a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
+  a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid; a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
+  if ((rc = launch_gemm<M_CS1>(fx.dtype, a, hw, fx.N, st)) != LAUD_OK) return rc;
+  // conv2 with kept input and output kernels -> compact h2
+  a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
+  a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid; a.lda = p->c_mid; a.ldo = p->c_mid;
+  if ((rc = launch_gemm<M_CS2>(fx.dtype, a, hw, fx.N, st)) != LAUD_OK) return rc;
+  // conv3 with the kept input kernels, residual add on every pixel
+  a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
+  a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
+  a.relu = p->relu_out ? 1 : 0;
+  return launch_gemm<M_CS3>(fx.dtype, a, hw, fx.N, st);
+}

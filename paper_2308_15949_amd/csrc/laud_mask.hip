@@ -1,0 +1,259 @@
+// Spatial masker, ordered index generation and stand-alone gather for gfx950.
+//
+//   k_mask_logits   Sec. 3.2 "Masker design" + App. B item 1: pooled one-channel masker,
+//                   threshold at 0; HBM-bound (reads x once, 16-byte loads).
+//   k_block_counts / k_compact
+//                   App. B item 2: the masker emits the ascending list of active patch
+//                   indices; wave64 ballot + mbcnt prefix inside a wave, LDS scan across
+//                   the 16 waves of a block, per-block counts for the cross-block base.
+//                   No atomics: the order is the ascending flat index, bit-exact.
+//   k_gather        Sec. 3.1 step 1: copy of active patches (+1 halo) to a dense buffer.
+#include "laud_common.h"
+
+namespace laud {
+
+// ------------------------------------------------------------------------------------------
+// ordered compaction
+// ------------------------------------------------------------------------------------------
+constexpr int kCompactThreads = 1024;                            // 16 waves
+constexpr int kCompactChunks = kCompactBlock / kCompactThreads;  // 4 sub-chunks per block
+
+__global__ __launch_bounds__(kCompactThreads) void k_block_counts(const uint8_t* __restrict__ mask, int n,
+                                                                  int32_t* __restrict__ block_counts) {
+  __shared__ int wcnt[kCompactThreads / kWave];
+  const int base = blockIdx.x * kCompactBlock;
+  int c = 0;
+#pragma unroll
+  for (int k = 0; k < kCompactChunks; ++k) {
+    int i = base + k * kCompactThreads + (int)threadIdx.x;
+    bool f = (i < n) && mask[i] != 0;
+    c += __popcll(__ballot(f));  // identical in every lane of the wave
+  }
+  if (lane_id() == 0) wcnt[threadIdx.x / kWave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kCompactThreads / kWave; ++w) t += wcnt[w];
+    block_counts[blockIdx.x] = t;
+  }
+}
+
+// Each block recomputes its base as the sum of the counts of the blocks before it (a few
+// hundred values at most), then writes its own indices in ascending order.
+__global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __restrict__ mask, int n,
+                                                             int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                             int32_t* __restrict__ sample_offsets, int per_sample,
+                                                             const int32_t* __restrict__ block_counts, int nblocks) {
+  __shared__ int wsum[kCompactThreads / kWave];
+  __shared__ int woff[kCompactThreads / kWave];
+  __shared__ int s_base;
+  const int wave = threadIdx.x / kWave, lane = lane_id();
+
+  // base = sum of block_counts[0 .. blockIdx.x)
+  int part = 0;
+  for (int b = threadIdx.x; b < (int)blockIdx.x; b += kCompactThreads) part += block_counts[b];
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+  if (lane == 0) wsum[wave] = part;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kCompactThreads / kWave; ++w) t += wsum[w];
+    s_base = t;
+  }
+  __syncthreads();
+  int running = s_base;
+
+  const int base = blockIdx.x * kCompactBlock;
+  for (int k = 0; k < kCompactChunks; ++k) {
+    const int i = base + k * kCompactThreads + (int)threadIdx.x;
+    const bool f = (i < n) && mask[i] != 0;
+    const unsigned long long b = __ballot(f);
+    const int lp = ballot_prefix(b);
+    if (lane == 0) wsum[wave] = __popcll(b);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
+      wsum[0] = t;  // chunk total (wsum[0] already consumed above)
+    }
+    __syncthreads();
+    const int pos = running + woff[wave] + lp;  // number of set entries before i
+    if (f) idx[pos] = i;
+    if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos;
+    running += wsum[0];
+    __syncthreads();
+  }
+  if ((int)blockIdx.x == nblocks - 1 && threadIdx.x == 0) {
+    *count = running;
+    if (sample_offsets) sample_offsets[n / per_sample] = running;
+  }
+}
+
+__global__ void k_write_zero_count(int32_t* count, int32_t* sample_offsets) {
+  *count = 0;
+  if (sample_offsets) sample_offsets[0] = 0;
+}
+
+int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int32_t* sample_offsets,
+                   int per_sample, int32_t* block_counts, hipStream_t stream) {
+  if (n == 0) {
+    hipLaunchKernelGGL(k_write_zero_count, dim3(1), dim3(1), 0, stream, count, sample_offsets);
+    return check_launch();
+  }
+  const int nb = (n + kCompactBlock - 1) / kCompactBlock;
+  if (nb > 1) {
+    hipLaunchKernelGGL(k_block_counts, dim3(nb - 1), dim3(kCompactThreads), 0, stream, mask, n, block_counts);
+    if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  }
+  hipLaunchKernelGGL(k_compact, dim3(nb), dim3(kCompactThreads), 0, stream, mask, n, idx, count, sample_offsets,
+                     per_sample > 0 ? per_sample : 1, block_counts, nb);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------
+// masker logits + threshold
+// ------------------------------------------------------------------------------------------
+// One "team" (a wave, or the whole 256-thread block for big patches) per patch.  The team
+// walks the S*S pixel rows of the patch in 16-byte chunks; float32 accumulation.
+template <typename ET, int TEAM>
+__global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, int N, int H, int W, int C, int S,
+                                                     const float* __restrict__ w, float bias,
+                                                     const uint8_t* __restrict__ keep, uint8_t* __restrict__ mask,
+                                                     float* __restrict__ logits) {
+  constexpr int EPC = elem<ET>::per16;
+  constexpr int TEAMS = 256 / TEAM;
+  __shared__ float red[256 / kWave];
+  const int Hp = H / S, Wp = W / S;
+  const int npatch = N * Hp * Wp;
+  const int team = threadIdx.x / TEAM, tl = threadIdx.x % TEAM;
+  const int q = blockIdx.x * TEAMS + team;
+  const bool live = q < npatch;  // uniform per team
+  float acc = 0.f;
+  int n = 0;
+  if (live) {
+    n = q / (Hp * Wp);
+    const int r = q - n * (Hp * Wp);
+    const int py = r / Wp, px = r - py * Wp;
+    const int cpr = C / EPC;          // chunks per pixel row
+    const int total = S * S * cpr;    // chunks per patch
+    for (int c = tl; c < total; c += TEAM) {
+      const int j = c / cpr, cv = c - j * cpr;
+      const int dy = j / S, dx = j - dy * S;
+      const size_t pix = ((size_t)n * H + (py * S + dy)) * W + (px * S + dx);
+      const uint4 raw = *reinterpret_cast<const uint4*>(x + pix * C + (size_t)cv * EPC);
+      const float4* wp = reinterpret_cast<const float4*>(w + cv * EPC);
+      if constexpr (EPC == 4) {
+        const float4 wv = wp[0];
+        acc += __uint_as_float(raw.x) * wv.x + __uint_as_float(raw.y) * wv.y + __uint_as_float(raw.z) * wv.z +
+               __uint_as_float(raw.w) * wv.w;
+      } else {
+        const float4 w0 = wp[0], w1 = wp[1];
+        acc += __uint_as_float(raw.x << 16) * w0.x + __uint_as_float(raw.x & 0xffff0000u) * w0.y +
+               __uint_as_float(raw.y << 16) * w0.z + __uint_as_float(raw.y & 0xffff0000u) * w0.w +
+               __uint_as_float(raw.z << 16) * w1.x + __uint_as_float(raw.z & 0xffff0000u) * w1.y +
+               __uint_as_float(raw.w << 16) * w1.z + __uint_as_float(raw.w & 0xffff0000u) * w1.w;
+      }
+    }
+  }
+  acc = wave_sum(acc);
+  if constexpr (TEAM > kWave) {
+    if (lane_id() == 0) red[threadIdx.x / kWave] = acc;
+    __syncthreads();
+    acc = 0.f;
+    for (int k = 0; k < 256 / kWave; ++k) acc += red[k];
+  }
+  if (live && tl == 0) {
+    const float logit = acc / (float)(S * S) + bias;
+    bool on = logit > 0.f;  // false for NaN
+    if (keep && keep[n] == 0) on = false;
+    mask[q] = on ? 1 : 0;
+    if (logits) logits[q] = logit;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// stand-alone gather
+// ------------------------------------------------------------------------------------------
+// One wave per (patch, dy, dx) slot of the gathered buffer; 16-byte copies, zero fill outside.
+__global__ __launch_bounds__(256) void k_gather(const uint4* __restrict__ x, int H, int W, int S, int halo,
+                                                int chunks_per_pixel, const int32_t* __restrict__ idx,
+                                                const int32_t* __restrict__ count, uint4* __restrict__ out,
+                                                long long cap_slots) {
+  const int E = S + 2 * halo;
+  const int Hp = H / S, Wp = W / S;
+  const long long slot = (long long)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+  if (slot >= cap_slots) return;
+  const int p = (int)(slot / (E * E));
+  if (p >= *count) return;
+  const int e = (int)(slot - (long long)p * (E * E));
+  const int dy = e / E, dx = e - dy * E;
+  const int q = idx[p];
+  const int n = q / (Hp * Wp);
+  const int r = q - n * (Hp * Wp);
+  const int py = r / Wp, px = r - py * Wp;
+  const int yy = py * S - halo + dy, xx = px * S - halo + dx;
+  const bool inside = yy >= 0 && yy < H && xx >= 0 && xx < W;
+  uint4* dst = out + (size_t)slot * chunks_per_pixel;
+  const uint4* src = x + (((size_t)n * H + (inside ? yy : 0)) * W + (inside ? xx : 0)) * chunks_per_pixel;
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+  for (int c = lane_id(); c < chunks_per_pixel; c += kWave) dst[c] = inside ? src[c] : zero;
+}
+
+}  // namespace laud
+
+using namespace laud;
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" int laud_layer_skip_compact(const uint8_t* keep, int n, int32_t* idx, int32_t* count, void* ws,
+                                       size_t ws_bytes, void* stream) {
+  if (n < 0 || !count || (n > 0 && (!keep || !idx))) return LAUD_ERR_INVALID_ARG;
+  if (n > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(n))) return LAUD_ERR_WORKSPACE;
+  return launch_compact(keep, n, idx, count, nullptr, 1, (int32_t*)ws, (hipStream_t)stream);
+}
+
+extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w, float bias, const uint8_t* keep,
+                             uint8_t* mask, int32_t* idx, int32_t* count, int32_t* sample_offsets, float* logits,
+                             void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !w || !mask || !idx || !count || !valid_fmap(fx) || S <= 0) return LAUD_ERR_INVALID_ARG;
+  if (fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
+  if (fx.C % 8) return LAUD_ERR_UNSUPPORTED;
+  const long long npatch = (long long)fx.N * (fx.H / S) * (fx.W / S);
+  if (npatch > 0x7fffffffLL || (long long)fx.N * fx.H * fx.W > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
+  if (npatch > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(npatch))) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t patch_bytes = (size_t)S * S * fx.C * elem_bytes(fx.dtype);
+  const bool big = patch_bytes >= 32768;  // a whole block per patch
+  const int teams = big ? 1 : 256 / kWave;
+  const unsigned grid = (unsigned)((npatch + teams - 1) / teams);
+#define LAUD_LAUNCH_MASK(ET, TEAM)                                                                            \
+  hipLaunchKernelGGL((k_mask_logits<ET, TEAM>), dim3(grid), dim3(256), 0, st, (const ET*)x, fx.N, fx.H, fx.W, \
+                     fx.C, S, w, bias, keep, mask, logits)
+  if (fx.dtype == LAUD_BF16) {
+    if (big) LAUD_LAUNCH_MASK(bf16_t, 256); else LAUD_LAUNCH_MASK(bf16_t, 64);
+  } else {
+    if (big) LAUD_LAUNCH_MASK(float, 256); else LAUD_LAUNCH_MASK(float, 64);
+  }
+#undef LAUD_LAUNCH_MASK
+  if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  return launch_compact(mask, (int)npatch, idx, count, sample_offsets, (fx.H / S) * (fx.W / S), (int32_t*)ws, st);
+}
+
+extern "C" int laud_gather_patches(const void* x, laud_fmap fx, int S, int halo, const int32_t* idx,
+                                   const int32_t* count, void* out, void* stream) {
+  if (!x || !idx || !count || !out || !valid_fmap(fx) || S <= 0 || halo < 0 || halo > 1) return LAUD_ERR_INVALID_ARG;
+  if (fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
+  if (fx.C % 8) return LAUD_ERR_UNSUPPORTED;
+  const long long npatch = (long long)fx.N * (fx.H / S) * (fx.W / S);
+  if (npatch > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
+  const int E = S + 2 * halo;
+  const long long slots = npatch * E * E;
+  const long long blocks = (slots + 3) / 4;
+  if (blocks > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
+  const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+  hipLaunchKernelGGL(k_gather, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)x, fx.H, fx.W,
+                     S, halo, cpp, idx, count, (uint4*)out, slots);
+  return check_launch();
+}

@@ -1,0 +1,160 @@
+"""CPU-only checks: the C-ABI library loads and exports what include/laud.h declares, argument
+validation returns the documented codes before anything is launched, and the seeded input
+generators behave (bf16 rounding against torch's conversion, bias placement, mask ratios)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2308_15949_amd as L
+from paper_2308_15949_amd import binding as B
+from paper_2308_15949_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2308_15949_amd import build
+        build.build(verbose=False)
+    return L.load()
+
+
+def test_header_symbols_are_exported(lib):
+    with open(os.path.join(ROOT, "include", "laud.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = sorted(set(re.findall(r"\b(laud_[a-z_]+)\s*\(", text)))
+    assert declared == sorted(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert L.abi_version() == 1
+    assert L.status_string(0) == "LAUD_OK"
+    for code in (-1, -2, -3, -4):
+        assert L.status_string(code).startswith("LAUD_ERR_")
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(B.Fmap) == 20
+    # 3 ints (+4 pad), 9 pointers, 1 int (+4 pad)
+    assert C.sizeof(B.Bottleneck) == 16 + 72 + 8
+
+
+FAKE = 0x10000  # never dereferenced: validation happens on the host before any launch
+
+
+def _bn(c_in=64, m=16, c_out=64):
+    return B.Bottleneck(c_in, m, c_out, *([FAKE] * 9), 0)
+
+
+def test_workspace_sizes(lib):
+    fx = B.Fmap(128, 14, 14, 1024, B.BF16)
+    p = _bn(1024, 256, 1024)
+    npix = 128 * 14 * 14
+    dyn = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, p, 2)
+    assert dyn >= 2 * npix * 256 * 2 + npix * 4 and dyn < 2 * npix * 256 * 2 + npix * 4 + 8192
+    assert L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4) == 2 * npix * 256 * 2
+    assert L.workspace_size(B.OP_MASK_GEN, fx, None, 2) == 256
+    assert L.workspace_size(B.OP_COMPACT, fx, None, 300001) >= 4 * 74
+    assert L.workspace_size(B.OP_GATHER, fx, None, 2) == 0
+    assert L.workspace_size(B.OP_MASK_GEN, fx, None, 3) == 0      # 3 does not divide 14
+    assert L.workspace_size(99, fx, None, 2) == 0
+
+
+def test_argument_validation_returns_codes_without_launching(lib):
+    vp = C.c_void_p
+    fx = B.Fmap(2, 8, 8, 64, B.F32)
+    p = _bn()
+    st = None
+    # mask_gen
+    f = lib.laud_mask_gen
+    assert f(None, fx, 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, None, 0, st) == B.ERR_INVALID_ARG
+    assert f(vp(FAKE), fx, 3, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, None, 0, st) == B.ERR_INVALID_ARG
+    assert f(vp(FAKE), B.Fmap(2, 8, 8, 60, 0), 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, None, 0, st) == B.ERR_UNSUPPORTED
+    assert f(vp(FAKE), B.Fmap(2, 8, 8, 64, 7), 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, None, 0, st) == B.ERR_INVALID_ARG
+    big = B.Fmap(200, 56, 56, 64, 0)  # 200*196 patches > one compaction block: needs a workspace
+    assert f(vp(FAKE), big, 4, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, None, 0, st) == B.ERR_WORKSPACE
+    # compact
+    g = lib.laud_layer_skip_compact
+    assert g(None, 5, vp(FAKE), vp(FAKE), None, 0, st) == B.ERR_INVALID_ARG
+    assert g(vp(FAKE), -1, vp(FAKE), vp(FAKE), None, 0, st) == B.ERR_INVALID_ARG
+    assert g(vp(FAKE), 100000, vp(FAKE), vp(FAKE), None, 0, st) == B.ERR_WORKSPACE
+    # gather
+    h = lib.laud_gather_patches
+    assert h(vp(FAKE), fx, 2, 2, vp(FAKE), vp(FAKE), vp(FAKE), st) == B.ERR_INVALID_ARG
+    assert h(vp(FAKE), fx, 5, 1, vp(FAKE), vp(FAKE), vp(FAKE), st) == B.ERR_INVALID_ARG
+    assert h(vp(FAKE), fx, 2, 1, None, vp(FAKE), vp(FAKE), st) == B.ERR_INVALID_ARG
+    # dyn bottleneck
+    d = lib.laud_dyn_bottleneck
+    need = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, p, 2)
+    assert d(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE), None, 0, st) == B.ERR_WORKSPACE
+    assert d(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need - 1, st) == B.ERR_WORKSPACE
+    assert d(vp(FAKE), fx, C.byref(p), 3, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    assert d(vp(FAKE), fx, None, 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    assert d(vp(FAKE), fx, C.byref(_bn(32, 16, 32)), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG  # C mismatch
+    assert d(vp(FAKE), fx, C.byref(_bn(64, 16, 128)), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_UNSUPPORTED
+    assert d(vp(FAKE), fx, C.byref(_bn(64, 12, 64)), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_UNSUPPORTED
+    assert d(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE + 64), vp(FAKE), need, st) == B.ERR_INVALID_ARG  # partial overlap
+    nullw = B.Bottleneck(64, 16, 64, 0, *([FAKE] * 8), 0)
+    assert d(vp(FAKE), fx, C.byref(nullw), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    # channel skip
+    c = lib.laud_channel_skip_conv
+    needc = L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4)
+    assert c(vp(FAKE), fx, C.byref(p), vp(FAKE), 3, vp(FAKE), vp(FAKE), needc, st) == B.ERR_INVALID_ARG  # 3 does not divide 16
+    assert c(vp(FAKE), fx, C.byref(p), None, 4, vp(FAKE), vp(FAKE), needc, st) == B.ERR_INVALID_ARG
+    assert c(vp(FAKE), fx, C.byref(p), vp(FAKE), 4, vp(FAKE), vp(FAKE), needc - 1, st) == B.ERR_WORKSPACE
+
+
+def test_binding_raises_typed_error(lib):
+    with pytest.raises(L.LaudError) as e:
+        B._check(B.ERR_WORKSPACE, "laud_dyn_bottleneck")
+    assert e.value.status == B.ERR_WORKSPACE and "workspace" in str(e.value)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liblaud.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.load()
+
+
+# ----- input generators --------------------------------------------------------------------
+def test_bf16_rounding_matches_torch():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(0)
+    a = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 10.0 ** rng.integers(-20, 20, 20000),
+                        np.array([0.0, -0.0, np.inf, -np.inf, 1.0, 1.00390625, 1.01171875, 3.4e38], np.float32)])
+    want = torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(I.bf16_bits(a), want)
+    assert np.array_equal(I.bf16_bits_to_f32(I.bf16_bits(a)), torch.from_numpy(a).to(torch.bfloat16).float().numpy())
+    assert I.bf16_bits(np.array([np.nan], np.float32))[0] == 0x7FC0
+    r = I.round_to(a[:100], I.BF16)
+    assert np.array_equal(I.round_to(r, I.BF16), r)  # idempotent
+
+
+def test_bias_for_ratio_hits_the_target_in_a_gap():
+    rng = np.random.default_rng(1)
+    lg = rng.standard_normal(6272)
+    for r in (0.25, 0.5, 0.75):
+        b, half = I.bias_for_ratio(lg, r)
+        n_on = int((lg + b > 0).sum())
+        assert abs(n_on - round(r * lg.size)) <= 16
+        assert np.abs(lg + b).min() == pytest.approx(half)
+    b, _ = I.bias_for_ratio(lg, 1.0)
+    assert (lg + b > 0).all()
+    b, _ = I.bias_for_ratio(lg, 0.0)
+    assert not (lg + b > 0).any()
+
+
+def test_masks_and_params_are_seeded_and_shaped():
+    m1 = I.coherent_mask(3, 4, 7, 7, 0.5)
+    assert m1.shape == (4, 7, 7) and np.all(m1.reshape(4, -1).sum(1) == 24)
+    assert np.array_equal(m1, I.coherent_mask(3, 4, 7, 7, 0.5))
+    assert I.coherent_mask(3, 2, 7, 7, 0.0).sum() == 0 and I.coherent_mask(3, 2, 7, 7, 1.0).sum() == 98
+    hb = I.bottleneck_params(10, 64, 16, 64, I.BF16)
+    assert hb.w1.shape == (16, 64) and hb.w2.shape == (16, 3, 3, 16) and hb.w3.shape == (64, 16)
+    assert np.array_equal(I.round_to(hb.w2, I.BF16), hb.w2)
+    assert abs(float(hb.w2.std()) - np.sqrt(2.0 / (9 * 16))) < 0.02
+    assert I.seed_for(2, 5, 3) == 2035
