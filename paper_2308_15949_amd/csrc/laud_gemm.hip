@@ -372,7 +372,10 @@ __global__ __launch_bounds__(256) void k_need(const int32_t* __restrict__ idx, c
   }
   __syncthreads();
   const int lo = lower_bound_dev(idx, cnt, n * pps), hi = lower_bound_dev(idx, cnt, (n + 1) * pps);
-  for (int i = lo + tid; i < hi; i += 256) s_pm[idx[i] - n * pps] = 1;
+  for (int i = lo + tid; i < hi; i += 256) {
+    const unsigned v = (unsigned)(idx[i] - n * pps);
+    if (v < (unsigned)pps) s_pm[v] = 1;
+  }
   __syncthreads();
   int running = WRITE ? s_base : 0;
   for (int p0 = 0; p0 < HW; p0 += 256) {
