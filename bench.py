@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamic-bottleneck hot path on one MI355X.
+
+A step = one pass of the whole path (laud_mask_gen + laud_dyn_bottleneck, in place) over one
+batch of BASELINE config 2: x 128 x 14 x 14 x 1024 bf16, mid width 256, S = 2, mask from the
+pooled masker with the bias calibrated to the target activation ratio.  Every step gets its own
+pristine copy of x (the block updates x in place), so inputs are resident in HBM but cold in
+the caches.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--ratio", type=float, default=0.5, help="target activation ratio of the timed steps")
+    ap.add_argument("--sweep-steps", type=int, default=40, help="steps per ratio of the latency-vs-ratio sweep (0 = off)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=128)
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards along the batch with no "
+              "exchange step; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import binding as B
+    from paper_2308_15949_amd import device as D
+    from paper_2308_15949_amd import inputs as I
+
+    L.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t = torch
+
+    st = I.STAGES[3]
+    N, H, C, m, S, dt = a.batch, st["hw"], st["c_in"], st["m"], st["S"], I.BF16
+    hp = H // S
+    npatch = N * hp * hp
+    x_host = I.feature_map(I.seed_for(2, 0), N, H, H, C, dt)
+    hb = I.bottleneck_params(I.seed_for(2, 0), C, m, C, dt, relu_out=False)
+    w_host = I.masker_weights(I.seed_for(2, 5), C)
+    x_master = D.to_device(x_host, dt)
+    fx = L.fmap_of(x_master)
+    db = D.DeviceBottleneck(hb)
+    wd = t.from_numpy(w_host).cuda()
+    mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    lg = t.zeros(npatch, dtype=t.float32, device="cuda")
+    wsm = D.workspace(L.workspace_size(B.OP_MASK_GEN, fx, None, S))
+    ws = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fx, db.desc, S))
+
+    nbuf = a.steps + a.warmup
+    xbytes = x_master.numel() * x_master.element_size()
+    free, _ = t.cuda.mem_get_info()
+    if nbuf * xbytes > 0.8 * free:
+        print(f"bench.py: {nbuf} input copies of {xbytes / 1e6:.1f} MB do not fit; lower --steps", file=sys.stderr)
+        sys.exit(2)
+    bufs = [x_master.clone() for _ in range(nbuf)]
+
+    def restore(k=None):
+        for b in (bufs if k is None else bufs[:k]):
+            b.copy_(x_master)
+        t.cuda.synchronize()
+
+    # bias per target ratio from the GPU's own logits (workload construction, not a checked value)
+    L.laud_mask_gen(x_master, fx, S, wd, 0.0, None, mask, idx, cnt, None, lg, wsm)
+    t.cuda.synchronize()
+    logits0 = lg.cpu().numpy()
+    bias_of = {r: I.bias_for_ratio(logits0, r)[0] for r in (0.0, 0.25, 0.5, 0.75, 1.0, a.ratio)}
+
+    def step(buf, bias):
+        L.laud_mask_gen(buf, fx, S, wd, bias, None, mask, idx, cnt, None, None, wsm)
+        L.laud_dyn_bottleneck(buf, fx, db.desc, S, idx, cnt, buf, ws)
+
+    def timed(bias, steps, warmup, per_step_events=False):
+        for i in range(warmup):
+            step(bufs[i], bias)
+        t.cuda.synchronize()
+        ev = [(t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)) for _ in range(steps)] \
+            if per_step_events else None
+        t0 = time.perf_counter()
+        for i in range(steps):
+            if ev:
+                ev[i][0].record()
+            step(bufs[warmup + i], bias)
+            if ev:
+                ev[i][1].record()
+        t.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        P = int(cnt.item())
+        lat = sorted(e0.elapsed_time(e1) for e0, e1 in ev) if ev else None
+        return wall, P, lat
+
+    def useful_flops(P):
+        return P * S * S * 2.0 * 17.0 * m * m
+
+    # ---- the timed region: exactly `steps` steps, sync on both sides ---------------------------
+    bias = bias_of[a.ratio]
+    wall, P, _ = timed(bias, a.steps, a.warmup)
+    ms_per_step = wall * 1e3 / a.steps
+    value = N * a.steps / wall
+
+    # ---- second pass over the same steps with events: p50 latency and per-stage kernel time ----
+    restore()
+    _, _, lat = timed(bias, a.steps, a.warmup, per_step_events=True)
+    p50 = lat[len(lat) // 2]
+    restore()
+    for i in range(a.warmup):
+        step(bufs[i], bias)
+    t.cuda.synchronize()
+    L.laud_stage_timing_enable(True)
+    for i in range(a.steps):
+        step(bufs[a.warmup + i], bias)
+    t.cuda.synchronize()
+    stages = L.laud_stage_timing_read()
+    L.laud_stage_timing_enable(False)
+    stage_us = {k: 1e3 * v[0] / a.steps for k, v in stages.items()}
+    conv2_us = stage_us["conv2"]
+    conv2_flops = P * S * S * 2.0 * 9.0 * m * m
+    achieved = conv2_flops / (conv2_us * 1e-6) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_gemm<CONV2,bf16> (3x3 implicit GEMM on active patches)",
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": conv2_flops, "avg_us": round(conv2_us, 2)}
+
+    # ---- latency vs activation ratio -------------------------------------------------------------
+    sweep = []
+    if a.sweep_steps > 0:
+        k = min(a.sweep_steps, a.steps)
+        wu = min(a.warmup, 5)
+        for r in (0.0, 0.25, 0.5, 0.75, 1.0):
+            restore(k + wu)
+            _, Pr, latr = timed(bias_of[r], k, wu, per_step_events=True)
+            p = latr[len(latr) // 2]
+            sweep.append({"ratio_target": r, "active_patches": Pr, "ratio": round(Pr / npatch, 4),
+                          "p50_us": round(p * 1e3, 1), "p10_us": round(latr[len(latr) // 10] * 1e3, 1),
+                          "p90_us": round(latr[(9 * len(latr)) // 10] * 1e3, 1),
+                          "images_per_s": round(N / (p * 1e-3), 0),
+                          "mfma_frac_useful": round(useful_flops(Pr) / (p * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4)})
+        rs = np.array([s["ratio"] for s in sweep])
+        ls = np.array([s["p50_us"] for s in sweep])
+        A = np.stack([np.ones_like(rs), rs], 1)
+        coef, *_ = np.linalg.lstsq(A, ls, rcond=None)
+        res = ls - A @ coef
+        r2 = 1.0 - float(res @ res) / float(((ls - ls.mean()) ** 2).sum() or 1.0)
+        fit = {"intercept_us": round(float(coef[0]), 1), "slope_us_per_unit_ratio": round(float(coef[1]), 1),
+               "r2": round(r2, 4)}
+    else:
+        fit = None
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload --------
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import laud_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        po = O.BottleneckParams(hb.w1, hb.w2, hb.w3, hb.s1, hb.t1, hb.s2, hb.t2, hb.s3, hb.t3, hb.relu_out)
+
+        def oracle_pass(ns):
+            t0 = time.perf_counter()
+            lgts = O.mask_logits(x_host[:ns], S, w_host, bias)
+            mk = O.threshold(lgts)
+            O.compact(mk)
+            O.dyn_bottleneck(x_host[:ns], po, S, mk)
+            return time.perf_counter() - t0
+
+        ns = min(4, N)
+        dt0 = oracle_pass(ns)
+        ns2 = int(max(ns, min(N, ns * 12.0 / max(dt0, 1e-3))))
+        dt1 = oracle_pass(ns2) if ns2 > ns else dt0
+        cpu = {"value": round(ns2 / dt1, 2), "unit": "images/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {ns2} of {N} images of the same batch, one pass of masker + index list + "
+                         f"dense-then-mask block in numpy float64 ({dt1:.1f} s)"}
+
+    out = {
+        "metric": "dynamic-bottleneck images/sec (mask_gen + dyn_bottleneck, stage-3 block, batch 128) "
+                  "at activation ratio %.2f; p50 latency vs ratio and MFMA fraction in 'sweep'" % a.ratio,
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "BASELINE config 2: stage-3 dynamic bottleneck, x 128x14x14x1024 NHWC bf16, "
+                               "mid 256, S=2 (7x7 patch grid), mask from the pooled 1x1 masker, bias calibrated "
+                               "to the target ratio; in place; one pristine cache-cold copy of x per step",
+                   "global_batch": N, "activation_ratio": round(P / npatch, 4), "active_patches": P},
+        "p50_us": round(p50 * 1e3, 1),
+        "mfma_frac_useful_flops": round(useful_flops(P) / (p50 * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+        "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "sweep": sweep,
+        "latency_fit": fit,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

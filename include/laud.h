@@ -154,6 +154,33 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
                            const uint8_t* cmask, int D, void* out,
                            void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Instrumentation (host side; not part of the paper's method): per-stage GPU time of the
+ * kernels the entry points launch.  While enabled, every stage is bracketed by a pair of HIP
+ * events recorded on the call's stream (at most 65536 stage launches are kept per collection;
+ * later ones are dropped).  laud_stage_timing_enable(1) clears what was collected and starts,
+ * (0) stops.  laud_stage_timing_read() waits for the recorded events, adds up the elapsed
+ * milliseconds and launch counts per stage into two HOST arrays of LAUD_STAGE_COUNT entries,
+ * and clears the collection.  Not thread-safe against concurrent entry-point calls.
+ */
+typedef enum {
+  LAUD_STAGE_MASK_LOGITS = 0, /* pooled masker + threshold */
+  LAUD_STAGE_COMPACT = 1,     /* ordered index generation */
+  LAUD_STAGE_GATHER = 2,      /* stand-alone gather */
+  LAUD_STAGE_COPY_INACTIVE = 3,
+  LAUD_STAGE_NEED = 4,        /* dilated active pixel list for conv1 */
+  LAUD_STAGE_CONV1 = 5,
+  LAUD_STAGE_CONV2 = 6,
+  LAUD_STAGE_CONV3 = 7,
+  LAUD_STAGE_CS1 = 8,
+  LAUD_STAGE_CS2 = 9,
+  LAUD_STAGE_CS3 = 10,
+  LAUD_STAGE_COUNT = 11
+} laud_stage;
+int laud_stage_timing_enable(int on);
+int laud_stage_timing_read(double* total_ms, int64_t* launches);
+const char* laud_stage_name(int stage);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
-           "laud_channel_skip_conv"]
+           "laud_channel_skip_conv", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+STAGE_COUNT = 11
 
 
 class Fmap(C.Structure):
@@ -68,6 +69,12 @@ def load() -> C.CDLL:
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
     lib.laud_channel_skip_conv.restype = i32
     lib.laud_channel_skip_conv.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, i32, vp, vp, sz, vp]
+    lib.laud_stage_timing_enable.restype = i32
+    lib.laud_stage_timing_enable.argtypes = [i32]
+    lib.laud_stage_timing_read.restype = i32
+    lib.laud_stage_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.laud_stage_name.restype = C.c_char_p
+    lib.laud_stage_name.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -157,3 +164,15 @@ def laud_channel_skip_conv(x, fx: Fmap, p: Bottleneck, cmask, D: int, out, ws) -
     wp, wb = _ws_args(ws)
     _check(load().laud_channel_skip_conv(_ptr(x), fx, C.byref(p), _ptr(cmask), int(D), _ptr(out),
                                          wp, wb, _stream()), "laud_channel_skip_conv")
+
+
+def laud_stage_timing_enable(on: bool) -> None:
+    _check(load().laud_stage_timing_enable(1 if on else 0), "laud_stage_timing_enable")
+
+
+def laud_stage_timing_read() -> dict[str, tuple[float, int]]:
+    """{stage name: (total milliseconds, launches)} for the stages that ran since enabling."""
+    ms = (C.c_double * STAGE_COUNT)()
+    n = (C.c_int64 * STAGE_COUNT)()
+    _check(load().laud_stage_timing_read(ms, n), "laud_stage_timing_read")
+    return {load().laud_stage_name(i).decode(): (float(ms[i]), int(n[i])) for i in range(STAGE_COUNT) if n[i]}

@@ -55,6 +55,10 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // ---- host-side launch checking -----------------------------------------------------------
+// hipGetLastError() reports (and clears) the last error of ANY earlier HIP call of the thread,
+// the caller's included; each entry point clears that state once, after validation and before
+// its first launch, so that check_launch() sees only the library's own launches.
+inline void clear_stale_error() { (void)hipGetLastError(); }
 inline int check_launch() { return hipGetLastError() == hipSuccess ? LAUD_OK : LAUD_ERR_HIP; }
 
 inline bool valid_fmap(const laud_fmap& f) {
@@ -69,8 +73,22 @@ inline size_t compact_ws_bytes(long long n) {
   return align_up((size_t)(nb > 0 ? nb : 1) * sizeof(int32_t), 256);
 }
 
-// Launches the ordered compaction of `n` mask bytes on `stream` (see laud_compact.hip).
+// Launches the ordered compaction of `n` mask bytes on `stream` (see laud_mask.hip).
 int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int32_t* sample_offsets,
                    int per_sample, int32_t* block_counts, hipStream_t stream);
+
+// Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
+extern bool g_stage_timing_on;
+void stage_mark(int stage, hipStream_t stream, bool begin);
+struct StageScope {
+  int stage;
+  hipStream_t stream;
+  StageScope(int s, hipStream_t st) : stage(s), stream(st) {
+    if (g_stage_timing_on) stage_mark(stage, stream, true);
+  }
+  ~StageScope() {
+    if (g_stage_timing_on) stage_mark(stage, stream, false);
+  }
+};
 
 }  // namespace laud

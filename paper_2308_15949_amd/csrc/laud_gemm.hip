@@ -469,6 +469,9 @@ static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hi
 
 template <int MODE>
 static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
+  constexpr int kStage[6] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
+                             LAUD_STAGE_CS1, LAUD_STAGE_CS2, LAUD_STAGE_CS3};
+  StageScope scope(kStage[MODE], st);
   return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
 }
@@ -548,6 +551,7 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   const DynWs L = dyn_ws_layout(fx, p->c_mid);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
   char* wsb = (char*)ws;
   int32_t* need_counts = (int32_t*)(wsb + L.need_counts);
   int32_t* total = (int32_t*)(wsb + L.total);
@@ -558,15 +562,19 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
 
   if (x != out) {
+    StageScope scope(LAUD_STAGE_COPY_INACTIVE, st);
     hipLaunchKernelGGL(k_copy_inactive, dim3((unsigned)(fx.N * Hp * Wp)), dim3(256), 0, st, (const uint4*)x,
                        (uint4*)out, fx.H, fx.W, S, cpp, idx, count);
     if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
   }
   const size_t pm_bytes = align_up((size_t)Hp * Wp, 16);
+  {
+    StageScope scope(LAUD_STAGE_NEED, st);
   hipLaunchKernelGGL((k_need<false>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
                      need_counts, pix, total);
   hipLaunchKernelGGL((k_need<true>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
                      need_counts, pix, total);
+  }
   if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
 
   GemmArgs a{};
@@ -597,6 +605,7 @@ extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bo
   const CsWs L = cs_ws_layout(fx, p->c_mid);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
   void* h1 = (char*)ws + L.h1;
   void* h2 = (char*)ws + L.h2;
   const long long hw = (long long)fx.H * fx.W;

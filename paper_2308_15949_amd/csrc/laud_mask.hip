@@ -97,6 +97,7 @@ __global__ void k_write_zero_count(int32_t* count, int32_t* sample_offsets) {
 
 int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int32_t* sample_offsets,
                    int per_sample, int32_t* block_counts, hipStream_t stream) {
+  StageScope scope(LAUD_STAGE_COMPACT, stream);
   if (n == 0) {
     hipLaunchKernelGGL(k_write_zero_count, dim3(1), dim3(1), 0, stream, count, sample_offsets);
     return check_launch();
@@ -211,6 +212,7 @@ extern "C" int laud_layer_skip_compact(const uint8_t* keep, int n, int32_t* idx,
                                        size_t ws_bytes, void* stream) {
   if (n < 0 || !count || (n > 0 && (!keep || !idx))) return LAUD_ERR_INVALID_ARG;
   if (n > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(n))) return LAUD_ERR_WORKSPACE;
+  clear_stale_error();
   return launch_compact(keep, n, idx, count, nullptr, 1, (int32_t*)ws, (hipStream_t)stream);
 }
 
@@ -224,10 +226,13 @@ extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w,
   if (npatch > 0x7fffffffLL || (long long)fx.N * fx.H * fx.W > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
   if (npatch > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(npatch))) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
   const size_t patch_bytes = (size_t)S * S * fx.C * elem_bytes(fx.dtype);
   const bool big = patch_bytes >= 32768;  // a whole block per patch
   const int teams = big ? 1 : 256 / kWave;
   const unsigned grid = (unsigned)((npatch + teams - 1) / teams);
+  {
+    StageScope scope(LAUD_STAGE_MASK_LOGITS, st);
 #define LAUD_LAUNCH_MASK(ET, TEAM)                                                                            \
   hipLaunchKernelGGL((k_mask_logits<ET, TEAM>), dim3(grid), dim3(256), 0, st, (const ET*)x, fx.N, fx.H, fx.W, \
                      fx.C, S, w, bias, keep, mask, logits)
@@ -237,6 +242,7 @@ extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w,
     if (big) LAUD_LAUNCH_MASK(float, 256); else LAUD_LAUNCH_MASK(float, 64);
   }
 #undef LAUD_LAUNCH_MASK
+  }
   if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
   return launch_compact(mask, (int)npatch, idx, count, sample_offsets, (fx.H / S) * (fx.W / S), (int32_t*)ws, st);
 }
@@ -253,6 +259,8 @@ extern "C" int laud_gather_patches(const void* x, laud_fmap fx, int S, int halo,
   const long long blocks = (slots + 3) / 4;
   if (blocks > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
   const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+  clear_stale_error();
+  StageScope scope(LAUD_STAGE_GATHER, (hipStream_t)stream);
   hipLaunchKernelGGL(k_gather, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)x, fx.H, fx.W,
                      S, halo, cpp, idx, count, (uint4*)out, slots);
   return check_launch();
