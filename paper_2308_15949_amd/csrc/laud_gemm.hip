@@ -27,8 +27,15 @@ namespace laud {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk in global memory
 
 enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5 };
+
+// 256 bytes of zeros in device memory: the source of every chunk that has to read as zero.  Not
+// declared const on purpose: the compiler must treat a load from it like any other load (it would
+// otherwise fold the zeros in and turn the pointer select back into a branch around the load).
+__device__ uint4 g_zero_page[16];
 
 constexpr int kMaxGroups = 1024;  // channel-skip decisions per sample the kernels can hold in LDS
 
@@ -107,8 +114,10 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2);
   constexpr bool CS = (MODE >= M_CS1);
 
-  __shared__ __align__(16) unsigned char sA[BM * LSTR];
-  __shared__ __align__(16) unsigned char sB[BN * LSTR];
+  constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int CSTR = BN * 4 + 32;      // epilogue staging row stride in bytes
+  static_assert(BM * CSTR <= 2 * STAGE_BYTES, "epilogue staging must fit in the two pipeline stages");
+  extern __shared__ __align__(16) unsigned char smem[];  // two pipeline stages, reused by the epilogue
   __shared__ int s_row[BM];
   __shared__ int s_kgrp[CS ? kMaxGroups : 1];
   __shared__ int s_nkept;
@@ -162,35 +171,61 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   }
 
   // ---- row descriptors ------------------------------------------------------------------------
+  // Each thread keeps, for the AR activation rows and BR weight rows it loads, one base pointer
+  // that already includes its 16-byte chunk, plus (tap modes) a 9-bit mask of the taps that fall
+  // inside the image.  Per K slice a load then costs one 64-bit add of a wave-uniform offset and
+  // one pointer select: a chunk that must read as zero (tap outside the image, row past the end,
+  // K tail) is loaded from a page of zeros, so nothing has to be masked afterwards.
   const int cc = tid & 7;    // 16-byte chunk within the 128-byte K slice
   const int lr = tid >> 3;   // 0..31: first row this thread loads
-  size_t abase[AR];          // A row offset in elements (modes without taps)
-  int ry[AR], rx[AR], rn[AR];  // pixel coordinates / sample pixel base (modes with taps)
-  bool rvalid[AR];
+  // Hide where the zero page's address comes from (knowing that it is a dereferenceable global, the
+  // compiler would split `load(ok ? row : zeros)` into two loads under a branch) but keep the fact
+  // that it is global memory, so that the loads stay global_load (vmcnt only) and not flat_load.
+  unsigned long long zaddr = reinterpret_cast<unsigned long long>(&g_zero_page[0]);
+#if defined(__HIP_DEVICE_COMPILE__)  // the constraint names a GPU register class: device pass only
+  asm volatile("" : "+s"(zaddr));
+#endif
+  const gptr16 zpage = (gptr16)zaddr;
+  const ET* arow[AR];
+  unsigned amask[AR];        // tap modes: bit t set = tap t readable; other modes: bit 0 = row valid
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int rho = row0 + lr + 32 * i;
-    rvalid[i] = rho < M;
-    abase[i] = 0; ry[i] = -4; rx[i] = -4; rn[i] = 0;
-    if (rvalid[i]) {
+    arow[i] = Ap;
+    amask[i] = 0;
+    if (rho < M) {
+      size_t pixrow;  // row of A (pixel id or compact row)
+      int y = 0, x = 0;
       if constexpr (MODE == M_CONV1) {
-        abase[i] = (size_t)a.list[rho] * a.lda;
+        pixrow = (size_t)a.list[rho];
       } else if constexpr (MODE == M_CONV3) {
-        abase[i] = (size_t)rho * a.lda;
+        pixrow = (size_t)rho;
       } else if constexpr (MODE == M_CONV2) {
         const int p = rho / SS, j = rho - p * SS;
         const int q = a.list[p];
         const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
         const int py = r2 / Wp, px = r2 - py * Wp;
-        ry[i] = py * a.S + j / a.S;
-        rx[i] = px * a.S + j % a.S;
-        rn[i] = n * HW;
+        y = py * a.S + j / a.S;
+        x = px * a.S + j % a.S;
+        pixrow = (size_t)n * HW + (size_t)y * a.W + x;
       } else if constexpr (MODE == M_CS2) {
-        ry[i] = rho / a.W;
-        rx[i] = rho - ry[i] * a.W;
-        rn[i] = sample * HW;
+        y = rho / a.W;
+        x = rho - y * a.W;
+        pixrow = (size_t)sample * HW + rho;
       } else {  // CS1, CS3
-        abase[i] = ((size_t)sample * HW + rho) * a.lda;
+        pixrow = (size_t)sample * HW + rho;
+      }
+      arow[i] = Ap + pixrow * a.lda + cc * EPC;
+      if constexpr (TAPS) {
+        unsigned mk = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
+          if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W) mk |= 1u << t;
+        }
+        amask[i] = mk;
+      } else {
+        amask[i] = 1u;
       }
     }
   }
@@ -216,60 +251,78 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   }
 
   // ---- weight-row descriptors -----------------------------------------------------------------
-  size_t wbase[BR];
+  const ET* wrow[BR];
   bool cvalid[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
     const int c = col0 + lr + 32 * i;
     cvalid[i] = c < ncols;
-    int wr = c;
-    if constexpr (MODE == M_CS1 || MODE == M_CS2) {
-      if (cvalid[i]) wr = s_kgrp[c / a.G] * a.G + (c % a.G);
-    }
-    wbase[i] = cvalid[i] ? (size_t)wr * a.ldw : 0;
+    int wr = cvalid[i] ? c : col0;  // a column past the end re-reads the tile's first row: its result is dropped
+    if constexpr (MODE == M_CS1 || MODE == M_CS2) wr = s_kgrp[wr / a.G] * a.G + (wr % a.G);
+    wrow[i] = Wp_ + (size_t)wr * a.ldw;
+    if constexpr (!(MODE == M_CS2 || MODE == M_CS3)) wrow[i] += cc * EPC;
   }
 
   const int kchunks = (keff + BKE - 1) / BKE;
   const int KT = (TAPS ? 9 : 1) * kchunks;
   const bool kvec = (a.G % EPC) == 0;  // kept-channel gather can use 16-byte loads
 
-  uint4 ra[AR], rb[BR];
-  auto load_slice = [&](int it) {
-    int tap = 0, kc = it;
-    if constexpr (TAPS) { tap = it / kchunks; kc = it - tap * kchunks; }
-    const int ke = kc * BKE + cc * EPC;  // first (compact) K element of this thread's chunk
+  // Issues the loads of this thread's 16-byte chunks of the next K slice (A: AR rows, B: BR weight
+  // rows).  All loads are unconditional and branch-free, so the compiler can count the loads in
+  // flight instead of draining them.  Slices are visited in order; (tap, kc) advance per call.
+  const int gW = a.W, glda = a.lda, gK = a.K, gG = a.G;
+  int ld_tap = 0, ld_kc = 0, ld_ky = -1, ld_kx = -1;
+  auto load_slice = [&](u32x4 (&ra)[AR], u32x4 (&rb)[BR], int& ke_out) __attribute__((always_inline)) {
+    const int tap = ld_tap;
+    const int kbase = ld_kc * BKE;          // wave-uniform first K element of the slice
+    const int ke = kbase + cc * EPC;        // this thread's first (compact) K element
+    ke_out = ke;
     const bool kv = ke < keff;
-    const int ky = tap / 3 - 1, kx = tap % 3 - 1;
+    // wave-uniform element offsets of this slice relative to the row base pointers
+    const long long aoff = TAPS ? (long long)(ld_ky * gW + ld_kx) * glda + kbase : (long long)kbase;
+    const long long woff = (long long)tap * gK + kbase;
+    if (++ld_kc == kchunks) {
+      ld_kc = 0; ++ld_tap;
+      if (++ld_kx == 2) { ld_kx = -1; ++ld_ky; }
+    }
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if constexpr (TAPS) {
-        const int yy = ry[i] + ky, xx = rx[i] + kx;
-        if (kv && rvalid[i] && yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
-          v = *reinterpret_cast<const uint4*>(Ap + ((size_t)(rn[i] + yy * a.W + xx)) * a.lda + ke);
-      } else {
-        if (kv && rvalid[i]) v = *reinterpret_cast<const uint4*>(Ap + abase[i] + ke);
-      }
-      if constexpr (MODE == M_CS2 || MODE == M_CS3) {
-        // compact rows are valid up to keff only; what lies beyond in the scratch buffer is undefined
-        if (!kvec && ke + EPC > keff) v = mask_tail<ET>(v, keff - ke);
-      }
-      ra[i] = v;
+      const bool ok = kv && ((amask[i] >> (TAPS ? tap : 0)) & 1u);
+      ra[i] = *(ok ? (gptr16)(arow[i] + aoff) : zpage);
     }
 #pragma unroll
     for (int i = 0; i < BR; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (kv && cvalid[i]) {
-        const ET* wrow = Wp_ + wbase[i] + (size_t)tap * a.K;
-        if constexpr (MODE == M_CS2 || MODE == M_CS3) {
-          if (kvec) v = *reinterpret_cast<const uint4*>(wrow + s_kgrp[ke / a.G] * a.G + (ke % a.G));
-          else v = gather_elems<ET>(wrow, s_kgrp, a.G, ke, keff);
-        } else {
-          v = *reinterpret_cast<const uint4*>(wrow + ke);
+      if constexpr (MODE == M_CS2 || MODE == M_CS3) {
+        const ET* wtap = wrow[i] + (long long)tap * gK;
+        if (kvec) {
+          rb[i] = *(kv ? (gptr16)(wtap + s_kgrp[ke / gG] * gG + (ke % gG)) : zpage);
+        } else {  // narrow groups: element-wise gather
+          uint4 g = make_uint4(0, 0, 0, 0);
+          if (kv) g = gather_elems<ET>(wtap, s_kgrp, gG, ke, keff);
+          rb[i] = u32x4{g.x, g.y, g.z, g.w};
+        }
+      } else {
+        rb[i] = *(kv ? (gptr16)(wrow[i] + woff) : zpage);
+      }
+    }
+  };
+  auto store_slice = [&](int buf, const u32x4 (&ra)[AR], const u32x4 (&rb)[BR], int ke) __attribute__((always_inline)) {
+    unsigned char* sA = smem + buf * STAGE_BYTES;
+    unsigned char* sB = sA + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < AR; ++i) {
+      u32x4 v = ra[i];
+      if constexpr (MODE == M_CS2 || MODE == M_CS3) {
+        // compact rows are valid up to keff only; what lies beyond in the scratch buffer is undefined
+        if (!kvec && ke + EPC > keff) {
+          const uint4 t = mask_tail<ET>(make_uint4(v.x, v.y, v.z, v.w), keff - ke);
+          v = u32x4{t.x, t.y, t.z, t.w};
         }
       }
-      rb[i] = v;
+      *reinterpret_cast<u32x4*>(sA + (lr + 32 * i) * LSTR + cc * 16) = v;
     }
+#pragma unroll
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<u32x4*>(sB + (lr + 32 * i) * LSTR + cc * 16) = rb[i];
   };
 
   f32x16 acc[TM][TN];
@@ -280,16 +333,10 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  if (KT > 0) load_slice(0);
-  for (int it = 0; it < KT; ++it) {
-#pragma unroll
-    for (int i = 0; i < AR; ++i) *reinterpret_cast<uint4*>(sA + (lr + 32 * i) * LSTR + cc * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < BR; ++i) *reinterpret_cast<uint4*>(sB + (lr + 32 * i) * LSTR + cc * 16) = rb[i];
-    __syncthreads();
-    if (it + 1 < KT) load_slice(it + 1);  // global loads fly while the MFMAs run
-    const unsigned char* pa = sA + (wm * (BM / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
-    const unsigned char* pb = sB + (wn * (BN / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
+  auto compute = [&](int buf) __attribute__((always_inline)) {
+    const unsigned char* pa = smem + buf * STAGE_BYTES + (wm * (BM / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
+    const unsigned char* pb = smem + buf * STAGE_BYTES + A_BYTES + (wn * (BN / 2) + (lane & 31)) * LSTR +
+                              (lane >> 5) * 16;
 #pragma unroll
     for (int kg = 0; kg < 4; ++kg) {
       uint4 fa[TM], fb[TN];
@@ -302,37 +349,131 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) mma16<ET>(acc[i][j], fa[i], fb[j]);
     }
+  };
+
+  // Software pipeline: two LDS stages, two register sets.  While slice `it` is multiplied out of LDS
+  // stage it%2, slice it+1 moves from registers to the other stage and slices it+2 / it+3 are in
+  // flight from L2 / HBM: one barrier per K slice, two slices of load latency covered.
+  u32x4 ra0[AR], rb0[BR], ra1[AR], rb1[BR];
+  int k0 = 0, k1 = 0;
+  if (KT >= 3) {
+    load_slice(ra0, rb0, k0);
+    load_slice(ra1, rb1, k1);
+    store_slice(0, ra0, rb0, k0);
+    load_slice(ra0, rb0, k0);
+    __syncthreads();  // also publishes s_row
+    int it = 0;
+    for (; it + 4 < KT; it += 2) {  // steady state: nothing conditional
+      store_slice(1, ra1, rb1, k1);
+      load_slice(ra1, rb1, k1);
+      compute(0);
+      __syncthreads();
+      store_slice(0, ra0, rb0, k0);
+      load_slice(ra0, rb0, k0);
+      compute(1);
+      __syncthreads();
+    }
+    // drain: three or four slices are left; slice it is in stage 0, it+1 in set 1, it+2 in set 0
+    const bool four = it + 3 < KT;
+    store_slice(1, ra1, rb1, k1);
+    if (four) load_slice(ra1, rb1, k1);
+    compute(0);
     __syncthreads();
+    store_slice(0, ra0, rb0, k0);
+    compute(1);
+    __syncthreads();
+    if (four) store_slice(1, ra1, rb1, k1);
+    compute(0);
+    __syncthreads();
+    if (four) {
+      compute(1);
+      __syncthreads();
+    }
+  } else {  // one or two slices (or none): no pipeline
+    __syncthreads();
+    for (int it = 0; it < KT; ++it) {
+      load_slice(ra0, rb0, k0);
+      store_slice(0, ra0, rb0, k0);
+      __syncthreads();
+      compute(0);
+      __syncthreads();
+    }
   }
-  if (KT == 0) __syncthreads();  // s_row must be visible before the epilogue
 
   // ---- epilogue ---------------------------------------------------------------------------------
-  // 32x32 accumulator layout: lane l holds column l%32, rows 8*(e/4) + 4*(l/32) + e%4.
-  ET* Op = (ET*)a.Out;
-  const ET* Rp = (const ET*)a.Res;
+  // Affine (+ReLU) in the accumulator layout (32x32 tile: lane l holds column l%32, rows
+  // 8*(e/4) + 4*(l/32) + e%4), then through LDS so that global traffic is 16 bytes per lane:
+  // residual read, add, rounding and the scatter store all happen on whole 16-byte channel chunks.
+  {
+    float* stg = reinterpret_cast<float*>(smem);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
-    if (col >= ncols) continue;
-    int ch = col;
-    if constexpr (MODE == M_CS1 || MODE == M_CS2) ch = s_kgrp[col / a.G] * a.G + (col % a.G);
-    const float sc = a.scale[ch], sh = a.shift[ch];
+    for (int j = 0; j < TN; ++j) {
+      const int cl = wn * (BN / 2) + j * 32 + (lane & 31);
+      const int col = col0 + cl;
+      float sc = 0.f, sh = 0.f;
+      if (col < ncols) {
+        int ch = col;
+        if constexpr (MODE == M_CS1 || MODE == M_CS2) ch = s_kgrp[col / a.G] * a.G + (col % a.G);
+        sc = a.scale[ch];
+        sh = a.shift[ch];
+      }
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        const int orow = s_row[rl];
-        if (orow < 0) continue;
-        const size_t off = (size_t)orow * a.ldo + col;
-        float v = acc[i][j][e] * sc + sh;
-        if constexpr (MODE == M_CONV3 || MODE == M_CS3) {
-          v += elem<ET>::load(Rp + off);
-          if (a.relu) v = fmaxf(v, 0.f);
-        } else {
-          v = fmaxf(v, 0.f);
+        for (int e = 0; e < 16; ++e) {
+          const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          float v = acc[i][j][e] * sc + sh;
+          if constexpr (!(MODE == M_CONV3 || MODE == M_CS3)) v = fmaxf(v, 0.f);
+          stg[rl * (CSTR / 4) + cl] = v;
         }
-        elem<ET>::store(Op + off, v);
+      }
+    }
+  }
+  __syncthreads();
+  {
+    ET* Op = (ET*)a.Out;
+    const ET* Rp = (const ET*)a.Res;
+    constexpr int CPR = BN / EPC;  // 16-byte output chunks per tile row
+    constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3);
+    for (int id = tid; id < BM * CPR; id += 256) {
+      const int rl = id / CPR, chk = id - rl * CPR;
+      const int orow = s_row[rl];
+      const int col = col0 + chk * EPC;
+      if (orow < 0 || col >= ncols) continue;
+      const float* sp = reinterpret_cast<const float*>(smem + rl * CSTR) + chk * EPC;
+      float v[EPC];
+#pragma unroll
+      for (int q = 0; q < EPC / 4; ++q) {
+        const float4 t4 = reinterpret_cast<const float4*>(sp)[q];
+        v[4 * q] = t4.x; v[4 * q + 1] = t4.y; v[4 * q + 2] = t4.z; v[4 * q + 3] = t4.w;
+      }
+      const size_t off = (size_t)orow * a.ldo + col;
+      if (col + EPC <= ncols) {
+        if constexpr (RES) {
+          const uint4 rraw = *reinterpret_cast<const uint4*>(Rp + off);
+          ET rr[EPC];
+          __builtin_memcpy(rr, &rraw, 16);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) {
+            v[e] += elem<ET>::load(&rr[e]);
+            if (a.relu) v[e] = fmaxf(v[e], 0.f);
+          }
+        }
+        ET ov[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) elem<ET>::store(&ov[e], v[e]);
+        uint4 oraw;
+        __builtin_memcpy(&oraw, ov, 16);
+        *reinterpret_cast<uint4*>(Op + off) = oraw;
+      } else {  // ragged last chunk (channel-skip widths that are not a multiple of the chunk)
+        for (int e = 0; e < ncols - col; ++e) {
+          float u = v[e];
+          if constexpr (RES) {
+            u += elem<ET>::load(Rp + off + e);
+            if (a.relu) u = fmaxf(u, 0.f);
+          }
+          elem<ET>::store(Op + off + e, u);
+        }
       }
     }
   }
@@ -455,7 +596,15 @@ static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream
   dim3 grid;
   if (!CS) grid = dim3((unsigned)(((a.row_tiles + 7) / 8) * 8 * a.col_tiles));
   else grid = dim3((unsigned)(a.row_tiles * a.col_tiles), (unsigned)nsamples);
-  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN>), grid, dim3(256), 0, st, a);
+  constexpr int kLds = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
+  static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be requested once per kernel
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess)
+      return LAUD_ERR_HIP;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN>), grid, dim3(256), kLds, st, a);
   return check_launch();
 }
 
