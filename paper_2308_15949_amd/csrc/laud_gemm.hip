@@ -58,6 +58,7 @@ struct GemmArgs {
   int relu;
   int D, G;              // CS: groups per sample, channels per group
   int row_tiles, col_tiles;
+  int group_rows, tiles_per_group;  // CONV1: pixel lists are kept per group of samples
 };
 
 // ---- one 16-byte fragment pair -> MFMA ------------------------------------------------------
@@ -104,33 +105,37 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int nvalid) {
   return v;
 }
 
-template <int MODE, typename ET, int BM, int BN>
-__global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
+template <int MODE, typename ET, int BM, int BN, int WGN>
+__global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
+  // 2 x WGN waves; each wave owns a (BM/2) x (BN/WGN) sub-tile of 32x32 MFMA tiles.
+  constexpr int NT = 128 * WGN;          // threads per workgroup
+  constexpr int RPP = NT / 8;            // tile rows covered by one pass of the loading threads
   constexpr int EPC = elem<ET>::per16;   // elements per 16-byte chunk
   constexpr int BKE = 8 * EPC;           // K elements per LDS slice (128 bytes per row)
   constexpr int LSTR = 144;              // LDS row stride in bytes (128 + 16 pad)
-  constexpr int AR = BM / 32, BR = BN / 32;
-  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int AR = BM / RPP, BR = BN / RPP;
+  constexpr int TM = BM / 64, TN = BN / (32 * WGN);
+  static_assert(AR >= 1 && BR >= 1 && TN >= 1, "tile too small for this many waves");
   constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2);
   constexpr bool CS = (MODE >= M_CS1);
 
   constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int CSTR = BN * 4 + 32;      // epilogue staging row stride in bytes
-  static_assert(BM * CSTR <= 2 * STAGE_BYTES, "epilogue staging must fit in the two pipeline stages");
+  // dynamic LDS = max(two pipeline stages, epilogue staging); the launcher sizes it the same way
   extern __shared__ __align__(16) unsigned char smem[];  // two pipeline stages, reused by the epilogue
   __shared__ int s_row[BM];
   __shared__ int s_kgrp[CS ? kMaxGroups : 1];
   __shared__ int s_nkept;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int HW = a.H * a.W, SS = a.S * a.S;
   const int Hp = a.H / a.S, Wp = a.W / a.S;
   const ET* __restrict__ Ap = (const ET*)a.A;
   const ET* __restrict__ Wp_ = (const ET*)a.Wt;
-
   // ---- which tile ---------------------------------------------------------------------------
   int rt, ct, sample = 0, M;
+  const int32_t* listp = a.list;
   if constexpr (!CS) {
     // XCD-aware decode: consecutive workgroup ids go round-robin over the 8 XCDs, so the column
     // tiles of one row tile (same A rows) are given to the same XCD, one after the other.
@@ -138,8 +143,15 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     rt = (s / a.col_tiles) * 8 + xcd;
     ct = s % a.col_tiles;
     if (rt >= a.row_tiles) return;
-    const int cnt = *a.count;
-    M = (MODE == M_CONV1) ? cnt : cnt * SS;
+    if constexpr (MODE == M_CONV1) {
+      // the dilated pixel lists are per group of samples: tile -> (group, tile within the group)
+      const int g = rt / a.tiles_per_group;
+      rt -= g * a.tiles_per_group;
+      listp += (size_t)g * a.group_rows;
+      M = a.count[g];
+    } else {
+      M = *a.count * SS;
+    }
   } else {
     rt = blockIdx.x % a.row_tiles;
     ct = blockIdx.x / a.row_tiles;
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   // one pointer select: a chunk that must read as zero (tap outside the image, row past the end,
   // K tail) is loaded from a page of zeros, so nothing has to be masked afterwards.
   const int cc = tid & 7;    // 16-byte chunk within the 128-byte K slice
-  const int lr = tid >> 3;   // 0..31: first row this thread loads
+  const int lr = tid >> 3;   // first row this thread loads
   // Hide where the zero page's address comes from (knowing that it is a dereferenceable global, the
   // compiler would split `load(ok ? row : zeros)` into two loads under a branch) but keep the fact
   // that it is global memory, so that the loads stay global_load (vmcnt only) and not flat_load.
@@ -190,14 +202,14 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   unsigned amask[AR];        // tap modes: bit t set = tap t readable; other modes: bit 0 = row valid
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
-    const int rho = row0 + lr + 32 * i;
+    const int rho = row0 + lr + RPP * i;
     arow[i] = Ap;
     amask[i] = 0;
     if (rho < M) {
       size_t pixrow;  // row of A (pixel id or compact row)
       int y = 0, x = 0;
       if constexpr (MODE == M_CONV1) {
-        pixrow = (size_t)a.list[rho];
+        pixrow = (size_t)listp[rho];
       } else if constexpr (MODE == M_CONV3) {
         pixrow = (size_t)rho;
       } else if constexpr (MODE == M_CONV2) {
@@ -234,7 +246,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     int o = -1;
     if (rho < M) {
       if constexpr (MODE == M_CONV1) {
-        o = a.list[rho];
+        o = listp[rho];
       } else if constexpr (MODE == M_CONV2) {
         o = rho;
       } else if constexpr (MODE == M_CONV3) {
@@ -255,14 +267,13 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   bool cvalid[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
-    const int c = col0 + lr + 32 * i;
+    const int c = col0 + lr + RPP * i;
     cvalid[i] = c < ncols;
     int wr = cvalid[i] ? c : col0;  // a column past the end re-reads the tile's first row: its result is dropped
     if constexpr (MODE == M_CS1 || MODE == M_CS2) wr = s_kgrp[wr / a.G] * a.G + (wr % a.G);
     wrow[i] = Wp_ + (size_t)wr * a.ldw;
     if constexpr (!(MODE == M_CS2 || MODE == M_CS3)) wrow[i] += cc * EPC;
   }
-
   const int kchunks = (keff + BKE - 1) / BKE;
   const int KT = (TAPS ? 9 : 1) * kchunks;
   const bool kvec = (a.G % EPC) == 0;  // kept-channel gather can use 16-byte loads
@@ -277,7 +288,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     const int kbase = ld_kc * BKE;          // wave-uniform first K element of the slice
     const int ke = kbase + cc * EPC;        // this thread's first (compact) K element
     ke_out = ke;
-    const bool kv = ke < keff;
+    const bool kv = ke < keff && tap < (TAPS ? 9 : 1);  // slices past the end read as zeros
     // wave-uniform element offsets of this slice relative to the row base pointers
     const long long aoff = TAPS ? (long long)(ld_ky * gW + ld_kx) * glda + kbase : (long long)kbase;
     const long long woff = (long long)tap * gK + kbase;
@@ -319,10 +330,10 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
           v = u32x4{t.x, t.y, t.z, t.w};
         }
       }
-      *reinterpret_cast<u32x4*>(sA + (lr + 32 * i) * LSTR + cc * 16) = v;
+      *reinterpret_cast<u32x4*>(sA + (lr + RPP * i) * LSTR + cc * 16) = v;
     }
 #pragma unroll
-    for (int i = 0; i < BR; ++i) *reinterpret_cast<u32x4*>(sB + (lr + 32 * i) * LSTR + cc * 16) = rb[i];
+    for (int i = 0; i < BR; ++i) *reinterpret_cast<u32x4*>(sB + (lr + RPP * i) * LSTR + cc * 16) = rb[i];
   };
 
   f32x16 acc[TM][TN];
@@ -335,7 +346,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 
   auto compute = [&](int buf) __attribute__((always_inline)) {
     const unsigned char* pa = smem + buf * STAGE_BYTES + (wm * (BM / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
-    const unsigned char* pb = smem + buf * STAGE_BYTES + A_BYTES + (wn * (BN / 2) + (lane & 31)) * LSTR +
+    const unsigned char* pb = smem + buf * STAGE_BYTES + A_BYTES + (wn * (BN / WGN) + (lane & 31)) * LSTR +
                               (lane >> 5) * 16;
 #pragma unroll
     for (int kg = 0; kg < 4; ++kg) {
@@ -351,55 +362,48 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     }
   };
 
-  // Software pipeline: two LDS stages, two register sets.  While slice `it` is multiplied out of LDS
-  // stage it%2, slice it+1 moves from registers to the other stage and slices it+2 / it+3 are in
-  // flight from L2 / HBM: one barrier per K slice, two slices of load latency covered.
-  u32x4 ra0[AR], rb0[BR], ra1[AR], rb1[BR];
-  int k0 = 0, k1 = 0;
-  if (KT >= 3) {
-    load_slice(ra0, rb0, k0);
-    load_slice(ra1, rb1, k1);
-    store_slice(0, ra0, rb0, k0);
-    load_slice(ra0, rb0, k0);
-    __syncthreads();  // also publishes s_row
-    int it = 0;
-    for (; it + 4 < KT; it += 2) {  // steady state: nothing conditional
-      store_slice(1, ra1, rb1, k1);
-      load_slice(ra1, rb1, k1);
-      compute(0);
-      __syncthreads();
-      store_slice(0, ra0, rb0, k0);
-      load_slice(ra0, rb0, k0);
-      compute(1);
-      __syncthreads();
+  // Residual prefetch (scatter-add modes): the 16-byte chunks this thread will add in the epilogue
+  // are requested now, so their latency hides behind the K loop.
+  constexpr int CPR = BN / EPC;                 // 16-byte output chunks per tile row
+  constexpr int EPI = (BM * CPR + NT - 1) / NT;  // epilogue chunks per thread
+  constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3);
+  // Software pipeline: PF register sets hold the slices in flight from L2 / HBM, two LDS stages.
+  // Step s multiplies slice s out of stage s%2 while slice s+1 moves from its registers to the other
+  // stage and slices s+2 .. s+PF are in flight: one barrier per slice, PF-1 slices of load latency
+  // covered.  Every step is identical -- slices past the end are loaded from the zero page and add
+  // nothing -- so the loop carries no conditional loads and the compiler's load counting holds.
+  constexpr int PF = 2;
+  static_assert(PF % 2 == 0, "stage parity must be static per unrolled step");
+  u32x4 ra[PF][AR], rb[PF][BR];
+  int kes[PF];
+#pragma unroll
+  for (int d = 0; d < PF; ++d) load_slice(ra[d], rb[d], kes[d]);
+  store_slice(0, ra[0], rb[0], kes[0]);
+  load_slice(ra[0], rb[0], kes[0]);
+  __syncthreads();  // stage 0 is ready; also publishes s_row
+  constexpr bool RES_EARLY = false;  // request the residual before the K loop instead of in the epilogue
+  u32x4 resv[RES ? EPI : 1];
+  if constexpr (RES && RES_EARLY) {
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+      const int id = tid + q * NT;
+      const int rl = id / CPR, chk = id - rl * CPR;
+      const int orow = (id < BM * CPR) ? s_row[rl] : -1;
+      const int col = col0 + chk * EPC;
+      const bool ok = orow >= 0 && col + EPC <= ncols;
+      resv[q] = *(ok ? (gptr16)((const ET*)a.Res + (size_t)orow * a.ldo + col) : zpage);
     }
-    // drain: three or four slices are left; slice it is in stage 0, it+1 in set 1, it+2 in set 0
-    const bool four = it + 3 < KT;
-    store_slice(1, ra1, rb1, k1);
-    if (four) load_slice(ra1, rb1, k1);
-    compute(0);
-    __syncthreads();
-    store_slice(0, ra0, rb0, k0);
-    compute(1);
-    __syncthreads();
-    if (four) store_slice(1, ra1, rb1, k1);
-    compute(0);
-    __syncthreads();
-    if (four) {
-      compute(1);
-      __syncthreads();
-    }
-  } else {  // one or two slices (or none): no pipeline
-    __syncthreads();
-    for (int it = 0; it < KT; ++it) {
-      load_slice(ra0, rb0, k0);
-      store_slice(0, ra0, rb0, k0);
-      __syncthreads();
-      compute(0);
+  }
+  for (int s0 = 0; s0 < KT; s0 += PF) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) {
+      const int nx = (d + 1) % PF;            // register set of slice s0+d+1
+      store_slice((d + 1) & 1, ra[nx], rb[nx], kes[nx]);
+      load_slice(ra[nx], rb[nx], kes[nx]);
+      compute(d & 1);
       __syncthreads();
     }
   }
-
   // ---- epilogue ---------------------------------------------------------------------------------
   // Affine (+ReLU) in the accumulator layout (32x32 tile: lane l holds column l%32, rows
   // 8*(e/4) + 4*(l/32) + e%4), then through LDS so that global traffic is 16 bytes per lane:
@@ -408,7 +412,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     float* stg = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int cl = wn * (BN / 2) + j * 32 + (lane & 31);
+      const int cl = wn * (BN / WGN) + j * 32 + (lane & 31);
       const int col = col0 + cl;
       float sc = 0.f, sh = 0.f;
       if (col < ncols) {
@@ -433,9 +437,10 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   {
     ET* Op = (ET*)a.Out;
     const ET* Rp = (const ET*)a.Res;
-    constexpr int CPR = BN / EPC;  // 16-byte output chunks per tile row
-    constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3);
-    for (int id = tid; id < BM * CPR; id += 256) {
+#pragma unroll
+    for (int q = 0; q < EPI; ++q) {
+      const int id = tid + q * NT;
+      if (id >= BM * CPR) continue;
       const int rl = id / CPR, chk = id - rl * CPR;
       const int orow = s_row[rl];
       const int col = col0 + chk * EPC;
@@ -443,16 +448,16 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
       const float* sp = reinterpret_cast<const float*>(smem + rl * CSTR) + chk * EPC;
       float v[EPC];
 #pragma unroll
-      for (int q = 0; q < EPC / 4; ++q) {
-        const float4 t4 = reinterpret_cast<const float4*>(sp)[q];
-        v[4 * q] = t4.x; v[4 * q + 1] = t4.y; v[4 * q + 2] = t4.z; v[4 * q + 3] = t4.w;
+      for (int u = 0; u < EPC / 4; ++u) {
+        const float4 t4 = reinterpret_cast<const float4*>(sp)[u];
+        v[4 * u] = t4.x; v[4 * u + 1] = t4.y; v[4 * u + 2] = t4.z; v[4 * u + 3] = t4.w;
       }
       const size_t off = (size_t)orow * a.ldo + col;
       if (col + EPC <= ncols) {
         if constexpr (RES) {
-          const uint4 rraw = *reinterpret_cast<const uint4*>(Rp + off);
+          if constexpr (!RES_EARLY) resv[q] = *(gptr16)(Rp + off);
           ET rr[EPC];
-          __builtin_memcpy(rr, &rraw, 16);
+          __builtin_memcpy(rr, &resv[q], 16);
 #pragma unroll
           for (int e = 0; e < EPC; ++e) {
             v[e] += elem<ET>::load(&rr[e]);
@@ -491,61 +496,63 @@ __device__ __forceinline__ int lower_bound_dev(const int32_t* v, int n, int key)
   return lo;
 }
 
-// One block per sample.  WRITE = false: count the sample's needed pixels; WRITE = true: write their
-// ids in ascending order at the exclusive prefix of the counts (ordered, no atomics) and, in the
-// last block, the total.  The sample's patch mask is rebuilt in LDS from the sorted index list.
-template <bool WRITE>
-__global__ __launch_bounds__(256) void k_need(const int32_t* __restrict__ idx, const int32_t* __restrict__ count,
-                                              int N, int H, int W, int S, int32_t* __restrict__ need_counts,
-                                              int32_t* __restrict__ pix, int32_t* __restrict__ total) {
-  extern __shared__ unsigned char s_pm[];  // [Hp*Wp] patch mask of this sample
-  __shared__ int wcnt[4], woff[4], s_tot, s_base;
-  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// One block per group of `gs` consecutive samples: writes the ids of the group's needed pixels in
+// ascending order at pix[g*gs*H*W ...] and their number at need_counts[g] (ordered, no atomics, no
+// dependency between blocks).  The group's patch mask is rebuilt in LDS from the sorted index list.
+constexpr int kNeedThreads = 1024;
+__global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict__ idx,
+                                                       const int32_t* __restrict__ count, int N, int H, int W, int S,
+                                                       int gs, int32_t* __restrict__ need_counts,
+                                                       int32_t* __restrict__ pix) {
+  extern __shared__ unsigned char s_pm[];  // [ns*Hp*Wp] patch masks of the group's samples
+  constexpr int NW = kNeedThreads / kWave;
+  __shared__ int wcnt[NW], woff[NW], s_tot;
+  const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Hp = H / S, Wp = W / S, pps = Hp * Wp, HW = H * W;
+  const int n0 = g * gs, ns = min(gs, N - n0);
   const int cnt = *count;
-  for (int i = tid; i < pps; i += 256) s_pm[i] = 0;
-  if (WRITE && tid < 64) {
-    int part = 0;
-    for (int b = tid; b < n; b += 64) part += need_counts[b];
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
-    if (tid == 0) s_base = part;
+  for (int i = tid; i < ns * pps; i += kNeedThreads) s_pm[i] = 0;
+  __syncthreads();
+  // The group's slice of the sorted index list: short lists are scanned whole by all threads (a
+  // handful of independent loads each); a binary search costs a dozen dependent loads in a row.
+  int lo = 0, hi = cnt;
+  if (cnt > 16 * kNeedThreads) {
+    lo = lower_bound_dev(idx, cnt, n0 * pps);
+    hi = lower_bound_dev(idx, cnt, (n0 + ns) * pps);
+  }
+  for (int i = lo + tid; i < hi; i += kNeedThreads) {
+    const unsigned v = (unsigned)(idx[i] - n0 * pps);
+    if (v < (unsigned)(ns * pps)) s_pm[v] = 1;
   }
   __syncthreads();
-  const int lo = lower_bound_dev(idx, cnt, n * pps), hi = lower_bound_dev(idx, cnt, (n + 1) * pps);
-  for (int i = lo + tid; i < hi; i += 256) {
-    const unsigned v = (unsigned)(idx[i] - n * pps);
-    if (v < (unsigned)pps) s_pm[v] = 1;
-  }
-  __syncthreads();
-  int running = WRITE ? s_base : 0;
-  for (int p0 = 0; p0 < HW; p0 += 256) {
+  int32_t* out = pix + (size_t)g * gs * HW;
+  int running = 0;
+  for (int p0 = 0; p0 < ns * HW; p0 += kNeedThreads) {
     const int pp = p0 + tid;
     bool need = false;
-    if (pp < HW) {
-      const int y = pp / W, x = pp - y * W;
+    if (pp < ns * HW) {
+      const int ln = pp / HW, q = pp - ln * HW;
+      const int y = q / W, x = q - y * W;
       const int py0 = max(y - 1, 0) / S, py1 = min(y + 1, H - 1) / S;
       const int px0 = max(x - 1, 0) / S, px1 = min(x + 1, W - 1) / S;
+      const unsigned char* pm = s_pm + ln * pps;
       for (int py = py0; py <= py1; ++py)
-        for (int px = px0; px <= px1; ++px) need |= s_pm[py * Wp + px] != 0;
+        for (int px = px0; px <= px1; ++px) need |= pm[py * Wp + px] != 0;
     }
     const unsigned long long b = __ballot(need);
     if (lane == 0) wcnt[wave] = __popcll(b);
     __syncthreads();
     if (tid == 0) {
       int t = 0;
-      for (int w = 0; w < 4; ++w) { woff[w] = t; t += wcnt[w]; }
+      for (int w = 0; w < NW; ++w) { woff[w] = t; t += wcnt[w]; }
       s_tot = t;
     }
     __syncthreads();
-    if (WRITE && need) pix[running + woff[wave] + ballot_prefix(b)] = n * HW + pp;
+    if (need) out[running + woff[wave] + ballot_prefix(b)] = n0 * HW + pp;
     running += s_tot;
     __syncthreads();
   }
-  if (tid == 0) {
-    if (!WRITE) need_counts[n] = running;
-    else if (n == N - 1) *total = running;
-  }
+  if (tid == 0) need_counts[g] = running;
 }
 
 // Out-of-place call: pixels of inactive patches are copied bit for bit.  One block per patch.
@@ -569,51 +576,67 @@ __global__ __launch_bounds__(256) void k_copy_inactive(const uint4* __restrict__
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-struct Tile { int bm, bn; };
+struct Tile { int bm, bn, waves; };
 
-// Tile choice.  LAUD_TILE=BMxBN (64x64, 64x128, 128x128) overrides it for tuning runs.
-static Tile pick_tile(int ncols) {
-  static int env_bm = -1, env_bn = -1;
-  if (env_bm < 0) {
-    env_bm = 0; env_bn = 0;
+// Tile choice.  LAUD_TILE=BMxBNxWAVES (64x64x4, 64x128x4, 128x128x4, 64x128x8, 128x128x8) overrides it
+// for tuning runs.
+static Tile pick_tile(int ncols, long long total_rows) {
+  static Tile env = {-1, 0, 0};
+  if (env.bm < 0) {
+    env = {0, 0, 0};
     if (const char* e = std::getenv("LAUD_TILE")) {
-      int bm = 0, bn = 0;
-      if (std::sscanf(e, "%dx%d", &bm, &bn) == 2 &&
-          ((bm == 64 && bn == 64) || (bm == 64 && bn == 128) || (bm == 128 && bn == 128))) {
-        env_bm = bm; env_bn = bn;
-      }
+      int bm = 0, bn = 0, w = 4;
+      const int got = std::sscanf(e, "%dx%dx%d", &bm, &bn, &w);
+      const bool ok4 = (bm == 64 && bn == 64) || (bm == 64 && bn == 128) || (bm == 128 && bn == 128);
+      const bool ok8 = (bm == 64 && bn == 128) || (bm == 128 && bn == 128) || (bm == 64 && bn == 256) ||
+                       (bm == 128 && bn == 256);
+      if (got >= 2 && ((w == 4 && ok4) || (w == 8 && ok8))) env = {bm, bn, w};
     }
   }
-  if (env_bm > 0) return {env_bm, env_bn};
-  return {64, ncols >= 128 ? 128 : 64};
+  if (env.bm > 0) return env;
+  if (ncols < 128) return {64, 64, 4};
+  // eight waves hide each other's LDS and load stalls; the large tile needs enough rows to fill the chip
+  return total_rows >= 8192 ? Tile{128, 128, 8} : Tile{64, 128, 8};
 }
 
-template <int MODE, typename ET, int BM, int BN>
+template <int MODE, typename ET, int BM, int BN, int WGN>
 static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream_t st) {
   constexpr bool CS = (MODE >= M_CS1);
   a.row_tiles = (int)((cap_rows + BM - 1) / BM);
+  if constexpr (MODE == M_CONV1) {  // cap_rows = rows per group of samples, nsamples = number of groups
+    a.tiles_per_group = a.row_tiles;
+    a.row_tiles *= nsamples;
+  }
   a.col_tiles = (a.Ncols + BN - 1) / BN;
   dim3 grid;
   if (!CS) grid = dim3((unsigned)(((a.row_tiles + 7) / 8) * 8 * a.col_tiles));
   else grid = dim3((unsigned)(a.row_tiles * a.col_tiles), (unsigned)nsamples);
-  constexpr int kLds = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
+  constexpr int kStages = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
+  constexpr int kStaging = BM * (BN * 4 + 32);  // fp32 tile the epilogue transposes through
+  constexpr int kLds = kStages > kStaging ? kStages : kStaging;
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be requested once per kernel
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN, WGN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess)
       return LAUD_ERR_HIP;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN>), grid, dim3(256), kLds, st, a);
+  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN, WGN>), grid, dim3(128 * WGN), kLds, st, a);
   return check_launch();
 }
 
 template <int MODE, typename ET>
 static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  const Tile t = pick_tile(a.Ncols);
-  if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128>(a, cap_rows, nsamples, st);
-  if (t.bn == 128) return launch_gemm_t<MODE, ET, 64, 128>(a, cap_rows, nsamples, st);
-  return launch_gemm_t<MODE, ET, 64, 64>(a, cap_rows, nsamples, st);
+  const Tile t = pick_tile(a.Ncols, cap_rows * (MODE == M_CONV1 || MODE >= M_CS1 ? nsamples : 1));
+  if (t.waves == 8) {
+    if (t.bn == 256 && t.bm == 128) return launch_gemm_t<MODE, ET, 128, 256, 4>(a, cap_rows, nsamples, st);
+    if (t.bn == 256) return launch_gemm_t<MODE, ET, 64, 256, 4>(a, cap_rows, nsamples, st);
+    if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128, 4>(a, cap_rows, nsamples, st);
+    return launch_gemm_t<MODE, ET, 64, 128, 4>(a, cap_rows, nsamples, st);
+  }
+  if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128, 2>(a, cap_rows, nsamples, st);
+  if (t.bn == 128) return launch_gemm_t<MODE, ET, 64, 128, 2>(a, cap_rows, nsamples, st);
+  return launch_gemm_t<MODE, ET, 64, 64, 2>(a, cap_rows, nsamples, st);
 }
 
 template <int MODE>
@@ -703,7 +726,6 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   clear_stale_error();
   char* wsb = (char*)ws;
   int32_t* need_counts = (int32_t*)(wsb + L.need_counts);
-  int32_t* total = (int32_t*)(wsb + L.total);
   int32_t* pix = (int32_t*)(wsb + L.pix);
   void* h1 = wsb + L.h1;
   void* h2 = wsb + L.h2;
@@ -716,13 +738,17 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
                        (uint4*)out, fx.H, fx.W, S, cpp, idx, count);
     if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
   }
-  const size_t pm_bytes = align_up((size_t)Hp * Wp, 16);
+  // samples per group of the dilated pixel lists: about 1.5k pixels, so that a group's ragged last
+  // conv1 tile wastes little, and its patch masks fit in LDS
+  const int hw = fx.H * fx.W, pps = Hp * Wp;
+  int gs = (1536 + hw - 1) / hw;
+  if (gs > fx.N) gs = fx.N;
+  while (gs > 1 && (size_t)gs * pps > 60000) --gs;
+  const int ngroups = (fx.N + gs - 1) / gs;
   {
     StageScope scope(LAUD_STAGE_NEED, st);
-  hipLaunchKernelGGL((k_need<false>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
-                     need_counts, pix, total);
-  hipLaunchKernelGGL((k_need<true>), dim3(fx.N), dim3(256), pm_bytes, st, idx, count, fx.N, fx.H, fx.W, S,
-                     need_counts, pix, total);
+    hipLaunchKernelGGL(k_need, dim3(ngroups), dim3(kNeedThreads), align_up((size_t)gs * pps, 16), st, idx, count,
+                       fx.N, fx.H, fx.W, S, gs, need_counts, pix);
   }
   if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
 
@@ -730,9 +756,9 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.cmask = nullptr;
   // conv1: gathered 1x1 over the dilated active set -> h1 at pixel positions
   a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
-  a.count = total; a.list = pix; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
+  a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
-  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
   // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;

@@ -90,6 +90,58 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
   }
 }
 
+// Small masks (a few thousand entries: one stage's patch grid, a batch of layer gates): one block
+// does the whole ordered compaction in one launch.  Each thread owns four consecutive entries per
+// pass; four ballots give the in-wave prefix (mbcnt), an LDS scan over the 16 waves the rest.
+constexpr int kSmallCompactMax = 8 * kCompactBlock;  // 32768 entries
+__global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t* __restrict__ mask, int n,
+                                                                   int32_t* __restrict__ idx,
+                                                                   int32_t* __restrict__ count,
+                                                                   int32_t* __restrict__ sample_offsets,
+                                                                   int per_sample) {
+  __shared__ int wsum[kCompactThreads / kWave];
+  __shared__ int woff[kCompactThreads / kWave];
+  __shared__ int s_tot;
+  const int wave = threadIdx.x / kWave, lane = lane_id();
+  int running = 0;
+  for (int base = 0; base < n; base += 4 * kCompactThreads) {
+    const int i0 = base + 4 * (int)threadIdx.x;
+    bool f[4];
+    unsigned long long b[4];
+    int before = 0, mine = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f[j] = (i0 + j < n) && mask[i0 + j] != 0;
+      b[j] = __ballot(f[j]);
+      before += ballot_prefix(b[j]);  // set entries of lower lanes at position j
+    }
+    int wtot = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
+    if (lane == 0) wsum[wave] = wtot;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
+      s_tot = t;
+    }
+    __syncthreads();
+    int pos = running + woff[wave] + before;  // set entries before (this thread, position 0)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = i0 + j;
+      if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
+      if (f[j]) { idx[pos + mine] = i; ++mine; }
+    }
+    running += s_tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *count = running;
+    if (sample_offsets) sample_offsets[n / per_sample] = running;
+  }
+}
+
 __global__ void k_write_zero_count(int32_t* count, int32_t* sample_offsets) {
   *count = 0;
   if (sample_offsets) sample_offsets[0] = 0;
@@ -100,6 +152,11 @@ int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int
   StageScope scope(LAUD_STAGE_COMPACT, stream);
   if (n == 0) {
     hipLaunchKernelGGL(k_write_zero_count, dim3(1), dim3(1), 0, stream, count, sample_offsets);
+    return check_launch();
+  }
+  if (n <= kSmallCompactMax) {
+    hipLaunchKernelGGL(k_compact_small, dim3(1), dim3(kCompactThreads), 0, stream, mask, n, idx, count,
+                       sample_offsets, per_sample > 0 ? per_sample : 1);
     return check_launch();
   }
   const int nb = (n + kCompactBlock - 1) / kCompactBlock;
@@ -138,24 +195,38 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
     const int py = r / Wp, px = r - py * Wp;
     const int cpr = C / EPC;          // chunks per pixel row
     const int total = S * S * cpr;    // chunks per patch
-    for (int c = tl; c < total; c += TEAM) {
+    // Four 16-byte loads of x are put in flight before any of them is consumed: the kernel is a pure
+    // stream over x and what bounds it is the number of bytes in flight per CU.
+    auto chunk_ptr = [&](int c) -> const uint4* {
       const int j = c / cpr, cv = c - j * cpr;
       const int dy = j / S, dx = j - dy * S;
       const size_t pix = ((size_t)n * H + (py * S + dy)) * W + (px * S + dx);
-      const uint4 raw = *reinterpret_cast<const uint4*>(x + pix * C + (size_t)cv * EPC);
+      return reinterpret_cast<const uint4*>(x + pix * C + (size_t)cv * EPC);
+    };
+    auto dot = [&](const uint4& raw, int c) -> float {
+      const int cv = c % cpr;
       const float4* wp = reinterpret_cast<const float4*>(w + cv * EPC);
       if constexpr (EPC == 4) {
         const float4 wv = wp[0];
-        acc += __uint_as_float(raw.x) * wv.x + __uint_as_float(raw.y) * wv.y + __uint_as_float(raw.z) * wv.z +
+        return __uint_as_float(raw.x) * wv.x + __uint_as_float(raw.y) * wv.y + __uint_as_float(raw.z) * wv.z +
                __uint_as_float(raw.w) * wv.w;
       } else {
         const float4 w0 = wp[0], w1 = wp[1];
-        acc += __uint_as_float(raw.x << 16) * w0.x + __uint_as_float(raw.x & 0xffff0000u) * w0.y +
+        return __uint_as_float(raw.x << 16) * w0.x + __uint_as_float(raw.x & 0xffff0000u) * w0.y +
                __uint_as_float(raw.y << 16) * w0.z + __uint_as_float(raw.y & 0xffff0000u) * w0.w +
                __uint_as_float(raw.z << 16) * w1.x + __uint_as_float(raw.z & 0xffff0000u) * w1.y +
                __uint_as_float(raw.w << 16) * w1.z + __uint_as_float(raw.w & 0xffff0000u) * w1.w;
       }
+    };
+    int c = tl;
+    for (; c + 3 * TEAM < total; c += 4 * TEAM) {
+      uint4 r[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) r[u] = *chunk_ptr(c + u * TEAM);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc += dot(r[u], c + u * TEAM);
     }
+    for (; c < total; c += TEAM) acc += dot(*chunk_ptr(c), c);
   }
   acc = wave_sum(acc);
   if constexpr (TEAM > kWave) {
@@ -211,7 +282,7 @@ using namespace laud;
 extern "C" int laud_layer_skip_compact(const uint8_t* keep, int n, int32_t* idx, int32_t* count, void* ws,
                                        size_t ws_bytes, void* stream) {
   if (n < 0 || !count || (n > 0 && (!keep || !idx))) return LAUD_ERR_INVALID_ARG;
-  if (n > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(n))) return LAUD_ERR_WORKSPACE;
+  if (n > kSmallCompactMax && (!ws || ws_bytes < compact_ws_bytes(n))) return LAUD_ERR_WORKSPACE;
   clear_stale_error();
   return launch_compact(keep, n, idx, count, nullptr, 1, (int32_t*)ws, (hipStream_t)stream);
 }
@@ -224,7 +295,7 @@ extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w,
   if (fx.C % 8) return LAUD_ERR_UNSUPPORTED;
   const long long npatch = (long long)fx.N * (fx.H / S) * (fx.W / S);
   if (npatch > 0x7fffffffLL || (long long)fx.N * fx.H * fx.W > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
-  if (npatch > kCompactBlock && (!ws || ws_bytes < compact_ws_bytes(npatch))) return LAUD_ERR_WORKSPACE;
+  if (npatch > kSmallCompactMax && (!ws || ws_bytes < compact_ws_bytes(npatch))) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
   const size_t patch_bytes = (size_t)S * S * fx.C * elem_bytes(fx.dtype);
