@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the conv2 kernel at the default workload (batch 128, ratio 0.5), from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/bench_config2_r050_pmc.txt
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors from a plain copy of known size).
+CONV2_TRAFFIC_BYTES_R050_B128 = 28.2e6
 
 
 def parse():
@@ -144,7 +148,8 @@ def main():
     achieved = conv2_flops / (conv2_us * 1e-6) / 1e12
     roofline = {"bound": "mfma", "kernel": "k_gemm<CONV2,bf16> (3x3 implicit GEMM on active patches)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": CONV2_TRAFFIC_BYTES_R050_B128 if (abs(a.ratio - 0.5) < 1e-9 and N == 128) else None,
                 "flops_per_launch": conv2_flops, "avg_us": round(conv2_us, 2)}
 
     # ---- latency vs activation ratio -------------------------------------------------------------
@@ -194,10 +199,14 @@ def main():
         ns = min(4, N)
         dt0 = oracle_pass(ns)
         ns2 = int(max(ns, min(N, ns * 12.0 / max(dt0, 1e-3))))
-        dt1 = oracle_pass(ns2) if ns2 > ns else dt0
-        cpu = {"value": round(ns2 / dt1, 2), "unit": "images/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {ns2} of {N} images of the same batch, one pass of masker + index list + "
-                         f"dense-then-mask block in numpy float64 ({dt1:.1f} s)"}
+        # about 10 s of CPU work: the whole batch takes under a second, so the pass is repeated
+        reps, spent = 0, 0.0
+        while spent < 10.0 and reps < 50:
+            spent += oracle_pass(ns2)
+            reps += 1
+        cpu = {"value": round(ns2 * reps / spent, 2), "unit": "images/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {ns2} of {N} images of the same batch, {reps} passes of masker + index list + "
+                         f"dense-then-mask block in numpy float64 ({spent:.1f} s in all)"}
 
     out = {
         "metric": "dynamic-bottleneck images/sec (mask_gen + dyn_bottleneck, stage-3 block, batch 128) "
