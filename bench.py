@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--sweep-steps", type=int, default=40, help="steps per ratio of the latency-vs-ratio sweep (0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=128)
+    ap.add_argument("--variant", choices=["fused", "two-call"], default="fused",
+                    help="fused: laud_masker_dyn_bottleneck (masker fused into a static conv1); "
+                         "two-call: laud_mask_gen + laud_dyn_bottleneck (sparse conv1)")
     return ap.parse_args()
 
 
@@ -96,9 +99,14 @@ def main():
     logits0 = lg.cpu().numpy()
     bias_of = {r: I.bias_for_ratio(logits0, r)[0] for r in (0.0, 0.25, 0.5, 0.75, 1.0, a.ratio)}
 
+    variant = [a.variant]
+
     def step(buf, bias):
-        L.laud_mask_gen(buf, fx, S, wd, bias, None, mask, idx, cnt, None, None, wsm)
-        L.laud_dyn_bottleneck(buf, fx, db.desc, S, idx, cnt, buf, ws)
+        if variant[0] == "fused":
+            L.laud_masker_dyn_bottleneck(buf, fx, db.desc, S, wd, bias, None, mask, idx, cnt, None, None, buf, ws)
+        else:
+            L.laud_mask_gen(buf, fx, S, wd, bias, None, mask, idx, cnt, None, None, wsm)
+            L.laud_dyn_bottleneck(buf, fx, db.desc, S, idx, cnt, buf, ws)
 
     def timed(bias, steps, warmup, per_step_events=False):
         for i in range(warmup):
@@ -151,6 +159,15 @@ def main():
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": CONV2_TRAFFIC_BYTES_R050_B128 if (abs(a.ratio - 0.5) < 1e-9 and N == 128) else None,
                 "flops_per_launch": conv2_flops, "avg_us": round(conv2_us, 2)}
+
+    # ---- the other variant, for context (p50 only) ----------------------------------------------------
+    other = "two-call" if a.variant == "fused" else "fused"
+    variant[0] = other
+    ko = min(40, a.steps)
+    restore(ko + min(a.warmup, 5))
+    _, _, lato = timed(bias, ko, min(a.warmup, 5), per_step_events=True)
+    other_p50 = lato[len(lato) // 2]
+    variant[0] = a.variant
 
     # ---- latency vs activation ratio -------------------------------------------------------------
     sweep = []
@@ -209,16 +226,19 @@ def main():
                          f"dense-then-mask block in numpy float64 ({spent:.1f} s in all)"}
 
     out = {
-        "metric": "dynamic-bottleneck images/sec (mask_gen + dyn_bottleneck, stage-3 block, batch 128) "
-                  "at activation ratio %.2f; p50 latency vs ratio and MFMA fraction in 'sweep'" % a.ratio,
+        "metric": "dynamic-bottleneck images/sec (masker + index list + dynamic bottleneck, stage-3 block, "
+                  "batch 128) at activation ratio %.2f; p50 latency vs ratio and MFMA fraction in 'sweep'" % a.ratio,
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "BASELINE config 2: stage-3 dynamic bottleneck, x 128x14x14x1024 NHWC bf16, "
                                "mid 256, S=2 (7x7 patch grid), mask from the pooled 1x1 masker, bias calibrated "
-                               "to the target ratio; in place; one pristine cache-cold copy of x per step",
+                               "to the target ratio; in place; one pristine cache-cold copy of x per step; entry point: "
+                               + ("laud_masker_dyn_bottleneck" if a.variant == "fused"
+                                  else "laud_mask_gen + laud_dyn_bottleneck"),
                    "global_batch": N, "activation_ratio": round(P / npatch, 4), "active_patches": P},
         "p50_us": round(p50 * 1e3, 1),
+        "other_variant": {"variant": other, "p50_us": round(other_p50 * 1e3, 1)},
         "mfma_frac_useful_flops": round(useful_flops(P) / (p50 * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
         "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
         "roofline": roofline,

@@ -144,6 +144,23 @@ int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, i
                         void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same block with the masker fused into the first 1x1 (Sec. 3.4 "Operator fusion for spatial
+ * maskers"; App. B item 1): conv1 is evaluated on EVERY pixel (spatially static) and the masker's
+ * per-pixel projection sum_c w[c]*x[n,y,x,c] is accumulated from the same reads of x; the
+ * projection is pooled over S x S patches, thresholded and turned into the index list, and conv2 /
+ * conv3 + scatter-add run on the active patches as in laud_dyn_bottleneck.  One call replaces
+ * laud_mask_gen followed by laud_dyn_bottleneck and produces the same mask / idx / count /
+ * sample_offsets / logits outputs (same meaning, same optional NULLs) and the same `out`; logits
+ * differ from laud_mask_gen's only in float32 summation order.  It pays off when the dilated
+ * activation ratio is close to 1 (small S); c_in <= 4096.  Workspace: as LAUD_OP_DYN_BOTTLENECK.
+ */
+int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                               const float* w, float bias, const uint8_t* keep,
+                               uint8_t* mask, int32_t* idx, int32_t* count,
+                               int32_t* sample_offsets, float* logits, void* out,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Channel-skipping bottleneck (Fig. 2(c); Sec. 3.1-3.2).  cmask is [N][D] bytes; group g of
  * sample n covers mid channels [g*G, (g+1)*G), G = c_mid / D.  The mask multiplies the input
  * and the output of the 3x3 conv; dropped channels are never computed (the weight gather is

@@ -19,7 +19,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
-           "laud_channel_skip_conv", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+           "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
 STAGE_COUNT = 11
 
 
@@ -69,6 +69,9 @@ def load() -> C.CDLL:
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
     lib.laud_channel_skip_conv.restype = i32
     lib.laud_channel_skip_conv.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, i32, vp, vp, sz, vp]
+    lib.laud_masker_dyn_bottleneck.restype = i32
+    lib.laud_masker_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, C.c_float, vp, vp, vp, vp,
+                                               vp, vp, vp, vp, sz, vp]
     lib.laud_stage_timing_enable.restype = i32
     lib.laud_stage_timing_enable.argtypes = [i32]
     lib.laud_stage_timing_read.restype = i32
@@ -164,6 +167,14 @@ def laud_channel_skip_conv(x, fx: Fmap, p: Bottleneck, cmask, D: int, out, ws) -
     wp, wb = _ws_args(ws)
     _check(load().laud_channel_skip_conv(_ptr(x), fx, C.byref(p), _ptr(cmask), int(D), _ptr(out),
                                          wp, wb, _stream()), "laud_channel_skip_conv")
+
+
+def laud_masker_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, w, bias: float, keep, mask, idx, count,
+                               sample_offsets, logits, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_masker_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(w), float(bias), _ptr(keep),
+                                             _ptr(mask), _ptr(idx), _ptr(count), _ptr(sample_offsets), _ptr(logits),
+                                             _ptr(out), wp, wb, _stream()), "laud_masker_dyn_bottleneck")
 
 
 def laud_stage_timing_enable(on: bool) -> None:

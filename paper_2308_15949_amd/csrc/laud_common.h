@@ -77,6 +77,12 @@ inline size_t compact_ws_bytes(long long n) {
 int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int32_t* sample_offsets,
                    int per_sample, int32_t* block_counts, hipStream_t stream);
 
+// Pools a per-pixel masker projection over S x S patches, thresholds, and launches the ordered
+// compaction (one launch for small patch counts); see laud_mask.hip.
+int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bias, const uint8_t* keep, uint8_t* mask,
+                        float* logits, int32_t* idx, int32_t* count, int32_t* sample_offsets, int32_t* block_counts,
+                        hipStream_t stream);
+
 // Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
 extern bool g_stage_timing_on;
 void stage_mark(int stage, hipStream_t stream, bool begin);

@@ -13,6 +13,9 @@
 //          fetch by index, output patches stored densely); result h2 dense, patch-major.
 //   CONV3  rows = the dense h2 rows; epilogue reads the residual at the patch's position, adds,
 //          and stores at that position (Sec. 3.4 "Fusing scatter and add"; App. B item 3).
+//   DENSE1 conv1 on every pixel, with the one-channel masker's per-pixel projection computed from the
+//          same A slices (Sec. 3.4 "Operator fusion for spatial maskers"; App. B item 1): x is read
+//          once for both.
 //   CS1..3 the same three convs for channel skipping (Fig. 2(c)): one sample per blockIdx.y,
 //          output channels / reduction channels gathered through the sample's kept-group list,
 //          i.e. the weight gather is fused into the conv (Sec. 3.4).
@@ -30,7 +33,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk in global memory
 
-enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5 };
+enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6 };
 
 // 256 bytes of zeros in device memory: the source of every chunk that has to read as zero.  Not
 // declared const on purpose: the compiler must treat a load from it like any other load (it would
@@ -59,6 +62,9 @@ struct GemmArgs {
   int D, G;              // CS: groups per sample, channels per group
   int row_tiles, col_tiles;
   int group_rows, tiles_per_group;  // CONV1: pixel lists are kept per group of samples
+  int m_rows;            // DENSE1: number of rows (all pixels), known on the host
+  const float* wmask;    // DENSE1: masker weights [K] or null
+  float* proj;           // DENSE1: per-pixel masker projection sum_c w[c]*x[pixel][c], [m_rows]
 };
 
 // ---- one 16-byte fragment pair -> MFMA ------------------------------------------------------
@@ -117,11 +123,13 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   constexpr int TM = BM / 64, TN = BN / (32 * WGN);
   static_assert(AR >= 1 && BR >= 1 && TN >= 1, "tile too small for this many waves");
   constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2);
-  constexpr bool CS = (MODE >= M_CS1);
+  constexpr bool CS = (MODE >= M_CS1 && MODE <= M_CS3);
 
   constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int CSTR = BN * 4 + 32;      // epilogue staging row stride in bytes
-  // dynamic LDS = max(two pipeline stages, epilogue staging); the launcher sizes it the same way
+  // dynamic LDS = max(two pipeline stages, epilogue staging) [+ K floats of masker weights in DENSE1];
+  // the launcher sizes it the same way
+  constexpr int MAIN_BYTES = (2 * STAGE_BYTES > BM * CSTR) ? 2 * STAGE_BYTES : BM * CSTR;
   extern __shared__ __align__(16) unsigned char smem[];  // two pipeline stages, reused by the epilogue
   __shared__ int s_row[BM];
   __shared__ int s_kgrp[CS ? kMaxGroups : 1];
@@ -149,6 +157,8 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       rt -= g * a.tiles_per_group;
       listp += (size_t)g * a.group_rows;
       M = a.count[g];
+    } else if constexpr (MODE == M_DENSE1) {
+      M = a.m_rows;
     } else {
       M = *a.count * SS;
     }
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       int y = 0, x = 0;
       if constexpr (MODE == M_CONV1) {
         pixrow = (size_t)listp[rho];
-      } else if constexpr (MODE == M_CONV3) {
+      } else if constexpr (MODE == M_CONV3 || MODE == M_DENSE1) {
         pixrow = (size_t)rho;
       } else if constexpr (MODE == M_CONV2) {
         const int p = rho / SS, j = rho - p * SS;
@@ -247,7 +257,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     if (rho < M) {
       if constexpr (MODE == M_CONV1) {
         o = listp[rho];
-      } else if constexpr (MODE == M_CONV2) {
+      } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1) {
         o = rho;
       } else if constexpr (MODE == M_CONV3) {
         const int p = rho / SS, j = rho - p * SS;
@@ -274,6 +284,19 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     wrow[i] = Wp_ + (size_t)wr * a.ldw;
     if constexpr (!(MODE == M_CS2 || MODE == M_CS3)) wrow[i] += cc * EPC;
   }
+  // DENSE1: the first column tile also accumulates the masker projection of its rows, on the vector
+  // ALU, from the A chunks on their way from registers to LDS (each thread: AR rows x one chunk).
+  const bool do_proj = (MODE == M_DENSE1) && ct == 0 && a.wmask != nullptr;
+  float* const s_wm = reinterpret_cast<float*>(smem + MAIN_BYTES);  // masker weights (DENSE1 only)
+  float pacc[AR];
+#pragma unroll
+  for (int i = 0; i < AR; ++i) pacc[i] = 0.f;
+  if constexpr (MODE == M_DENSE1) {
+    if (do_proj)
+      for (int k = tid; k < a.K; k += NT) s_wm[k] = a.wmask[k];
+    __syncthreads();  // the first store_slice below already reads s_wm
+  }
+
   const int kchunks = (keff + BKE - 1) / BKE;
   const int KT = (TAPS ? 9 : 1) * kchunks;
   const bool kvec = (a.G % EPC) == 0;  // kept-channel gather can use 16-byte loads
@@ -331,6 +354,14 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         }
       }
       *reinterpret_cast<u32x4*>(sA + (lr + RPP * i) * LSTR + cc * 16) = v;
+      if constexpr (MODE == M_DENSE1) {
+        if (do_proj && ke < keff) {
+          ET xe[EPC];
+          __builtin_memcpy(xe, &v, 16);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) pacc[i] += elem<ET>::load(&xe[e]) * s_wm[ke + e];
+        }
+      }
     }
 #pragma unroll
     for (int i = 0; i < BR; ++i) *reinterpret_cast<u32x4*>(sB + (lr + RPP * i) * LSTR + cc * 16) = rb[i];
@@ -343,6 +374,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
 
   auto compute = [&](int buf) __attribute__((always_inline)) {
     const unsigned char* pa = smem + buf * STAGE_BYTES + (wm * (BM / 2) + (lane & 31)) * LSTR + (lane >> 5) * 16;
@@ -404,6 +436,20 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       __syncthreads();
     }
   }
+  if constexpr (MODE == M_DENSE1) {
+    if (do_proj) {
+#pragma unroll
+      for (int i = 0; i < AR; ++i) {
+        float v = pacc[i];  // partial over this thread's chunk column; the row's 8 chunk columns are 8 adjacent lanes
+        v += __shfl_xor(v, 1, kWave);
+        v += __shfl_xor(v, 2, kWave);
+        v += __shfl_xor(v, 4, kWave);
+        const int rho = row0 + lr + RPP * i;
+        if (cc == 0 && rho < M) a.proj[rho] = v;
+      }
+    }
+  }
+
   // ---- epilogue ---------------------------------------------------------------------------------
   // Affine (+ReLU) in the accumulator layout (32x32 tile: lane l holds column l%32, rows
   // 8*(e/4) + 4*(l/32) + e%4), then through LDS so that global traffic is 16 bytes per lane:
@@ -601,7 +647,7 @@ static Tile pick_tile(int ncols, long long total_rows) {
 
 template <int MODE, typename ET, int BM, int BN, int WGN>
 static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream_t st) {
-  constexpr bool CS = (MODE >= M_CS1);
+  constexpr bool CS = (MODE >= M_CS1 && MODE <= M_CS3);
   a.row_tiles = (int)((cap_rows + BM - 1) / BM);
   if constexpr (MODE == M_CONV1) {  // cap_rows = rows per group of samples, nsamples = number of groups
     a.tiles_per_group = a.row_tiles;
@@ -617,17 +663,18 @@ static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be requested once per kernel
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN, WGN>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds + (MODE == M_DENSE1 ? 4096 * 4 : 0)) != hipSuccess)
       return LAUD_ERR_HIP;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN, WGN>), grid, dim3(128 * WGN), kLds, st, a);
+  const int lds = kLds + ((MODE == M_DENSE1 && a.wmask) ? a.K * 4 : 0);  // + masker weights
+  hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN, WGN>), grid, dim3(128 * WGN), lds, st, a);
   return check_launch();
 }
 
 template <int MODE, typename ET>
 static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  const Tile t = pick_tile(a.Ncols, cap_rows * (MODE == M_CONV1 || MODE >= M_CS1 ? nsamples : 1));
+  const Tile t = pick_tile(a.Ncols, cap_rows * (MODE == M_CONV1 || (MODE >= M_CS1 && MODE <= M_CS3) ? nsamples : 1));
   if (t.waves == 8) {
     if (t.bn == 256 && t.bm == 128) return launch_gemm_t<MODE, ET, 128, 256, 4>(a, cap_rows, nsamples, st);
     if (t.bn == 256) return launch_gemm_t<MODE, ET, 64, 256, 4>(a, cap_rows, nsamples, st);
@@ -641,8 +688,8 @@ static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hi
 
 template <int MODE>
 static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  constexpr int kStage[6] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
-                             LAUD_STAGE_CS1, LAUD_STAGE_CS2, LAUD_STAGE_CS3};
+  constexpr int kStage[7] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
+                             LAUD_STAGE_CS1, LAUD_STAGE_CS2, LAUD_STAGE_CS3, LAUD_STAGE_CONV1};
   StageScope scope(kStage[MODE], st);
   return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
@@ -664,7 +711,7 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   return LAUD_OK;
 }
 
-struct DynWs { size_t need_counts, total, pix, h1, h2, bytes; };
+struct DynWs { size_t need_counts, total, pix, h1, h2, blocks, bytes; };
 static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
   DynWs w;
@@ -674,6 +721,7 @@ static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   w.pix = o;         o += align_up(npix * 4, 256);
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(npix * c_mid * eb, 256);
+  w.blocks = o;      o += compact_ws_bytes((long long)npix);  // block counts of a large compaction
   w.bytes = o;
   return w;
 }
@@ -765,6 +813,55 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   a.lda = p->c_mid; a.ldo = p->c_mid;
   if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
   // conv3: 1x1 on dense h2 with the scatter-add epilogue
+  a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
+  a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
+  a.relu = p->relu_out ? 1 : 0;
+  return launch_gemm<M_CONV3>(fx.dtype, a, npix, 1, st);
+}
+
+extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                                          const float* w, float bias, const uint8_t* keep, uint8_t* mask,
+                                          int32_t* idx, int32_t* count, int32_t* sample_offsets, float* logits,
+                                          void* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_block(x, fx, p, out);
+  if (rc != LAUD_OK) return rc;
+  if (!w || !mask || !idx || !count || S <= 0 || fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
+  if (p->c_in > 4096) return LAUD_ERR_UNSUPPORTED;  // masker weights are held in LDS by conv1
+  const int Hp = fx.H / S, Wp = fx.W / S;
+  const DynWs L = dyn_ws_layout(fx, p->c_mid);
+  if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  char* wsb = (char*)ws;
+  float* proj = (float*)(wsb + L.pix);  // the pixel-list region is free in this variant
+  void* h1 = wsb + L.h1;
+  void* h2 = wsb + L.h2;
+  const long long npix = (long long)fx.N * fx.H * fx.W;
+  const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.cmask = nullptr;
+  // conv1 on every pixel + per-pixel masker projection, one read of x
+  a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
+  a.count = nullptr; a.list = nullptr; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
+  a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1; a.m_rows = (int)npix; a.wmask = w; a.proj = proj;
+  if ((rc = launch_gemm<M_DENSE1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  // pooled logits -> threshold -> ascending index list (device-side count)
+  if ((rc = launch_pool_compact(proj, fx.N, fx.H, fx.W, S, bias, keep, mask, logits, idx, count, sample_offsets,
+                                (int32_t*)(wsb + L.blocks), st)) != LAUD_OK)
+    return rc;
+  if (x != out) {
+    StageScope scope(LAUD_STAGE_COPY_INACTIVE, st);
+    hipLaunchKernelGGL(k_copy_inactive, dim3((unsigned)(fx.N * Hp * Wp)), dim3(256), 0, st, (const uint4*)x,
+                       (uint4*)out, fx.H, fx.W, S, cpp, idx, count);
+    if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  }
+  a.wmask = nullptr; a.proj = nullptr;
+  // conv2 and conv3 exactly as in laud_dyn_bottleneck
+  a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
+  a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
+  a.lda = p->c_mid; a.ldo = p->c_mid;
+  if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
   a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
   a.relu = p->relu_out ? 1 : 0;

@@ -94,11 +94,53 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
 // does the whole ordered compaction in one launch.  Each thread owns four consecutive entries per
 // pass; four ballots give the in-wave prefix (mbcnt), an LDS scan over the 16 waves the rest.
 constexpr int kSmallCompactMax = 8 * kCompactBlock;  // 32768 entries
-__global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t* __restrict__ mask, int n,
+// Pooling of the per-pixel masker projection (Masker-Conv1x1 fusion, App. B item 1): patch logit =
+// bias + mean over the S x S patch of proj; active iff logit > 0 (and the sample's gate, if any).
+struct PoolArgs {
+  const float* proj;    // [N*H*W] per-pixel projection, or null: the mask bytes are the input
+  const uint8_t* keep;  // [N] or null
+  float* logits;        // [npatch] or null
+  int H, W, S;
+  float bias;
+};
+__device__ __forceinline__ bool pooled_decision(const PoolArgs& pa, int q, uint8_t* mask) {
+  const int Hp = pa.H / pa.S, Wp = pa.W / pa.S;
+  const int n = q / (Hp * Wp), r = q - n * (Hp * Wp);
+  const int py = r / Wp, px = r - py * Wp;
+  float acc = 0.f;
+  const float* base = pa.proj + ((size_t)n * pa.H + py * pa.S) * pa.W + px * pa.S;
+  if (pa.S == 2) {  // all loads in flight at once; fixed summation order (row major)
+    const float a0 = base[0], a1 = base[1], a2 = base[pa.W], a3 = base[pa.W + 1];
+    acc = ((a0 + a1) + a2) + a3;
+  } else if (pa.S == 4) {
+    float v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = base[(k >> 2) * pa.W + (k & 3)];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc += v[k];
+  } else {
+    for (int dy = 0; dy < pa.S; ++dy)
+      for (int dx = 0; dx < pa.S; ++dx) acc += base[dy * pa.W + dx];
+  }
+  const float logit = acc / (float)(pa.S * pa.S) + pa.bias;
+  bool on = logit > 0.f;
+  if (pa.keep && pa.keep[n] == 0) on = false;
+  mask[q] = on ? 1 : 0;
+  if (pa.logits) pa.logits[q] = logit;
+  return on;
+}
+
+__global__ __launch_bounds__(256) void k_pool_mask(PoolArgs pa, int npatch, uint8_t* __restrict__ mask) {
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q < npatch) pooled_decision(pa, q, mask);
+}
+
+template <bool POOL>
+__global__ __launch_bounds__(kCompactThreads) void k_compact_small(uint8_t* __restrict__ mask, int n,
                                                                    int32_t* __restrict__ idx,
                                                                    int32_t* __restrict__ count,
                                                                    int32_t* __restrict__ sample_offsets,
-                                                                   int per_sample) {
+                                                                   int per_sample, PoolArgs pa) {
   __shared__ int wsum[kCompactThreads / kWave];
   __shared__ int woff[kCompactThreads / kWave];
   __shared__ int s_tot;
@@ -111,7 +153,8 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
     int before = 0, mine = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      f[j] = (i0 + j < n) && mask[i0 + j] != 0;
+      if constexpr (POOL) f[j] = (i0 + j < n) && pooled_decision(pa, i0 + j, mask);
+      else f[j] = (i0 + j < n) && mask[i0 + j] != 0;
       b[j] = __ballot(f[j]);
       before += ballot_prefix(b[j]);  // set entries of lower lanes at position j
     }
@@ -155,8 +198,9 @@ int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int
     return check_launch();
   }
   if (n <= kSmallCompactMax) {
-    hipLaunchKernelGGL(k_compact_small, dim3(1), dim3(kCompactThreads), 0, stream, mask, n, idx, count,
-                       sample_offsets, per_sample > 0 ? per_sample : 1);
+    hipLaunchKernelGGL((k_compact_small<false>), dim3(1), dim3(kCompactThreads), 0, stream,
+                       const_cast<uint8_t*>(mask), n, idx, count, sample_offsets, per_sample > 0 ? per_sample : 1,
+                       PoolArgs{});
     return check_launch();
   }
   const int nb = (n + kCompactBlock - 1) / kCompactBlock;
@@ -167,6 +211,21 @@ int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int
   hipLaunchKernelGGL(k_compact, dim3(nb), dim3(kCompactThreads), 0, stream, mask, n, idx, count, sample_offsets,
                      per_sample > 0 ? per_sample : 1, block_counts, nb);
   return check_launch();
+}
+
+int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bias, const uint8_t* keep, uint8_t* mask,
+                        float* logits, int32_t* idx, int32_t* count, int32_t* sample_offsets, int32_t* block_counts,
+                        hipStream_t stream) {
+  const int pps = (H / S) * (W / S), npatch = N * pps;
+  PoolArgs pa{proj, keep, logits, H, W, S, bias};
+  // One thread per patch over a wide grid: the S*S projection reads of a patch are independent, and a
+  // single block walking all patches would serialise their latency.
+  {
+    StageScope scope(LAUD_STAGE_MASK_LOGITS, stream);
+    hipLaunchKernelGGL(k_pool_mask, dim3((npatch + 255) / 256), dim3(256), 0, stream, pa, npatch, mask);
+  }
+  if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  return launch_compact(mask, npatch, idx, count, sample_offsets, pps, block_counts, stream);
 }
 
 // ------------------------------------------------------------------------------------------

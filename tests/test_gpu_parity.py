@@ -413,3 +413,99 @@ def test_config2_full_size_sampled(G, r):
     up = O.upsample_mask(got_mask[sample], S).astype(bool)
     assert np.array_equal(got[~up], x[sample][~up])
     assert_close(got[up], ref[up], TOL[dt], "config 2 sampled images")
+
+
+# ------------------------------------------------------------------------------------------
+# masker fused into the first 1x1 (laud_masker_dyn_bottleneck)
+# ------------------------------------------------------------------------------------------
+FUSED_CASES = [
+    # N, H, W, C, m, S, dtype, relu_out
+    (2, 12, 12, 40, 24, 2, I.F32, True),
+    (3, 12, 8, 32, 16, 4, I.F32, False),
+    (4, 14, 14, 1024, 256, 2, I.BF16, False),
+    (3, 7, 7, 2048, 512, 1, I.BF16, True),
+    (2, 28, 28, 512, 128, 4, I.BF16, True),
+    (5, 14, 14, 64, 32, 14, I.F32, True),      # S = H: the masker is a layer gate
+    (40, 28, 28, 16, 8, 1, I.BF16, False),     # 31360 patches: still the one-launch compaction
+    (44, 28, 28, 16, 8, 1, I.BF16, False),     # 34496 patches: pooled mask kernel + block compaction
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES)
+@pytest.mark.parametrize("inplace", [True, False])
+@pytest.mark.parametrize("use_keep", [False, True])
+def test_masker_dyn_bottleneck(G, case, inplace, use_keep):
+    t, L, D = G.torch, G.L, G.D
+    N, H, W, C, m, S, dt, relu_out = case
+    x = I.feature_map(900 + C + H, N, H, W, C, dt)
+    hb = I.bottleneck_params(901 + C, C, m, C, dt, relu_out)
+    w = I.masker_weights(902 + C, C)
+    hp, wp = H // S, W // S
+    npatch = N * hp * wp
+    ref0 = O.mask_logits(x, S, w, 0.0)
+    bias, _ = I.bias_for_ratio(ref0, 0.5, window=max(2, npatch // 8))
+    keep = I.bernoulli_mask(903 + N, (N,), 0.6) if use_keep else None
+    ref_mask = O.threshold(ref0 + bias)
+    if use_keep:
+        ref_mask = ref_mask * keep[:, None, None]
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    mask = t.full((npatch,), 9, dtype=t.uint8, device="cuda")
+    idx = t.full((npatch,), -7, dtype=t.int32, device="cuda")
+    cnt = t.full((1,), -1, dtype=t.int32, device="cuda")
+    so = t.full((N + 1,), -1, dtype=t.int32, device="cuda")
+    lg = t.full((npatch,), float("nan"), dtype=t.float32, device="cuda")
+    ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+    ws.fill_(0xFF)
+    out = xd if inplace else t.full_like(xd, 123.0)
+    L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias,
+                                 t.from_numpy(keep).cuda() if use_keep else None, mask, idx, cnt, so, lg, out, ws)
+    t.cuda.synchronize()
+    scale = float(np.sqrt(np.mean(ref0 * ref0))) + abs(bias)
+    eps = 2e-5 * scale + 1e-6
+    got_logits = lg.cpu().numpy().reshape(N, hp, wp)
+    assert np.abs(got_logits - (ref0 + bias)).max() <= eps
+    got_mask = mask.cpu().numpy().reshape(N, hp, wp)
+    sure = np.abs(ref0 + bias) > eps
+    assert np.array_equal(got_mask[sure], ref_mask[sure])
+    c = int(cnt.item())
+    assert c == int(got_mask.sum())
+    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(got_mask))
+    assert np.all(idx.cpu().numpy()[c:] == -7)
+    assert np.array_equal(so.cpu().numpy(), O.sample_offsets(got_mask))
+    got = D.to_host(out)
+    ref = O.dyn_bottleneck(x, oracle_params(hb), S, got_mask)
+    up = O.upsample_mask(got_mask, S).astype(bool)
+    assert np.array_equal(got[~up], x[~up])
+    assert_close(got[up], ref[up], TOL[dt], "fused masker block")
+
+
+def test_masker_dyn_bottleneck_equals_two_call_path(G):
+    """Same mask, same indices, same output bits as laud_mask_gen + laud_dyn_bottleneck on config-2 geometry."""
+    t, L, D = G.torch, G.L, G.D
+    N, H, C, m, S, dt = 16, 14, 1024, 256, 2, I.BF16
+    x = I.feature_map(950, N, H, H, C, dt)
+    hb = I.bottleneck_params(951, C, m, C, dt, False)
+    w = I.masker_weights(952, C)
+    bias, _ = I.bias_for_ratio(O.mask_logits(x, S, w, 0.0), 0.5)
+    db = D.DeviceBottleneck(hb)
+    npatch = N * 49
+    res = []
+    for fused in (False, True):
+        xd = D.to_device(x, dt)
+        fx = L.fmap_of(xd)
+        mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.zeros(1, dtype=t.int32, device="cuda")
+        ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+        wd = t.from_numpy(w).cuda()
+        if fused:
+            L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, wd, bias, None, mask, idx, cnt, None, None, xd, ws)
+        else:
+            L.laud_mask_gen(xd, fx, S, wd, bias, None, mask, idx, cnt, None, None, D.workspace(4096))
+            L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
+        t.cuda.synchronize()
+        res.append((mask.cpu().numpy(), idx.cpu().numpy()[: int(cnt.item())], D.to_host(xd)))
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+    assert np.array_equal(res[0][2], res[1][2])  # conv1 rows are computed identically in both variants

@@ -54,7 +54,7 @@ def test_workspace_sizes(lib):
     p = _bn(1024, 256, 1024)
     npix = 128 * 14 * 14
     dyn = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, p, 2)
-    assert dyn >= 2 * npix * 256 * 2 + npix * 4 and dyn < 2 * npix * 256 * 2 + npix * 4 + 8192
+    assert dyn >= 2 * npix * 256 * 2 + npix * 4 and dyn < 2 * npix * 256 * 2 + npix * 4 + 8192  # + small counters
     assert L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4) == 2 * npix * 256 * 2
     assert L.workspace_size(B.OP_MASK_GEN, fx, None, 2) == 256
     assert L.workspace_size(B.OP_COMPACT, fx, None, 300001) >= 4 * 74
@@ -99,6 +99,11 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert d(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE + 64), vp(FAKE), need, st) == B.ERR_INVALID_ARG  # partial overlap
     nullw = B.Bottleneck(64, 16, 64, 0, *([FAKE] * 8), 0)
     assert d(vp(FAKE), fx, C.byref(nullw), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    # fused masker variant
+    fm = lib.laud_masker_dyn_bottleneck
+    assert fm(vp(FAKE), fx, C.byref(p), 2, None, 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    assert fm(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need - 1, st) == B.ERR_WORKSPACE
+    assert fm(vp(FAKE), fx, C.byref(p), 3, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
     # channel skip
     c = lib.laud_channel_skip_conv
     needc = L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4)
