@@ -37,10 +37,101 @@ def parse():
     ap.add_argument("--sweep-steps", type=int, default=40, help="steps per ratio of the latency-vs-ratio sweep (0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=128)
+    ap.add_argument("--no-extras", action="store_true", help="skip the short per-entry-point measurements")
     ap.add_argument("--variant", choices=["fused", "two-call"], default="fused",
                     help="fused: laud_masker_dyn_bottleneck (masker fused into a static conv1); "
                          "two-call: laud_mask_gen + laud_dyn_bottleneck (sparse conv1)")
     return ap.parse_args()
+
+
+def _p50_us(t, fn, iters=20, warm=3):
+    for i in range(warm):
+        fn(i)
+    t.cuda.synchronize()
+    ev = [(t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for i in range(iters):
+        ev[i][0].record()
+        fn(warm + i)
+        ev[i][1].record()
+    t.cuda.synchronize()
+    lat = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    return lat[len(lat) // 2] * 1e3
+
+
+def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm):
+    """p50 of single entry points on rotating buffers; bytes and FLOPs are the algorithmic ones."""
+    ex = {}
+    nb = len(bufs)
+    for b in bufs:
+        b.copy_(x_master)
+    xbytes = x_master.numel() * x_master.element_size()
+    # masker alone (HBM-bound: reads x once)
+    us = _p50_us(t, lambda i: L.laud_mask_gen(bufs[i % nb], fx, S, wd, bias, None, mask, idx, cnt, None, None, wsm))
+    ex["mask_gen_config2"] = {"p50_us": round(us, 1), "GB_per_s": round(xbytes / us / 1e3, 0),
+                              "hbm_frac": round(xbytes / us / 1e3 / PEAK_HBM_GBS, 3)}
+    # stand-alone gather with halo of the active patches (reads and writes P*(S+2)^2 pixel rows)
+    P = int(cnt.item())
+    E = S + 2
+    g = t.empty((P, E, E, fx.C), dtype=x_master.dtype, device="cuda")
+    us = _p50_us(t, lambda i: L.laud_gather_patches(bufs[i % nb], fx, S, 1, idx, cnt, g))
+    gbytes = 2.0 * P * E * E * fx.C * 2
+    ex["gather_halo_config2_r050"] = {"p50_us": round(us, 1), "GB_per_s": round(gbytes / us / 1e3, 0),
+                                      "hbm_frac": round(gbytes / us / 1e3 / PEAK_HBM_GBS, 3)}
+    del g
+    # identity bottlenecks of the other stages (batch 128, Bernoulli 0.5 masks), two-call dyn part only,
+    # channel skipping (config 4: batch 64, 4 groups, keep 0.5) and the layer gate (config 5, stage 3)
+    for stage in (1, 2, 3, 4):
+        sg = I.STAGES[stage]
+        for name, N in (("dyn", 128), ("chan", 64)):
+            if name == "dyn" and stage == 3:
+                continue
+            xs = D.to_device(I.feature_map(7000 + stage, 8, sg["hw"], sg["hw"], sg["c_in"], I.BF16), I.BF16)
+            xs = xs.repeat(N // 8, 1, 1, 1).contiguous()
+            fxs = L.fmap_of(xs)
+            hb = I.bottleneck_params(7100 + stage, sg["c_in"], sg["m"], sg["c_in"], I.BF16, relu_out=True)
+            dbs = D.DeviceBottleneck(hb)
+            xb = [xs.clone() for _ in range(4)]
+            flops_img = 2.0 * 17 * sg["m"] ** 2 * sg["hw"] ** 2
+            if name == "dyn":
+                Ss = sg["S"]
+                npatch = N * (sg["hw"] // Ss) ** 2
+                mk = t.from_numpy(I.bernoulli_mask(7200 + stage, (npatch,), 0.5)).cuda()
+                ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+                cn = t.zeros(1, dtype=t.int32, device="cuda")
+                L.laud_layer_skip_compact(mk, npatch, ids, cn, D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, npatch)))
+                wss = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+                us = _p50_us(t, lambda i: L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wss))
+                r = float(cn.item()) / npatch
+                ex[f"dyn_bottleneck_stage{stage}_b128_r050"] = {
+                    "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
+                    "mfma_frac_useful": round(r * N * flops_img / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+            else:
+                cm = I.bernoulli_mask(7300 + stage, (N, 4), 0.5)
+                rn = cm.mean(axis=1)
+                useful = float(((8 * rn + 9 * rn * rn) / 17).sum()) * flops_img
+                cmd = t.from_numpy(cm).cuda()
+                wss = D.workspace(L.workspace_size(B.OP_CHANNEL_SKIP, fxs, dbs.desc, 4))
+                us = _p50_us(t, lambda i: L.laud_channel_skip_conv(xb[i % 4], fxs, dbs.desc, cmd, 4, xb[i % 4], wss))
+                ex[f"channel_skip_stage{stage}_b64_keep050"] = {
+                    "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
+                    "mfma_frac_useful": round(useful / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+            del xb, xs
+    # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound
+    sg = I.STAGES[1]
+    x1 = D.to_device(I.feature_map(1000, 1, 56, 56, 256, I.F32), I.F32)
+    fx1 = L.fmap_of(x1)
+    db1 = D.DeviceBottleneck(I.bottleneck_params(1000, 256, 64, 256, I.F32))
+    mk = t.from_numpy(I.bernoulli_mask(1005, (196,), 0.5)).cuda()
+    ids = t.zeros(196, dtype=t.int32, device="cuda")
+    cn = t.zeros(1, dtype=t.int32, device="cuda")
+    ws1 = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fx1, db1.desc, 4))
+    wc = D.workspace(4096)
+
+    def cfg1(i):
+        L.laud_layer_skip_compact(mk, 196, ids, cn, wc)
+        L.laud_dyn_bottleneck(x1, fx1, db1.desc, 4, ids, cn, x1, ws1)
+    ex["config1_fp32_batch1"] = {"p50_us": round(_p50_us(t, cfg1), 1)}
+    return ex
 
 
 def main():
@@ -194,6 +285,13 @@ def main():
     else:
         fit = None
 
+    # ---- short measurements of the other entry points and stage shapes (context, 20 launches each) ----
+    extras = None
+    if not a.no_extras:
+        del bufs[12:]
+        t.cuda.empty_cache()
+        extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm)
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload --------
     cpu = None
     if not a.no_cpu_baseline:
@@ -245,6 +343,7 @@ def main():
         "cpu_baseline": cpu,
         "sweep": sweep,
         "latency_fit": fit,
+        "extras": extras,
     }
     print(json.dumps(out))
 
