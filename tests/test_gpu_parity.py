@@ -509,3 +509,108 @@ def test_masker_dyn_bottleneck_equals_two_call_path(G):
         res.append((mask.cpu().numpy(), idx.cpu().numpy()[: int(cnt.item())], D.to_host(xd)))
     assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
     assert np.array_equal(res[0][2], res[1][2])  # conv1 rows are computed identically in both variants
+
+
+# ------------------------------------------------------------------------------------------
+# BASELINE configs 4 and 5 at full size (sampled images), and a chain of dynamic blocks (config 3's
+# identity blocks of one stage)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("stage", [1, 2, 3, 4])
+def test_config4_channel_skip_full_size_sampled(G, stage):
+    """ResNet-50 identity bottleneck of each stage, batch 64, bf16, 4 channel groups, keep 0.5."""
+    t, L, D = G.torch, G.L, G.D
+    sg = I.STAGES[stage]
+    N, H, C, m, dt = 64, sg["hw"], sg["c_in"], sg["m"], I.BF16
+    xs = I.feature_map(I.seed_for(4, 0, stage), 4, H, H, C, dt)        # 4 distinct images, tiled to 64
+    x = np.tile(xs, (N // 4, 1, 1, 1))
+    hb = I.bottleneck_params(I.seed_for(4, 0, stage), C, m, C, dt, relu_out=True)
+    cm = I.bernoulli_mask(I.seed_for(4, 6, stage), (N, 4), 0.5)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    ws = D.workspace(L.workspace_size(L.binding.OP_CHANNEL_SKIP, fx, db.desc, 4))
+    L.laud_channel_skip_conv(xd, fx, db.desc, t.from_numpy(cm).cuda(), 4, xd, ws)
+    t.cuda.synchronize()
+    sample = [0, 5, 31, 63]
+    got = D.to_host(xd[sample])
+    ref = O.channel_skip_bottleneck(x[sample], oracle_params(hb), cm[sample])
+    assert_close(got, ref, TOL[dt], f"config 4 stage {stage}")
+
+
+def test_config5_layer_gate_and_spatial_full_size_sampled(G):
+    """Stage-3 block at batch 256, bf16: per-sample keep gate (0.6) AND spatial mask S = 2 at ratio 0.5."""
+    t, L, D = G.torch, G.L, G.D
+    sg = I.STAGES[3]
+    N, H, C, m, S, dt = 256, sg["hw"], sg["c_in"], sg["m"], sg["S"], I.BF16
+    xs = I.feature_map(I.seed_for(5, 0), 8, H, H, C, dt)
+    x = np.tile(xs, (N // 8, 1, 1, 1))
+    hb = I.bottleneck_params(I.seed_for(5, 0), C, m, C, dt, relu_out=True)
+    w = I.masker_weights(I.seed_for(5, 5), C)
+    keep = I.bernoulli_mask(I.seed_for(5, 7), (N,), 0.6)
+    keep[0], keep[8] = 1, 0
+    ref0 = O.mask_logits(xs, S, w, 0.0)
+    bias, _ = I.bias_for_ratio(ref0, 0.5)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    npatch = N * 49
+    for fused in (False, True):
+        xw = xd.clone()
+        mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.zeros(1, dtype=t.int32, device="cuda")
+        ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+        wd, kd = t.from_numpy(w).cuda(), t.from_numpy(keep).cuda()
+        if fused:
+            L.laud_masker_dyn_bottleneck(xw, fx, db.desc, S, wd, bias, kd, mask, idx, cnt, None, None, xw, ws)
+        else:
+            L.laud_mask_gen(xw, fx, S, wd, bias, kd, mask, idx, cnt, None, None,
+                            D.workspace(L.workspace_size(L.binding.OP_MASK_GEN, fx, None, S)))
+            L.laud_dyn_bottleneck(xw, fx, db.desc, S, idx, cnt, xw, ws)
+        t.cuda.synchronize()
+        got_mask = mask.cpu().numpy().reshape(N, 7, 7)
+        ref_mask = np.tile(O.threshold(ref0 + bias), (N // 8, 1, 1)) * keep[:, None, None]
+        assert np.array_equal(got_mask, ref_mask)
+        assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(ref_mask))
+        sample = [0, 8, 100, 255]
+        got = D.to_host(xw[sample])
+        ref = O.layer_skip_bottleneck(x[sample], oracle_params(hb), keep[sample], S,
+                                      np.tile(O.threshold(ref0 + bias), (N // 8, 1, 1))[sample])
+        up = O.upsample_mask(ref_mask[sample], S).astype(bool)
+        assert np.array_equal(got[~up], x[sample][~up])
+        assert_close(got[up], ref[up], TOL[dt], "config 5 stage-3 block")
+
+
+def test_chain_of_dynamic_blocks_in_place(G):
+    """Three consecutive stage-3 identity blocks (each with its own masker and weights) applied in place,
+    as in the body of the network; every block is checked against the oracle fed with the block's actual
+    input (per-block parity; end-to-end bf16 drift is not gated)."""
+    t, L, D = G.torch, G.L, G.D
+    sg = I.STAGES[3]
+    N, H, C, m, S, dt = 8, sg["hw"], sg["c_in"], sg["m"], sg["S"], I.BF16
+    x = np.abs(I.feature_map(I.seed_for(3, 0), N, H, H, C, dt))  # post-ReLU activations are non-negative
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    npatch = N * 49
+    mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    for blk in range(3):
+        hb = I.bottleneck_params(I.seed_for(3, 0, blk + 1), C, m, C, dt, relu_out=True, s3_gain=0.25)
+        w = I.masker_weights(I.seed_for(3, 5, blk + 1), C)
+        db = D.DeviceBottleneck(hb)
+        x_in = D.to_host(xd)
+        ref0 = O.mask_logits(x_in, S, w, 0.0)
+        bias, _ = I.bias_for_ratio(ref0, 0.5)
+        ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+        L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None,
+                                     None, xd, ws)
+        t.cuda.synchronize()
+        got_mask = mask.cpu().numpy().reshape(N, 7, 7)
+        assert np.array_equal(got_mask, O.threshold(ref0 + bias))
+        got = D.to_host(xd)
+        ref = O.dyn_bottleneck(x_in, oracle_params(hb), S, got_mask)
+        up = O.upsample_mask(got_mask, S).astype(bool)
+        assert np.array_equal(got[~up], x_in[~up])
+        assert_close(got[up], ref[up], TOL[dt], f"block {blk}")
+        assert got.min() >= 0.0
