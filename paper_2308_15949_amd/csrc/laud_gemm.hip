@@ -1,8 +1,8 @@
 // The three convolutions of the dynamic bottleneck as gathered implicit GEMMs on gfx950 MFMA.
 //
-// One kernel template, k_gemm<MODE, ET, BM, BN>, computes a BM x BN output tile with four
-// waves (2 x 2) of 32x32 MFMA tiles; A (activations) and B (weights, [N][K] K-contiguous) are
-// staged through LDS in 128-byte K slices.  What differs per MODE is only where a row of A
+// One kernel template, k_gemm<MODE, ET, BM, BN, WGN>, computes a BM x BN output tile with 2 x WGN
+// waves of 32x32 MFMA tiles; A (activations) and B (weights, [N][K] K-contiguous) are staged
+// through LDS in 128-byte K slices.  What differs per MODE is only where a row of A
 // comes from and where a row of the result goes:
 //
 //   CONV1  rows = pixels of the dilated active set (list of pixel ids): the gather is fused
@@ -394,8 +394,6 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     }
   };
 
-  // Residual prefetch (scatter-add modes): the 16-byte chunks this thread will add in the epilogue
-  // are requested now, so their latency hides behind the K loop.
   constexpr int CPR = BN / EPC;                 // 16-byte output chunks per tile row
   constexpr int EPI = (BM * CPR + NT - 1) / NT;  // epilogue chunks per thread
   constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3);
@@ -413,19 +411,6 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   store_slice(0, ra[0], rb[0], kes[0]);
   load_slice(ra[0], rb[0], kes[0]);
   __syncthreads();  // stage 0 is ready; also publishes s_row
-  constexpr bool RES_EARLY = false;  // request the residual before the K loop instead of in the epilogue
-  u32x4 resv[RES ? EPI : 1];
-  if constexpr (RES && RES_EARLY) {
-#pragma unroll
-    for (int q = 0; q < EPI; ++q) {
-      const int id = tid + q * NT;
-      const int rl = id / CPR, chk = id - rl * CPR;
-      const int orow = (id < BM * CPR) ? s_row[rl] : -1;
-      const int col = col0 + chk * EPC;
-      const bool ok = orow >= 0 && col + EPC <= ncols;
-      resv[q] = *(ok ? (gptr16)((const ET*)a.Res + (size_t)orow * a.ldo + col) : zpage);
-    }
-  }
   for (int s0 = 0; s0 < KT; s0 += PF) {
 #pragma unroll
     for (int d = 0; d < PF; ++d) {
@@ -501,9 +486,11 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       const size_t off = (size_t)orow * a.ldo + col;
       if (col + EPC <= ncols) {
         if constexpr (RES) {
-          if constexpr (!RES_EARLY) resv[q] = *(gptr16)(Rp + off);
+          // the residual is read here, not ahead of the K loop: requested early it only delays the first
+          // slices (loads return in order) and measured slower
+          const u32x4 rraw = *(gptr16)(Rp + off);
           ET rr[EPC];
-          __builtin_memcpy(rr, &resv[q], 16);
+          __builtin_memcpy(rr, &rraw, 16);
 #pragma unroll
           for (int e = 0; e < EPC; ++e) {
             v[e] += elem<ET>::load(&rr[e]);
@@ -711,13 +698,12 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   return LAUD_OK;
 }
 
-struct DynWs { size_t need_counts, total, pix, h1, h2, blocks, bytes; };
+struct DynWs { size_t need_counts, pix, h1, h2, blocks, bytes; };
 static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
   DynWs w;
   size_t o = 0;
   w.need_counts = o; o += align_up((size_t)fx.N * 4, 256);
-  w.total = o;       o += 256;
   w.pix = o;         o += align_up(npix * 4, 256);
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(npix * c_mid * eb, 256);

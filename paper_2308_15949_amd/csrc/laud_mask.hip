@@ -135,12 +135,11 @@ __global__ __launch_bounds__(256) void k_pool_mask(PoolArgs pa, int npatch, uint
   if (q < npatch) pooled_decision(pa, q, mask);
 }
 
-template <bool POOL>
-__global__ __launch_bounds__(kCompactThreads) void k_compact_small(uint8_t* __restrict__ mask, int n,
+__global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t* __restrict__ mask, int n,
                                                                    int32_t* __restrict__ idx,
                                                                    int32_t* __restrict__ count,
                                                                    int32_t* __restrict__ sample_offsets,
-                                                                   int per_sample, PoolArgs pa) {
+                                                                   int per_sample) {
   __shared__ int wsum[kCompactThreads / kWave];
   __shared__ int woff[kCompactThreads / kWave];
   __shared__ int s_tot;
@@ -153,8 +152,7 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(uint8_t* __re
     int before = 0, mine = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if constexpr (POOL) f[j] = (i0 + j < n) && pooled_decision(pa, i0 + j, mask);
-      else f[j] = (i0 + j < n) && mask[i0 + j] != 0;
+      f[j] = (i0 + j < n) && mask[i0 + j] != 0;
       b[j] = __ballot(f[j]);
       before += ballot_prefix(b[j]);  // set entries of lower lanes at position j
     }
@@ -198,9 +196,8 @@ int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int
     return check_launch();
   }
   if (n <= kSmallCompactMax) {
-    hipLaunchKernelGGL((k_compact_small<false>), dim3(1), dim3(kCompactThreads), 0, stream,
-                       const_cast<uint8_t*>(mask), n, idx, count, sample_offsets, per_sample > 0 ? per_sample : 1,
-                       PoolArgs{});
+    hipLaunchKernelGGL(k_compact_small, dim3(1), dim3(kCompactThreads), 0, stream, mask, n, idx, count,
+                       sample_offsets, per_sample > 0 ? per_sample : 1);
     return check_launch();
   }
   const int nb = (n + kCompactBlock - 1) / kCompactBlock;
@@ -254,7 +251,7 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
     const int py = r / Wp, px = r - py * Wp;
     const int cpr = C / EPC;          // chunks per pixel row
     const int total = S * S * cpr;    // chunks per patch
-    // Four 16-byte loads of x are put in flight before any of them is consumed: the kernel is a pure
+    // Eight (then four) 16-byte loads of x are put in flight before any of them is consumed: the kernel is a pure
     // stream over x and what bounds it is the number of bytes in flight per CU.
     auto chunk_ptr = [&](int c) -> const uint4* {
       const int j = c / cpr, cv = c - j * cpr;
@@ -278,6 +275,13 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
       }
     };
     int c = tl;
+    for (; c + 7 * TEAM < total; c += 8 * TEAM) {
+      uint4 r[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) r[u] = *chunk_ptr(c + u * TEAM);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += dot(r[u], c + u * TEAM);
+    }
     for (; c + 3 * TEAM < total; c += 4 * TEAM) {
       uint4 r[4];
 #pragma unroll
