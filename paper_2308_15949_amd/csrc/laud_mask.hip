@@ -230,7 +230,7 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
 // ------------------------------------------------------------------------------------------
 // One "team" (a wave, or the whole 256-thread block for big patches) per patch.  The team
 // walks the S*S pixel rows of the patch in 16-byte chunks; float32 accumulation.
-template <typename ET, int TEAM>
+template <typename ET, int TEAM, bool WLDS>
 __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, int N, int H, int W, int C, int S,
                                                      const float* __restrict__ w, float bias,
                                                      const uint8_t* __restrict__ keep, uint8_t* __restrict__ mask,
@@ -238,6 +238,14 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
   constexpr int EPC = elem<ET>::per16;
   constexpr int TEAMS = 256 / TEAM;
   __shared__ float red[256 / kWave];
+  // The masker weights are read once per 16-byte chunk of x; from global memory they would double the
+  // number of vector-memory instructions of a kernel that should only stream x, so the block keeps
+  // them in LDS (C floats) when they fit.
+  extern __shared__ __align__(16) float s_w[];
+  if constexpr (WLDS) {
+    for (int k = threadIdx.x; k < C; k += 256) s_w[k] = w[k];
+    __syncthreads();
+  }
   const int Hp = H / S, Wp = W / S;
   const int npatch = N * Hp * Wp;
   const int team = threadIdx.x / TEAM, tl = threadIdx.x % TEAM;
@@ -261,13 +269,20 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
     };
     auto dot = [&](const uint4& raw, int c) -> float {
       const int cv = c % cpr;
-      const float4* wp = reinterpret_cast<const float4*>(w + cv * EPC);
-      if constexpr (EPC == 4) {
-        const float4 wv = wp[0];
-        return __uint_as_float(raw.x) * wv.x + __uint_as_float(raw.y) * wv.y + __uint_as_float(raw.z) * wv.z +
-               __uint_as_float(raw.w) * wv.w;
+      float4 w0, w1 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (WLDS) {
+        const float4* wp = reinterpret_cast<const float4*>(s_w + cv * EPC);
+        w0 = wp[0];
+        if constexpr (EPC == 8) w1 = wp[1];
       } else {
-        const float4 w0 = wp[0], w1 = wp[1];
+        const float4* wp = reinterpret_cast<const float4*>(w + cv * EPC);
+        w0 = wp[0];
+        if constexpr (EPC == 8) w1 = wp[1];
+      }
+      if constexpr (EPC == 4) {
+        return __uint_as_float(raw.x) * w0.x + __uint_as_float(raw.y) * w0.y + __uint_as_float(raw.z) * w0.z +
+               __uint_as_float(raw.w) * w0.w;
+      } else {
         return __uint_as_float(raw.x << 16) * w0.x + __uint_as_float(raw.x & 0xffff0000u) * w0.y +
                __uint_as_float(raw.y << 16) * w0.z + __uint_as_float(raw.y & 0xffff0000u) * w0.w +
                __uint_as_float(raw.z << 16) * w1.x + __uint_as_float(raw.z & 0xffff0000u) * w1.y +
@@ -365,11 +380,18 @@ extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w,
   const bool big = patch_bytes >= 32768;  // a whole block per patch
   const int teams = big ? 1 : 256 / kWave;
   const unsigned grid = (unsigned)((npatch + teams - 1) / teams);
+  const int w_lds = fx.C <= 8192 ? 1 : 0;
   {
     StageScope scope(LAUD_STAGE_MASK_LOGITS, st);
 #define LAUD_LAUNCH_MASK(ET, TEAM)                                                                            \
-  hipLaunchKernelGGL((k_mask_logits<ET, TEAM>), dim3(grid), dim3(256), 0, st, (const ET*)x, fx.N, fx.H, fx.W, \
-                     fx.C, S, w, bias, keep, mask, logits)
+  do {                                                                                                        \
+    if (w_lds)                                                                                                \
+      hipLaunchKernelGGL((k_mask_logits<ET, TEAM, true>), dim3(grid), dim3(256), (size_t)fx.C * 4, st,        \
+                         (const ET*)x, fx.N, fx.H, fx.W, fx.C, S, w, bias, keep, mask, logits);                \
+    else                                                                                                      \
+      hipLaunchKernelGGL((k_mask_logits<ET, TEAM, false>), dim3(grid), dim3(256), 0, st, (const ET*)x, fx.N,  \
+                         fx.H, fx.W, fx.C, S, w, bias, keep, mask, logits);                                   \
+  } while (0)
   if (fx.dtype == LAUD_BF16) {
     if (big) LAUD_LAUNCH_MASK(bf16_t, 256); else LAUD_LAUNCH_MASK(bf16_t, 64);
   } else {
