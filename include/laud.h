@@ -172,6 +172,20 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Channel masker (Sec. 3.2 "Masker design"; Fig. 3(b)): g = mean of x over H x W per sample and
+ * channel; h = relu(wa*g + ba) (the paper does not name the non-linearity; ReLU is assumed);
+ * l = wb*h + bb, 2D logits viewed row-major as [D][2]; group d is kept iff l[d][0] > l[d][1]
+ * (strict; NaN drops the group).  The paper sets hidden = max(floor(D/16), 16); any positive
+ * width is accepted.  All weights float32 device arrays: wa [hidden][C], ba [hidden],
+ * wb [2*D][hidden], bb [2*D].  Outputs: cmask [N][D] bytes (the input of laud_channel_skip_conv),
+ * logits2 [N][2*D] float32 or NULL.  Workspace: laud_channel_masker_workspace(fx) bytes.
+ */
+size_t laud_channel_masker_workspace(laud_fmap fx);
+int laud_channel_masker(const void* x, laud_fmap fx, const float* wa, const float* ba, int hidden,
+                        const float* wb, const float* bb, int D, uint8_t* cmask, float* logits2,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Instrumentation (host side; not part of the paper's method): per-stage GPU time of the
  * kernels the entry points launch.  While enabled, every stage is bracketed by a pair of HIP
  * events recorded on the call's stream (at most 65536 stage launches are kept per collection;

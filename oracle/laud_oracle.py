@@ -147,6 +147,31 @@ def upsample_mask(mask_coarse: np.ndarray, S: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- #
+# channel masker (Sec. 3.2 "Masker design"; Fig. 3(b))
+# --------------------------------------------------------------------------- #
+def channel_masker_hidden(D: int) -> int:
+    """Hidden width of the channel masker's MLP: max(floor(D/16), 16)."""
+    return max(D // 16, 16)
+
+
+def channel_masker_logits(x: np.ndarray, wa: np.ndarray, ba: np.ndarray, wb: np.ndarray, bb: np.ndarray) -> np.ndarray:
+    """Global average pooling over H x W, then a 2-layer MLP (ReLU between the layers; the paper does
+    not name the non-linearity) producing 2D logits per sample, viewed as [N, D, 2] (row-major
+    reshape of the 2D vector, as the paper reshapes the 2C vector to C x 2).
+    wa [hidden, C], ba [hidden], wb [2D, hidden], bb [2D]."""
+    g = np.asarray(x, np.float64).mean(axis=(1, 2))                       # [N, C]
+    h = relu(np.matmul(g, np.asarray(wa, np.float64).T) + np.asarray(ba, np.float64))
+    l2 = np.matmul(h, np.asarray(wb, np.float64).T) + np.asarray(bb, np.float64)  # [N, 2D]
+    return l2.reshape(l2.shape[0], -1, 2)
+
+
+def channel_mask_from_logits(l2: np.ndarray) -> np.ndarray:
+    """Group d of a sample is kept iff its logit 0 strictly exceeds its logit 1 (argmax at inference,
+    ties and NaN drop the group, as for the spatial masker)."""
+    return (l2[..., 0] > l2[..., 1]).astype(np.uint8)
+
+
+# --------------------------------------------------------------------------- #
 # index generation / gather (App. B, operator fusion item 2; Sec. 3.1 step 1)
 # --------------------------------------------------------------------------- #
 def compact(mask: np.ndarray) -> np.ndarray:

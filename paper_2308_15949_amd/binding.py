@@ -19,7 +19,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
-           "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+           "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace",
+           "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
 STAGE_COUNT = 11
 
 
@@ -72,6 +73,10 @@ def load() -> C.CDLL:
     lib.laud_masker_dyn_bottleneck.restype = i32
     lib.laud_masker_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, C.c_float, vp, vp, vp, vp,
                                                vp, vp, vp, vp, sz, vp]
+    lib.laud_channel_masker_workspace.restype = sz
+    lib.laud_channel_masker_workspace.argtypes = [Fmap]
+    lib.laud_channel_masker.restype = i32
+    lib.laud_channel_masker.argtypes = [vp, Fmap, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.laud_stage_timing_enable.restype = i32
     lib.laud_stage_timing_enable.argtypes = [i32]
     lib.laud_stage_timing_read.restype = i32
@@ -175,6 +180,16 @@ def laud_masker_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, w, bias: floa
     _check(load().laud_masker_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(w), float(bias), _ptr(keep),
                                              _ptr(mask), _ptr(idx), _ptr(count), _ptr(sample_offsets), _ptr(logits),
                                              _ptr(out), wp, wb, _stream()), "laud_masker_dyn_bottleneck")
+
+
+def channel_masker_workspace(fx: Fmap) -> int:
+    return int(load().laud_channel_masker_workspace(fx))
+
+
+def laud_channel_masker(x, fx: Fmap, wa, ba, hidden: int, wb, bb, D: int, cmask, logits2, ws) -> None:
+    wp, wb_ = _ws_args(ws)
+    _check(load().laud_channel_masker(_ptr(x), fx, _ptr(wa), _ptr(ba), int(hidden), _ptr(wb), _ptr(bb), int(D),
+                                      _ptr(cmask), _ptr(logits2), wp, wb_, _stream()), "laud_channel_masker")
 
 
 def laud_stage_timing_enable(on: bool) -> None:

@@ -156,3 +156,16 @@ def seed_for(config: int, k: int, block: int = 0) -> int:
     """seed = 1000*config + 10*block + k; k: 0 x, 1..3 weights, 4 affine, 5 mask / masker
     weights, 6 channel masks, 7 layer gates."""
     return 1000 * config + 10 * block + k
+
+
+def channel_masker_weights(seed: int, c: int, d: int, hidden: int | None = None):
+    """Channel-masker MLP weights (float32): wa [hidden, C] ~ N(0, 2/C), ba ~ 0.1 N(0,1),
+    wb [2D, hidden] ~ N(0, 1/hidden), bb ~ 0.1 N(0,1); hidden defaults to max(D // 16, 16)
+    (Sec. 3.2 "Masker design")."""
+    hidden = max(d // 16, 16) if hidden is None else hidden
+    g = np.random.default_rng(seed)
+    wa = (g.standard_normal((hidden, c)) * np.sqrt(2.0 / c)).astype(np.float32)
+    ba = (0.1 * g.standard_normal(hidden)).astype(np.float32)
+    wb = (g.standard_normal((2 * d, hidden)) / np.sqrt(hidden)).astype(np.float32)
+    bb = (0.1 * g.standard_normal(2 * d)).astype(np.float32)
+    return wa, ba, wb, bb, hidden

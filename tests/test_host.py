@@ -104,6 +104,14 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert fm(vp(FAKE), fx, C.byref(p), 2, None, 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
     assert fm(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need - 1, st) == B.ERR_WORKSPACE
     assert fm(vp(FAKE), fx, C.byref(p), 3, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    # channel masker
+    km = lib.laud_channel_masker
+    wsk = lib.laud_channel_masker_workspace(fx)
+    assert wsk >= 2 * 64 * 4
+    assert km(vp(FAKE), fx, None, vp(FAKE), 16, vp(FAKE), vp(FAKE), 4, vp(FAKE), None, vp(FAKE), wsk, st) == B.ERR_INVALID_ARG
+    assert km(vp(FAKE), fx, vp(FAKE), vp(FAKE), 0, vp(FAKE), vp(FAKE), 4, vp(FAKE), None, vp(FAKE), wsk, st) == B.ERR_INVALID_ARG
+    assert km(vp(FAKE), fx, vp(FAKE), vp(FAKE), 16, vp(FAKE), vp(FAKE), 4, vp(FAKE), None, vp(FAKE), wsk - 1, st) == B.ERR_WORKSPACE
+    assert km(vp(FAKE), B.Fmap(2, 8, 8, 60, 0), vp(FAKE), vp(FAKE), 16, vp(FAKE), vp(FAKE), 4, vp(FAKE), None, vp(FAKE), wsk, st) == B.ERR_UNSUPPORTED
     # channel skip
     c = lib.laud_channel_skip_conv
     needc = L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4)

@@ -444,3 +444,40 @@ def test_activation_and_dilated_ratio():
                             hit = True
                 cnt += hit
     assert O.dilated_ratio(mk, S) == pytest.approx(cnt / 72)
+
+
+# --------------------------------------------------------------------------- #
+# channel masker (Sec. 3.2 "Masker design")
+# --------------------------------------------------------------------------- #
+def test_channel_masker_hidden_width_formula():
+    # max(floor(D/16), 16): D = C/G for the mid widths 64..512 with G in {1, 2} and for 4 groups
+    assert [O.channel_masker_hidden(d) for d in (4, 32, 64, 256, 257, 512, 1024)] == [16, 16, 16, 16, 16, 32, 64]
+
+
+def test_channel_masker_vs_pure_python_and_hand_example():
+    rng = np.random.default_rng(30)
+    N, H, W, C, D, hid = 3, 3, 2, 5, 4, 6
+    x = rng.standard_normal((N, H, W, C))
+    wa, ba = rng.standard_normal((hid, C)), rng.standard_normal(hid)
+    wb, bb = rng.standard_normal((2 * D, hid)), rng.standard_normal(2 * D)
+    got = O.channel_masker_logits(x, wa, ba, wb, bb)
+    assert got.shape == (N, D, 2)
+    xl = x.tolist()
+    for n in range(N):
+        g = [sum(xl[n][y][xx][c] for y in range(H) for xx in range(W)) / (H * W) for c in range(C)]
+        h = [max(0.0, sum(wa[j][c] * g[c] for c in range(C)) + ba[j]) for j in range(hid)]
+        for o in range(2 * D):
+            want = sum(wb[o][j] * h[j] for j in range(hid)) + bb[o]
+            assert got[n, o // 2, o % 2] == pytest.approx(want, abs=1e-12)   # row-major [D, 2] view
+    # hand example: one pixel, identity first layer, second layer picks h0 - h1 against 0
+    x1 = np.array([[[[2.0, -3.0]]]])
+    l = O.channel_masker_logits(x1, np.eye(2), np.zeros(2), np.array([[1.0, 0.0], [0.0, 1.0]]), np.zeros(2))
+    assert l.tolist() == [[[2.0, 0.0]]]            # relu(-3) = 0
+    assert O.channel_mask_from_logits(l).tolist() == [[1]]
+    assert O.channel_mask_from_logits(np.array([[[1.0, 1.0], [0.0, 1.0], [np.nan, 0.0]]])).tolist() == [[0, 0, 0]]
+    # argmax of two logits == sign of their difference, computed from differenced second-layer weights
+    l2 = O.channel_masker_logits(x, wa, ba, wb, bb)
+    g = x.mean(axis=(1, 2))
+    h = np.maximum(g @ wa.T + ba, 0)
+    diff = h @ (wb[0::2] - wb[1::2]).T + (bb[0::2] - bb[1::2])
+    assert np.array_equal(O.channel_mask_from_logits(l2), (diff > 0).astype(np.uint8))
