@@ -116,6 +116,49 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                     "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
                     "mfma_frac_useful": round(useful / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
             del xb, xs
+    # operator-fusion ablation in the manner of the paper's Tab. 1 (masker + block, p50 per step):
+    #   unfused    = laud_mask_gen, then gather / convs on gathered tiles / scatter-add as separate kernels
+    #   two-call   = laud_mask_gen + laud_dyn_bottleneck (gather fused into conv1/conv2, scatter-add fused)
+    #   all fused  = laud_masker_dyn_bottleneck (masker fused into conv1 as well)
+    for tag, stage, ratio in (("config2_stage3_r050", 3, 0.5), ("stage1_S4_r060", 1, 0.6)):
+        sg = I.STAGES[stage]
+        N, Ss = 128, sg["S"]
+        xs = D.to_device(I.feature_map(7400 + stage, 8, sg["hw"], sg["hw"], sg["c_in"], I.BF16), I.BF16)
+        xs = xs.repeat(N // 8, 1, 1, 1).contiguous()
+        fxs = L.fmap_of(xs)
+        dbs = D.DeviceBottleneck(I.bottleneck_params(7500 + stage, sg["c_in"], sg["m"], sg["c_in"], I.BF16))
+        wm = t.from_numpy(I.masker_weights(7600 + stage, sg["c_in"])).cuda()
+        npatch = N * (sg["hw"] // Ss) ** 2
+        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cn = t.zeros(1, dtype=t.int32, device="cuda")
+        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+        L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+        t.cuda.synchronize()
+        b2 = I.bias_for_ratio(lgs.cpu().numpy(), ratio)[0]
+        xb = [xs.clone() for _ in range(4)]
+        wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+        wsu = D.workspace(L.dyn_bottleneck_unfused_workspace(fxs, dbs.desc, Ss))
+
+        def unfused(i):
+            L.laud_mask_gen(xb[i % 4], fxs, Ss, wm, b2, None, mk, ids, cn, None, None, wsm2)
+            L.laud_dyn_bottleneck_unfused(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wsu)
+
+        def twocall(i):
+            L.laud_mask_gen(xb[i % 4], fxs, Ss, wm, b2, None, mk, ids, cn, None, None, wsm2)
+            L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wsd)
+
+        def fused(i):
+            L.laud_masker_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, wm, b2, None, mk, ids, cn, None, None,
+                                         xb[i % 4], wsd)
+        res = {}
+        for name, fn in (("unfused", unfused), ("two_call", twocall), ("all_fused", fused)):
+            for b in xb:
+                b.copy_(xs)
+            res[name + "_p50_us"] = round(_p50_us(t, fn, iters=12, warm=2), 1)
+        ex["fusion_ablation_" + tag] = res
+        del xb, xs, wsu, wsd
     # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound
     sg = I.STAGES[1]
     x1 = D.to_device(I.feature_map(1000, 1, 56, 56, 256, I.F32), I.F32)

@@ -161,6 +161,20 @@ int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottlenec
                                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The UNFUSED three-step schedule of Sec. 3.1 (gather, compute, scatter), kept as the baseline of
+ * the operator-fusion ablation (Tab. 1): a stand-alone gather of the active patches with their halo
+ * into a dense buffer, the three convolutions on that buffer (conv1 on all (S+2)^2 gathered
+ * positions, with h1 := 0 at positions outside the image; the 3x3 inside the gathered tile; the last
+ * 1x1 into a dense float32 buffer), and a stand-alone scatter that adds the residual.
+ * Same arguments and same result as laud_dyn_bottleneck.  Workspace:
+ * laud_dyn_bottleneck_unfused_workspace(fx, p, S) bytes.
+ */
+size_t laud_dyn_bottleneck_unfused_workspace(laud_fmap fx, const laud_bottleneck* p, int S);
+int laud_dyn_bottleneck_unfused(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                                const int32_t* idx, const int32_t* count, void* out,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Channel-skipping bottleneck (Fig. 2(c); Sec. 3.1-3.2).  cmask is [N][D] bytes; group g of
  * sample n covers mid channels [g*G, (g+1)*G), G = c_mid / D.  The mask multiplies the input
  * and the output of the 3x3 conv; dropped channels are never computed (the weight gather is
@@ -206,7 +220,8 @@ typedef enum {
   LAUD_STAGE_CS1 = 8,
   LAUD_STAGE_CS2 = 9,
   LAUD_STAGE_CS3 = 10,
-  LAUD_STAGE_COUNT = 11
+  LAUD_STAGE_SCATTER = 11,    /* stand-alone scatter + residual add (unfused schedule) */
+  LAUD_STAGE_COUNT = 12
 } laud_stage;
 int laud_stage_timing_enable(int on);
 int laud_stage_timing_read(double* total_ms, int64_t* launches);

@@ -19,9 +19,10 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
-           "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace",
+           "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
+           "laud_dyn_bottleneck_unfused_workspace",
            "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
-STAGE_COUNT = 11
+STAGE_COUNT = 12
 
 
 class Fmap(C.Structure):
@@ -73,6 +74,10 @@ def load() -> C.CDLL:
     lib.laud_masker_dyn_bottleneck.restype = i32
     lib.laud_masker_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, C.c_float, vp, vp, vp, vp,
                                                vp, vp, vp, vp, sz, vp]
+    lib.laud_dyn_bottleneck_unfused_workspace.restype = sz
+    lib.laud_dyn_bottleneck_unfused_workspace.argtypes = [Fmap, C.POINTER(Bottleneck), i32]
+    lib.laud_dyn_bottleneck_unfused.restype = i32
+    lib.laud_dyn_bottleneck_unfused.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
     lib.laud_channel_masker_workspace.restype = sz
     lib.laud_channel_masker_workspace.argtypes = [Fmap]
     lib.laud_channel_masker.restype = i32
@@ -180,6 +185,16 @@ def laud_masker_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, w, bias: floa
     _check(load().laud_masker_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(w), float(bias), _ptr(keep),
                                              _ptr(mask), _ptr(idx), _ptr(count), _ptr(sample_offsets), _ptr(logits),
                                              _ptr(out), wp, wb, _stream()), "laud_masker_dyn_bottleneck")
+
+
+def dyn_bottleneck_unfused_workspace(fx: Fmap, p: Bottleneck, S: int) -> int:
+    return int(load().laud_dyn_bottleneck_unfused_workspace(fx, C.byref(p), int(S)))
+
+
+def laud_dyn_bottleneck_unfused(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_dyn_bottleneck_unfused(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
+                                              wp, wb, _stream()), "laud_dyn_bottleneck_unfused")
 
 
 def channel_masker_workspace(fx: Fmap) -> int:

@@ -16,6 +16,10 @@
 //   DENSE1 conv1 on every pixel, with the one-channel masker's per-pixel projection computed from the
 //          same A slices (Sec. 3.4 "Operator fusion for spatial maskers"; App. B item 1): x is read
 //          once for both.
+//   U1..3  the three convs of the UNFUSED three-step schedule (Sec. 3.1: gather, compute, scatter), on
+//          the densely gathered halo tiles: U1 = conv1 on all (S+2)^2 positions of every active patch
+//          (positions outside the image are written as zeros: the padding is the 3x3's), U2 = 3x3
+//          inside the gathered tile, U3 = last 1x1 into a dense buffer (a separate kernel scatters).
 //   CS1..3 the same three convs for channel skipping (Fig. 2(c)): one sample per blockIdx.y,
 //          output channels / reduction channels gathered through the sample's kept-group list,
 //          i.e. the weight gather is fused into the conv (Sec. 3.4).
@@ -33,7 +37,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk in global memory
 
-enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6 };
+enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6, M_U1 = 7, M_U2 = 8, M_U3 = 9 };
 
 // 256 bytes of zeros in device memory: the source of every chunk that has to read as zero.  Not
 // declared const on purpose: the compiler must treat a load from it like any other load (it would
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   constexpr int AR = BM / RPP, BR = BN / RPP;
   constexpr int TM = BM / 64, TN = BN / (32 * WGN);
   static_assert(AR >= 1 && BR >= 1 && TN >= 1, "tile too small for this many waves");
-  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2);
+  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2 || MODE == M_U2);
   constexpr bool CS = (MODE >= M_CS1 && MODE <= M_CS3);
 
   constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -160,7 +164,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     } else if constexpr (MODE == M_DENSE1) {
       M = a.m_rows;
     } else {
-      M = *a.count * SS;
+      M = *a.count * (MODE == M_U1 ? (a.S + 2) * (a.S + 2) : SS);
     }
   } else {
     rt = blockIdx.x % a.row_tiles;
@@ -220,8 +224,13 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       int y = 0, x = 0;
       if constexpr (MODE == M_CONV1) {
         pixrow = (size_t)listp[rho];
-      } else if constexpr (MODE == M_CONV3 || MODE == M_DENSE1) {
+      } else if constexpr (MODE == M_CONV3 || MODE == M_DENSE1 || MODE == M_U1 || MODE == M_U3) {
         pixrow = (size_t)rho;
+      } else if constexpr (MODE == M_U2) {
+        // row = (patch p, pixel j of the patch); its centre inside the gathered (S+2) x (S+2) tile
+        const int E = a.S + 2;
+        const int p = rho / SS, j = rho - p * SS;
+        pixrow = (size_t)p * E * E + (size_t)(j / a.S + 1) * E + (j % a.S + 1);
       } else if constexpr (MODE == M_CONV2) {
         const int p = rho / SS, j = rho - p * SS;
         const int q = a.list[p];
@@ -238,7 +247,9 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         pixrow = (size_t)sample * HW + rho;
       }
       arow[i] = Ap + pixrow * a.lda + cc * EPC;
-      if constexpr (TAPS) {
+      if constexpr (MODE == M_U2) {
+        amask[i] = 0x1ffu;  // every tap lies inside the gathered tile
+      } else if constexpr (TAPS) {
         unsigned mk = 0;
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
@@ -257,8 +268,16 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     if (rho < M) {
       if constexpr (MODE == M_CONV1) {
         o = listp[rho];
-      } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1) {
+      } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1 || MODE == M_U2 || MODE == M_U3) {
         o = rho;
+      } else if constexpr (MODE == M_U1) {
+        // gathered position (p, e): inside the image -> row rho, outside -> -2 - rho (stored as zeros)
+        const int E = a.S + 2;
+        const int p = rho / (E * E), e = rho - p * (E * E);
+        const int q = a.list[p];
+        const int r2 = q % (Hp * Wp);
+        const int yy = (r2 / Wp) * a.S - 1 + e / E, xx = (r2 % Wp) * a.S - 1 + e % E;
+        o = (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W) ? rho : -2 - rho;
       } else if constexpr (MODE == M_CONV3) {
         const int p = rho / SS, j = rho - p * SS;
         const int q = a.list[p];
@@ -313,7 +332,8 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     ke_out = ke;
     const bool kv = ke < keff && tap < (TAPS ? 9 : 1);  // slices past the end read as zeros
     // wave-uniform element offsets of this slice relative to the row base pointers
-    const long long aoff = TAPS ? (long long)(ld_ky * gW + ld_kx) * glda + kbase : (long long)kbase;
+    const long long aoff = TAPS ? (long long)(ld_ky * (MODE == M_U2 ? a.S + 2 : gW) + ld_kx) * glda + kbase
+                                : (long long)kbase;
     const long long woff = (long long)tap * gK + kbase;
     if (++ld_kc == kchunks) {
       ld_kc = 0; ++ld_tap;
@@ -458,7 +478,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         for (int e = 0; e < 16; ++e) {
           const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           float v = acc[i][j][e] * sc + sh;
-          if constexpr (!(MODE == M_CONV3 || MODE == M_CS3)) v = fmaxf(v, 0.f);
+          if constexpr (!(MODE == M_CONV3 || MODE == M_CS3 || MODE == M_U3)) v = fmaxf(v, 0.f);
           stg[rl * (CSTR / 4) + cl] = v;
         }
       }
@@ -473,8 +493,12 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       const int id = tid + q * NT;
       if (id >= BM * CPR) continue;
       const int rl = id / CPR, chk = id - rl * CPR;
-      const int orow = s_row[rl];
+      int orow = s_row[rl];
       const int col = col0 + chk * EPC;
+      bool zero_row = false;
+      if constexpr (MODE == M_U1) {
+        if (orow <= -2) { orow = -2 - orow; zero_row = true; }
+      }
       if (orow < 0 || col >= ncols) continue;
       const float* sp = reinterpret_cast<const float*>(smem + rl * CSTR) + chk * EPC;
       float v[EPC];
@@ -482,6 +506,10 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       for (int u = 0; u < EPC / 4; ++u) {
         const float4 t4 = reinterpret_cast<const float4*>(sp)[u];
         v[4 * u] = t4.x; v[4 * u + 1] = t4.y; v[4 * u + 2] = t4.z; v[4 * u + 3] = t4.w;
+      }
+      if (zero_row) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) v[e] = 0.f;
       }
       const size_t off = (size_t)orow * a.ldo + col;
       if (col + EPC <= ncols) {
@@ -497,12 +525,21 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
             if (a.relu) v[e] = fmaxf(v[e], 0.f);
           }
         }
-        ET ov[EPC];
+        if constexpr (MODE == M_U3) {
+          // the unfused schedule's branch output stays float32 so that the stand-alone scatter adds
+          // the residual before the only rounding, like the fused epilogue does
+          float* fo = reinterpret_cast<float*>(a.Out) + off;
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) elem<ET>::store(&ov[e], v[e]);
-        uint4 oraw;
-        __builtin_memcpy(&oraw, ov, 16);
-        *reinterpret_cast<uint4*>(Op + off) = oraw;
+          for (int u = 0; u < EPC / 4; ++u)
+            reinterpret_cast<float4*>(fo)[u] = make_float4(v[4 * u], v[4 * u + 1], v[4 * u + 2], v[4 * u + 3]);
+        } else {
+          ET ov[EPC];
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) elem<ET>::store(&ov[e], v[e]);
+          uint4 oraw;
+          __builtin_memcpy(&oraw, ov, 16);
+          *reinterpret_cast<uint4*>(Op + off) = oraw;
+        }
       } else {  // ragged last chunk (channel-skip widths that are not a multiple of the chunk)
         for (int e = 0; e < ncols - col; ++e) {
           float u = v[e];
@@ -675,8 +712,8 @@ static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hi
 
 template <int MODE>
 static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  constexpr int kStage[7] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
-                             LAUD_STAGE_CS1, LAUD_STAGE_CS2, LAUD_STAGE_CS3, LAUD_STAGE_CONV1};
+  constexpr int kStage[10] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CS1, LAUD_STAGE_CS2,
+                              LAUD_STAGE_CS3,   LAUD_STAGE_CONV1, LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3};
   StageScope scope(kStage[MODE], st);
   return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
@@ -852,6 +889,112 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
   a.relu = p->relu_out ? 1 : 0;
   return launch_gemm<M_CONV3>(fx.dtype, a, npix, 1, st);
+}
+
+// Unfused schedule, step 3 (Sec. 3.1): out[pixel] = act(x[pixel] + f[row]) for every pixel of every
+// active patch; one wave per pixel row, 16-byte chunks.
+template <typename ET>
+__global__ __launch_bounds__(256) void k_scatter_add(const float* __restrict__ f, const ET* x, ET* out, int H, int W,
+                                                     int S, int C, int relu, const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ count, long long cap_rows) {
+  constexpr int EPC = elem<ET>::per16;
+  const long long rho = (long long)blockIdx.x * 4 + threadIdx.x / kWave;
+  if (rho >= cap_rows) return;
+  const int SS = S * S, p = (int)(rho / SS), j = (int)(rho - (long long)p * SS);
+  if (p >= *count) return;
+  const int Hp = H / S, Wp = W / S;
+  const int q = idx[p];
+  const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
+  const size_t pix = ((size_t)n * H + (r2 / Wp) * S + j / S) * W + (r2 % Wp) * S + j % S;
+  for (int c = lane_id() * EPC; c < C; c += kWave * EPC) {
+    const float* fp = f + (size_t)rho * C + c;
+    uint4 xv = *reinterpret_cast<const uint4*>(x + pix * C + c);
+    ET xe[EPC], oe[EPC];
+    float fe[EPC];
+#pragma unroll
+    for (int u = 0; u < EPC / 4; ++u) {
+      const float4 t4 = reinterpret_cast<const float4*>(fp)[u];
+      fe[4 * u] = t4.x; fe[4 * u + 1] = t4.y; fe[4 * u + 2] = t4.z; fe[4 * u + 3] = t4.w;
+    }
+    __builtin_memcpy(xe, &xv, 16);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      float v = elem<ET>::load(&xe[e]) + fe[e];
+      if (relu) v = fmaxf(v, 0.f);
+      elem<ET>::store(&oe[e], v);
+    }
+    uint4 ov;
+    __builtin_memcpy(&ov, oe, 16);
+    *reinterpret_cast<uint4*>(out + pix * C + c) = ov;
+  }
+}
+
+struct UnfusedWs { size_t xg, h1g, h2g, fg, bytes; };
+static UnfusedWs unfused_ws_layout(const laud_fmap& fx, int c_mid, int S) {
+  const size_t eb = elem_bytes(fx.dtype), E = (size_t)S + 2;
+  const size_t npatch = (size_t)fx.N * (fx.H / S) * (fx.W / S), npix = (size_t)fx.N * fx.H * fx.W;
+  UnfusedWs w;
+  size_t o = 0;
+  w.xg = o;  o += align_up(npatch * E * E * fx.C * eb, 256);
+  w.h1g = o; o += align_up(npatch * E * E * c_mid * eb, 256);
+  w.h2g = o; o += align_up(npix * c_mid * eb, 256);
+  w.fg = o;  o += align_up(npix * fx.C * sizeof(float), 256);  // branch output stays float32
+  w.bytes = o;
+  return w;
+}
+
+extern "C" size_t laud_dyn_bottleneck_unfused_workspace(laud_fmap fx, const laud_bottleneck* p, int S) {
+  if (!valid_fmap(fx) || !p || p->c_mid <= 0 || S <= 0 || fx.H % S || fx.W % S) return 0;
+  return unfused_ws_layout(fx, p->c_mid, S).bytes;
+}
+
+extern "C" int laud_dyn_bottleneck_unfused(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                                           const int32_t* idx, const int32_t* count, void* out, void* ws,
+                                           size_t ws_bytes, void* stream) {
+  int rc = validate_block(x, fx, p, out);
+  if (rc != LAUD_OK) return rc;
+  if (!idx || !count || S <= 0 || fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
+  const int Hp = fx.H / S, Wp = fx.W / S, E = S + 2;
+  const long long npatch = (long long)fx.N * Hp * Wp, npix = (long long)fx.N * fx.H * fx.W;
+  if (npatch * E * E > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  const UnfusedWs L = unfused_ws_layout(fx, p->c_mid, S);
+  if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = (char*)ws;
+  void *xg = wsb + L.xg, *h1g = wsb + L.h1g, *h2g = wsb + L.h2g, *fg = wsb + L.fg;
+  const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+  // step 1: gather (stand-alone kernel, zero fill outside the image)
+  if ((rc = laud_gather_patches(x, fx, S, 1, idx, count, xg, stream)) != LAUD_OK) return rc;
+  if (x != out) {
+    StageScope scope(LAUD_STAGE_COPY_INACTIVE, st);
+    hipLaunchKernelGGL(k_copy_inactive, dim3((unsigned)npatch), dim3(256), 0, st, (const uint4*)x, (uint4*)out, fx.H,
+                       fx.W, S, cpp, idx, count);
+    if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  }
+  // step 2: the three convolutions on the gathered tiles
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.cmask = nullptr; a.count = count; a.list = idx;
+  a.A = xg; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1g; a.Res = nullptr;
+  a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid; a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
+  if ((rc = launch_gemm<M_U1>(fx.dtype, a, npatch * E * E, 1, st)) != LAUD_OK) return rc;
+  a.A = h1g; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2g;
+  a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid; a.lda = p->c_mid; a.ldo = p->c_mid;
+  if ((rc = launch_gemm<M_U2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  a.A = h2g; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = fg;
+  a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out; a.relu = 0;
+  if ((rc = launch_gemm<M_U3>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  // step 3: scatter + residual add
+  {
+    StageScope scope(LAUD_STAGE_SCATTER, st);
+    const unsigned blocks = (unsigned)((npix + 3) / 4);
+    if (fx.dtype == LAUD_BF16)
+      hipLaunchKernelGGL((k_scatter_add<bf16_t>), dim3(blocks), dim3(256), 0, st, (const float*)fg, (const bf16_t*)x,
+                         (bf16_t*)out, fx.H, fx.W, S, fx.C, p->relu_out ? 1 : 0, idx, count, npix);
+    else
+      hipLaunchKernelGGL((k_scatter_add<float>), dim3(blocks), dim3(256), 0, st, (const float*)fg, (const float*)x,
+                         (float*)out, fx.H, fx.W, S, fx.C, p->relu_out ? 1 : 0, idx, count, npix);
+  }
+  return check_launch();
 }
 
 extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p, const uint8_t* cmask,
