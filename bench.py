@@ -44,12 +44,16 @@ def parse():
     return ap.parse_args()
 
 
-def _p50_us(t, fn, iters=20, warm=3):
+def _p50_us(t, fn, iters=20, warm=3, prep=None):
     for i in range(warm):
+        if prep:
+            prep()
         fn(i)
     t.cuda.synchronize()
     ev = [(t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)) for _ in range(iters)]
     for i in range(iters):
+        if prep:
+            prep()  # untimed
         ev[i][0].record()
         fn(warm + i)
         ev[i][1].record()
@@ -159,6 +163,53 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[name + "_p50_us"] = round(_p50_us(t, fn, iters=12, warm=2), 1)
         ex["fusion_ablation_" + tag] = res
         del xb, xs, wsu, wsd
+    # the 29 dynamic identity blocks of the ResNet-101 body (config 3: 2 + 3 + 22 + 2 blocks of stages 1-4,
+    # granularity 4-4-2-1, batch 128, masker bias calibrated per block to ratio 0.5 on the block's actual
+    # input), chained in place per stage; the static stem and the four projection blocks are not included
+    plan = ((1, 2), (2, 3), (3, 22), (4, 2))
+    blocks = []
+    keepalive = []
+    for stage, nblk in plan:
+        sg = I.STAGES[stage]
+        N, Ss = 128, sg["S"]
+        xs = D.to_device(I.feature_map(7700 + stage, 8, sg["hw"], sg["hw"], sg["c_in"], I.BF16, nonneg=True), I.BF16)
+        xs = xs.repeat(N // 8, 1, 1, 1).contiguous()
+        fxs = L.fmap_of(xs)
+        npatch = N * (sg["hw"] // Ss) ** 2
+        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cn = t.zeros(1, dtype=t.int32, device="cuda")
+        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+        xw = xs.clone()
+        for b in range(nblk):
+            dbs = D.DeviceBottleneck(I.bottleneck_params(7800 + 10 * stage + b, sg["c_in"], sg["m"], sg["c_in"], I.BF16,
+                                                         relu_out=True, s3_gain=0.25))
+            wm = t.from_numpy(I.masker_weights(7900 + 10 * stage + b, sg["c_in"])).cuda()
+            wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+            # calibrate this block's bias on its actual input, then apply the block so the next one sees its output
+            L.laud_mask_gen(xw, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+            t.cuda.synchronize()
+            bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
+            L.laud_masker_dyn_bottleneck(xw, fxs, dbs.desc, Ss, wm, bb, None, mk, ids, cn, None, None, xw, wsd)
+            blocks.append((xs, fxs, dbs, Ss, wm, bb, mk, ids, cn, wsd))
+            keepalive.append((xw, lgs, wsm2))
+    t.cuda.synchronize()
+    work = {id(b[0]): b[0].clone() for b in blocks}
+
+    def body(i):
+        for (xs, fxs, dbs, Ss, wm, bb, mk, ids, cn, wsd) in blocks:
+            xw = work[id(xs)]
+            L.laud_masker_dyn_bottleneck(xw, fxs, dbs.desc, Ss, wm, bb, None, mk, ids, cn, None, None, xw, wsd)
+    def reset():
+        for b in blocks:
+            work[id(b[0])].copy_(b[0])
+    us = _p50_us(t, body, iters=6, warm=1, prep=reset)
+    ex["config3_dynamic_blocks_b128"] = {"blocks": len(blocks), "p50_ms": round(us / 1e3, 3),
+                                         "images_per_s": round(128 / us * 1e6, 0),
+                                         "note": "the 29 dynamic identity blocks only (no stem, no projection blocks); every "
+                                                 "block at activation ratio 0.5 on its actual input"}
+    del blocks, keepalive, work
     # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound
     sg = I.STAGES[1]
     x1 = D.to_device(I.feature_map(1000, 1, 56, 56, 256, I.F32), I.F32)
