@@ -186,6 +186,29 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Static parts of the ResNet body (BASELINE config 3; always executed, no mask).  The paper's
+ * formulation assumes stride 1 inside dynamic blocks (Sec. 3.1); the first block of every stage
+ * (projection shortcut, stride 2 in stages 2-4, placed on the 3x3 as in the torchvision models the
+ * paper starts from) and the stem run as ordinary dense layers.
+ *
+ * laud_static_bottleneck: out = relu(s3*conv1x1(h2;w3)+t3 + s_sc*conv1x1_stride(x;w_sc)+t_sc), with
+ * h1 = relu(affine1(conv1x1(x;w1))), h2 = relu(affine2(conv3x3 stride, pad 1 (h1;w2))).  x is
+ * [N,H,W,c_in]; out is [N,Ho,Wo,c_out] with Ho = (H-1)/stride + 1 (stride 1 or 2) and must not alias x;
+ * w_sc is [c_out][c_in] in x's dtype, s_sc/t_sc float32 [c_out]; p->c_out may differ from p->c_in.
+ *
+ * laud_stem: x [N,Hin,Win,3] dtype; 7x7 stride-2 pad-3 conv with w7 [c_out][7][7][3] (dtype),
+ * affine s,t (float32), ReLU, then 3x3 stride-2 pad-1 max pooling; out [N,Hp,Wp,c_out] with
+ * Hc = (Hin-1)/2 + 1, Hp = (Hc-1)/2 + 1; c_out a multiple of 8, at most 96.
+ */
+size_t laud_static_bottleneck_workspace(laud_fmap fx, const laud_bottleneck* p, int stride);
+int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, const void* w_sc,
+                           const float* s_sc, const float* t_sc, int stride, void* out,
+                           void* ws, size_t ws_bytes, void* stream);
+size_t laud_stem_workspace(int N, int Hin, int Win, int c_out, int dtype);
+int laud_stem(const void* x, int N, int Hin, int Win, int dtype, const void* w7, const float* s,
+              const float* t, int c_out, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Channel masker (Sec. 3.2 "Masker design"; Fig. 3(b)): g = mean of x over H x W per sample and
  * channel; h = relu(wa*g + ba) (the paper does not name the non-linearity; ReLU is assumed);
  * l = wb*h + bb, 2D logits viewed row-major as [D][2]; group d is kept iff l[d][0] > l[d][1]

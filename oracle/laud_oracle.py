@@ -294,3 +294,58 @@ def channel_flops_ratio(rc: float, c_in: int, m: int, c_out: int) -> float:
     """(r*F1 + r^2*F2 + r*F3) / (F1 + F2 + F3)."""
     f1, f2, f3 = conv_macs_per_pixel(c_in, m, c_out)
     return (rc * f1 + rc * rc * f2 + rc * f3) / (f1 + f2 + f3)
+
+
+# --------------------------------------------------------------------------- #
+# static parts of the ResNet body (BASELINE config 3): stem and projection blocks
+# --------------------------------------------------------------------------- #
+def conv2d(x: np.ndarray, w: np.ndarray, stride: int, pad: int) -> np.ndarray:
+    """General cross-correlation, NHWC: out[n,yo,xo,o] = sum_{ky,kx,c} w[o,ky,kx,c] *
+    xpad[n, yo*stride + ky, xo*stride + kx, c], xpad = x with `pad` rings of zeros;
+    output size floor((H + 2*pad - k)/stride) + 1."""
+    x = np.asarray(x, np.float64)
+    w = np.asarray(w, np.float64)
+    n, h, wd, c = x.shape
+    co, kh, kw, _ = w.shape
+    ho = (h + 2 * pad - kh) // stride + 1
+    wo = (wd + 2 * pad - kw) // stride + 1
+    xp = np.zeros((n, h + 2 * pad, wd + 2 * pad, c), np.float64)
+    xp[:, pad:pad + h, pad:pad + wd, :] = x
+    out = np.zeros((n, ho, wo, co), np.float64)
+    for ky in range(kh):
+        for kx in range(kw):
+            win = xp[:, ky:ky + (ho - 1) * stride + 1:stride, kx:kx + (wo - 1) * stride + 1:stride, :]
+            out += np.matmul(win, w[:, ky, kx, :].T)
+    return out
+
+
+def maxpool3x3_s2(x: np.ndarray) -> np.ndarray:
+    """3x3 max pooling, stride 2, padding 1 (padding never wins: -inf)."""
+    x = np.asarray(x, np.float64)
+    n, h, wd, c = x.shape
+    ho, wo = (h + 2 - 3) // 2 + 1, (wd + 2 - 3) // 2 + 1
+    xp = np.full((n, h + 2, wd + 2, c), -np.inf)
+    xp[:, 1:h + 1, 1:wd + 1, :] = x
+    out = np.full((n, ho, wo, c), -np.inf)
+    for ky in range(3):
+        for kx in range(3):
+            out = np.maximum(out, xp[:, ky:ky + (ho - 1) * 2 + 1:2, kx:kx + (wo - 1) * 2 + 1:2, :])
+    return out
+
+
+def stem(x: np.ndarray, w7: np.ndarray, s: np.ndarray, t: np.ndarray) -> np.ndarray:
+    """ResNet stem: 7x7 stride-2 pad-3 conv, affine (folded BN), ReLU, 3x3 stride-2 max pool."""
+    return maxpool3x3_s2(relu(affine(conv2d(x, w7, 2, 3), s, t)))
+
+
+def projection_bottleneck(x: np.ndarray, p: BottleneckParams, w_sc: np.ndarray, s_sc: np.ndarray,
+                          t_sc: np.ndarray, stride: int) -> np.ndarray:
+    """First block of a stage (always executed, no mask): the stride sits on the 3x3 (as in the
+    torchvision models the paper initialises from) and the shortcut is a strided 1x1 conv with its
+    own affine; out = relu(branch + shortcut)."""
+    p = p.as_f64()
+    h1 = relu(affine(conv1x1(x, p.w1), p.s1, p.t1))
+    h2 = relu(affine(conv2d(h1, p.w2, stride, 1), p.s2, p.t2))
+    f = affine(conv1x1(h2, p.w3), p.s3, p.t3)
+    sc = affine(conv2d(x, np.asarray(w_sc, np.float64)[:, None, None, :], stride, 0), s_sc, t_sc)
+    return relu(f + sc)

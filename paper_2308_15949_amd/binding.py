@@ -20,7 +20,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
            "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
-           "laud_dyn_bottleneck_unfused_workspace",
+           "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
+           "laud_stem", "laud_stem_workspace",
            "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
 STAGE_COUNT = 12
 
@@ -78,6 +79,14 @@ def load() -> C.CDLL:
     lib.laud_dyn_bottleneck_unfused_workspace.argtypes = [Fmap, C.POINTER(Bottleneck), i32]
     lib.laud_dyn_bottleneck_unfused.restype = i32
     lib.laud_dyn_bottleneck_unfused.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
+    lib.laud_static_bottleneck_workspace.restype = sz
+    lib.laud_static_bottleneck_workspace.argtypes = [Fmap, C.POINTER(Bottleneck), i32]
+    lib.laud_static_bottleneck.restype = i32
+    lib.laud_static_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.laud_stem_workspace.restype = sz
+    lib.laud_stem_workspace.argtypes = [i32, i32, i32, i32, i32]
+    lib.laud_stem.restype = i32
+    lib.laud_stem.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.laud_channel_masker_workspace.restype = sz
     lib.laud_channel_masker_workspace.argtypes = [Fmap]
     lib.laud_channel_masker.restype = i32
@@ -195,6 +204,26 @@ def laud_dyn_bottleneck_unfused(x, fx: Fmap, p: Bottleneck, S: int, idx, count, 
     wp, wb = _ws_args(ws)
     _check(load().laud_dyn_bottleneck_unfused(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
                                               wp, wb, _stream()), "laud_dyn_bottleneck_unfused")
+
+
+def static_bottleneck_workspace(fx: Fmap, p: Bottleneck, stride: int) -> int:
+    return int(load().laud_static_bottleneck_workspace(fx, C.byref(p), int(stride)))
+
+
+def laud_static_bottleneck(x, fx: Fmap, p: Bottleneck, w_sc, s_sc, t_sc, stride: int, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_static_bottleneck(_ptr(x), fx, C.byref(p), _ptr(w_sc), _ptr(s_sc), _ptr(t_sc), int(stride),
+                                         _ptr(out), wp, wb, _stream()), "laud_static_bottleneck")
+
+
+def stem_workspace(n: int, hin: int, win: int, c_out: int, dtype: int) -> int:
+    return int(load().laud_stem_workspace(int(n), int(hin), int(win), int(c_out), int(dtype)))
+
+
+def laud_stem(x, n: int, hin: int, win: int, dtype: int, w7, s, t, c_out: int, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_stem(_ptr(x), int(n), int(hin), int(win), int(dtype), _ptr(w7), _ptr(s), _ptr(t), int(c_out),
+                            _ptr(out), wp, wb, _stream()), "laud_stem")
 
 
 def channel_masker_workspace(fx: Fmap) -> int:

@@ -20,6 +20,9 @@
 //          the densely gathered halo tiles: U1 = conv1 on all (S+2)^2 positions of every active patch
 //          (positions outside the image are written as zeros: the padding is the 3x3's), U2 = 3x3
 //          inside the gathered tile, U3 = last 1x1 into a dense buffer (a separate kernel scatters).
+//   SD1..3 static dense convs of the always-executed first block of a stage: 1x1 with a spatial stride
+//          (SD1: conv1 with stride 1, shortcut with the block's stride), 3x3 with stride (SD2), last
+//          1x1 with the shortcut already in the output buffer as residual (SD3).
 //   CS1..3 the same three convs for channel skipping (Fig. 2(c)): one sample per blockIdx.y,
 //          output channels / reduction channels gathered through the sample's kept-group list,
 //          i.e. the weight gather is fused into the conv (Sec. 3.4).
@@ -37,7 +40,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk in global memory
 
-enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6, M_U1 = 7, M_U2 = 8, M_U3 = 9 };
+enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6, M_U1 = 7, M_U2 = 8, M_U3 = 9,
+       M_SD1 = 10, M_SD2 = 11, M_SD3 = 12 };
 
 // 256 bytes of zeros in device memory: the source of every chunk that has to read as zero.  Not
 // declared const on purpose: the compiler must treat a load from it like any other load (it would
@@ -66,7 +70,8 @@ struct GemmArgs {
   int D, G;              // CS: groups per sample, channels per group
   int row_tiles, col_tiles;
   int group_rows, tiles_per_group;  // CONV1: pixel lists are kept per group of samples
-  int m_rows;            // DENSE1: number of rows (all pixels), known on the host
+  int m_rows;            // DENSE1, SD1..3: number of rows (all output pixels), known on the host
+  int stride, Ho, Wo;    // SD1, SD2: spatial stride and output size (H, W are the input size)
   const float* wmask;    // DENSE1: masker weights [K] or null
   float* proj;           // DENSE1: per-pixel masker projection sum_c w[c]*x[pixel][c], [m_rows]
 };
@@ -126,7 +131,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   constexpr int AR = BM / RPP, BR = BN / RPP;
   constexpr int TM = BM / 64, TN = BN / (32 * WGN);
   static_assert(AR >= 1 && BR >= 1 && TN >= 1, "tile too small for this many waves");
-  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2 || MODE == M_U2);
+  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2 || MODE == M_U2 || MODE == M_SD2);
   constexpr bool CS = (MODE >= M_CS1 && MODE <= M_CS3);
 
   constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -161,7 +166,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       rt -= g * a.tiles_per_group;
       listp += (size_t)g * a.group_rows;
       M = a.count[g];
-    } else if constexpr (MODE == M_DENSE1) {
+    } else if constexpr (MODE == M_DENSE1 || MODE >= M_SD1) {
       M = a.m_rows;
     } else {
       M = *a.count * (MODE == M_U1 ? (a.S + 2) * (a.S + 2) : SS);
@@ -226,6 +231,14 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         pixrow = (size_t)listp[rho];
       } else if constexpr (MODE == M_CONV3 || MODE == M_DENSE1 || MODE == M_U1 || MODE == M_U3) {
         pixrow = (size_t)rho;
+      } else if constexpr (MODE == M_SD3) {
+        pixrow = (size_t)rho;
+      } else if constexpr (MODE == M_SD1 || MODE == M_SD2) {
+        // row = output pixel (n, yo, xo); the input pixel under it (centre of the 3x3) is (yo*stride, xo*stride)
+        const int n = rho / (a.Ho * a.Wo), r2 = rho - n * (a.Ho * a.Wo);
+        y = (r2 / a.Wo) * a.stride;
+        x = (r2 % a.Wo) * a.stride;
+        pixrow = (size_t)n * HW + (size_t)y * a.W + x;
       } else if constexpr (MODE == M_U2) {
         // row = (patch p, pixel j of the patch); its centre inside the gathered (S+2) x (S+2) tile
         const int E = a.S + 2;
@@ -268,7 +281,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     if (rho < M) {
       if constexpr (MODE == M_CONV1) {
         o = listp[rho];
-      } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1 || MODE == M_U2 || MODE == M_U3) {
+      } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1 || MODE == M_U2 || MODE == M_U3 || MODE >= M_SD1) {
         o = rho;
       } else if constexpr (MODE == M_U1) {
         // gathered position (p, e): inside the image -> row rho, outside -> -2 - rho (stored as zeros)
@@ -416,7 +429,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
 
   constexpr int CPR = BN / EPC;                 // 16-byte output chunks per tile row
   constexpr int EPI = (BM * CPR + NT - 1) / NT;  // epilogue chunks per thread
-  constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3);
+  constexpr bool RES = (MODE == M_CONV3 || MODE == M_CS3 || MODE == M_SD3);
   // Software pipeline: PF register sets hold the slices in flight from L2 / HBM, two LDS stages.
   // Step s multiplies slice s out of stage s%2 while slice s+1 moves from its registers to the other
   // stage and slices s+2 .. s+PF are in flight: one barrier per slice, PF-1 slices of load latency
@@ -478,7 +491,11 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         for (int e = 0; e < 16; ++e) {
           const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           float v = acc[i][j][e] * sc + sh;
-          if constexpr (!(MODE == M_CONV3 || MODE == M_CS3 || MODE == M_U3)) v = fmaxf(v, 0.f);
+          if constexpr (MODE == M_SD1) {
+            if (a.relu) v = fmaxf(v, 0.f);
+          } else if constexpr (!(MODE == M_CONV3 || MODE == M_CS3 || MODE == M_U3 || MODE == M_SD3)) {
+            v = fmaxf(v, 0.f);
+          }
           stg[rl * (CSTR / 4) + cl] = v;
         }
       }
@@ -712,8 +729,9 @@ static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hi
 
 template <int MODE>
 static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  constexpr int kStage[10] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CS1, LAUD_STAGE_CS2,
-                              LAUD_STAGE_CS3,   LAUD_STAGE_CONV1, LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3};
+  constexpr int kStage[13] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CS1, LAUD_STAGE_CS2,
+                              LAUD_STAGE_CS3,   LAUD_STAGE_CONV1, LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
+                              LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3};
   StageScope scope(kStage[MODE], st);
   return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
@@ -995,6 +1013,53 @@ extern "C" int laud_dyn_bottleneck_unfused(const void* x, laud_fmap fx, const la
                          (float*)out, fx.H, fx.W, S, fx.C, p->relu_out ? 1 : 0, idx, count, npix);
   }
   return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------
+// static first block of a stage (projection shortcut, optional stride on the 3x3)
+// ------------------------------------------------------------------------------------------------
+extern "C" size_t laud_static_bottleneck_workspace(laud_fmap fx, const laud_bottleneck* p, int stride) {
+  if (!valid_fmap(fx) || !p || p->c_mid <= 0 || (stride != 1 && stride != 2)) return 0;
+  const size_t eb = elem_bytes(fx.dtype), npix = (size_t)fx.N * fx.H * fx.W;
+  const size_t nout = (size_t)fx.N * ((fx.H - 1) / stride + 1) * ((fx.W - 1) / stride + 1);
+  return align_up(npix * p->c_mid * eb, 256) + align_up(nout * p->c_mid * eb, 256);
+}
+
+extern "C" int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, const void* w_sc,
+                                      const float* s_sc, const float* t_sc, int stride, void* out, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  if (!x || !out || !p || !w_sc || !s_sc || !t_sc || !valid_fmap(fx) || x == out) return LAUD_ERR_INVALID_ARG;
+  if (!p->w1 || !p->w2 || !p->w3 || !p->s1 || !p->t1 || !p->s2 || !p->t2 || !p->s3 || !p->t3)
+    return LAUD_ERR_INVALID_ARG;
+  if (p->c_in != fx.C || p->c_mid <= 0 || p->c_out <= 0 || (stride != 1 && stride != 2)) return LAUD_ERR_INVALID_ARG;
+  if (p->c_in % 8 || p->c_mid % 8 || p->c_out % 8) return LAUD_ERR_UNSUPPORTED;
+  const int Ho = (fx.H - 1) / stride + 1, Wo = (fx.W - 1) / stride + 1;  // 3x3 pad 1 and 1x1 pad 0 agree on this
+  const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
+  if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < laud_static_bottleneck_workspace(fx, p, stride)) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  void* h1 = ws;
+  void* h2 = (char*)ws + align_up((size_t)npix * p->c_mid * elem_bytes(fx.dtype), 256);
+  int rc;
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = 1; a.D = 1; a.G = 1; a.Ho = Ho; a.Wo = Wo;
+  // shortcut: strided 1x1 + affine, straight into the output buffer
+  a.A = x; a.Wt = w_sc; a.scale = s_sc; a.shift = t_sc; a.Out = out; a.K = p->c_in; a.ldw = p->c_in;
+  a.Ncols = p->c_out; a.lda = p->c_in; a.ldo = p->c_out; a.relu = 0; a.stride = stride; a.m_rows = (int)nout;
+  if ((rc = launch_gemm<M_SD1>(fx.dtype, a, nout, 1, st)) != LAUD_OK) return rc;
+  // conv1 on every input pixel
+  a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
+  a.stride = 1; a.Ho = fx.H; a.Wo = fx.W; a.m_rows = (int)npix;
+  if ((rc = launch_gemm<M_SD1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  // conv2: 3x3, pad 1, the block's stride
+  a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2; a.K = p->c_mid; a.ldw = 9 * p->c_mid;
+  a.lda = p->c_mid; a.stride = stride; a.Ho = Ho; a.Wo = Wo; a.m_rows = (int)nout;
+  if ((rc = launch_gemm<M_SD2>(fx.dtype, a, nout, 1, st)) != LAUD_OK) return rc;
+  // conv3 + shortcut (already in `out`) + ReLU
+  a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = out; a.K = p->c_mid;
+  a.ldw = p->c_mid; a.Ncols = p->c_out; a.ldo = p->c_out; a.relu = 1;
+  return launch_gemm<M_SD3>(fx.dtype, a, nout, 1, st);
 }
 
 extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p, const uint8_t* cmask,

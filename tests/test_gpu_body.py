@@ -1,0 +1,129 @@
+"""GPU parity of the static parts of the ResNet body (stem, projection blocks) and of a reduced
+body run (BASELINE config 3 in miniature: stem, then per stage one static first block followed by
+dynamic identity blocks), block by block against the CPU oracle fed with each block's actual input."""
+import numpy as np
+import pytest
+
+from oracle import laud_oracle as O
+from paper_2308_15949_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+TOL = {I.F32: 1e-4, I.BF16: 2e-2}
+
+
+def close(got, ref, tol):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    err = np.abs(got - ref)
+    assert np.all(err <= tol * (np.abs(ref) + rms)), f"max err {err.max():.3e}, rms {rms:.3e}"
+
+
+def oparams(hb):
+    return O.BottleneckParams(hb.w1, hb.w2, hb.w3, hb.s1, hb.t1, hb.s2, hb.t2, hb.s3, hb.t3, hb.relu_out)
+
+
+def shortcut_params(seed, c_in, c_out, dt):
+    g = np.random.default_rng(seed)
+    w = I.round_to(g.standard_normal((c_out, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), dt)
+    return w, (0.5 * (1 + 0.1 * g.standard_normal(c_out))).astype(np.float32), (0.1 * g.standard_normal(c_out)).astype(np.float32)
+
+
+@pytest.mark.parametrize("case", [(2, 33, 21, 16, I.F32), (2, 64, 64, 64, I.BF16), (1, 224, 224, 64, I.BF16)])
+def test_stem(case):
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    N, Hin, Win, co, dt = case
+    g = np.random.default_rng(600 + Hin)
+    x = I.round_to(g.standard_normal((N, Hin, Win, 3), dtype=np.float32), dt)
+    w7 = I.round_to(g.standard_normal((co, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), dt)
+    s = (1 + 0.1 * g.standard_normal(co)).astype(np.float32)
+    tt = (0.1 * g.standard_normal(co)).astype(np.float32)
+    ref = O.stem(x, w7, s, tt)
+    xd, wd = D.to_device(x, dt), D.to_device(w7, dt)
+    out = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+    ws = D.workspace(L.stem_workspace(N, Hin, Win, co, dt))
+    L.laud_stem(xd, N, Hin, Win, dt, wd, t.from_numpy(s).cuda(), t.from_numpy(tt).cuda(), co, out, ws)
+    t.cuda.synchronize()
+    close(D.to_host(out), ref, TOL[dt])
+
+
+@pytest.mark.parametrize("case", [
+    (2, 12, 10, 16, 8, 32, 1, I.F32), (2, 12, 10, 16, 8, 32, 2, I.F32), (3, 9, 7, 40, 24, 64, 2, I.F32),
+    (2, 56, 56, 64, 64, 256, 1, I.BF16), (2, 56, 56, 256, 128, 512, 2, I.BF16), (2, 14, 14, 1024, 512, 2048, 2, I.BF16)])
+def test_static_projection_block(case):
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    N, H, W, ci, m, co, stride, dt = case
+    x = I.feature_map(610 + ci, N, H, W, ci, dt)
+    hb = I.bottleneck_params(611 + ci, ci, m, co, dt, relu_out=True, s3_gain=0.5)
+    wsc, ssc, tsc = shortcut_params(612 + ci, ci, co, dt)
+    ref = O.projection_bottleneck(x, oparams(hb), wsc, ssc, tsc, stride)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    out = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+    ws = D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride))
+    ws.fill_(0xFF)
+    L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(), t.from_numpy(tsc).cuda(),
+                             stride, out, ws)
+    t.cuda.synchronize()
+    assert np.array_equal(D.to_host(xd), x)   # the input is left alone
+    close(D.to_host(out), ref, TOL[dt])
+
+
+def test_reduced_body_block_by_block():
+    """64x64 images, stem to 16x16x64, then stages 1-3 with widths 64/128/256 (x4), granularity 4-4-2: one
+    static first block and two dynamic identity blocks per stage, masks from each block's masker at ratio 0.5."""
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    dt, N = I.BF16, 4
+    g = np.random.default_rng(620)
+    img = I.round_to(g.standard_normal((N, 64, 64, 3), dtype=np.float32), dt)
+    w7 = I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), dt)
+    s7, t7 = (1 + 0.1 * g.standard_normal(64)).astype(np.float32), (0.1 * g.standard_normal(64)).astype(np.float32)
+    xd = t.empty((N, 16, 16, 64), dtype=t.bfloat16, device="cuda")
+    L.laud_stem(D.to_device(img, dt), N, 64, 64, dt, D.to_device(w7, dt), t.from_numpy(s7).cuda(), t.from_numpy(t7).cuda(),
+                64, xd, D.workspace(L.stem_workspace(N, 64, 64, 64, dt)))
+    t.cuda.synchronize()
+    close(D.to_host(xd), O.stem(img, w7, s7, t7), TOL[dt])
+    c_in, hw = 64, 16
+    for stage, (m, S, stride) in enumerate(((64, 4, 1), (128, 4, 2), (256, 2, 2)), start=1):
+        co = 4 * m
+        # static first block
+        x_in = D.to_host(xd)
+        hb = I.bottleneck_params(630 + stage, c_in, m, co, dt, relu_out=True, s3_gain=0.5)
+        wsc, ssc, tsc = shortcut_params(640 + stage, c_in, co, dt)
+        fx = L.fmap_of(xd)
+        db = D.DeviceBottleneck(hb)
+        hw = (hw - 1) // stride + 1
+        out = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+        L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(), t.from_numpy(tsc).cuda(),
+                                 stride, out, D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride)))
+        t.cuda.synchronize()
+        close(D.to_host(out), O.projection_bottleneck(x_in, oparams(hb), wsc, ssc, tsc, stride), TOL[dt])
+        xd, c_in = out, co
+        fx = L.fmap_of(xd)
+        npatch = N * (hw // S) ** 2
+        mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.zeros(1, dtype=t.int32, device="cuda")
+        for blk in range(2):
+            x_in = D.to_host(xd)
+            hb = I.bottleneck_params(650 + 10 * stage + blk, co, m, co, dt, relu_out=True, s3_gain=0.25)
+            w = I.masker_weights(660 + 10 * stage + blk, co)
+            ref0 = O.mask_logits(x_in, S, w, 0.0)
+            bias, _ = I.bias_for_ratio(ref0, 0.5)
+            db = D.DeviceBottleneck(hb)
+            L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None,
+                                         None, xd, D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S)))
+            t.cuda.synchronize()
+            gm = mask.cpu().numpy().reshape(N, hw // S, hw // S)
+            assert np.array_equal(gm, O.threshold(ref0 + bias))
+            got = D.to_host(xd)
+            ref = O.dyn_bottleneck(x_in, oparams(hb), S, gm)
+            up = O.upsample_mask(gm, S).astype(bool)
+            assert np.array_equal(got[~up], x_in[~up])
+            close(got[up], ref[up], TOL[dt])

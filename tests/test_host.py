@@ -104,6 +104,26 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert fm(vp(FAKE), fx, C.byref(p), 2, None, 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
     assert fm(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need - 1, st) == B.ERR_WORKSPACE
     assert fm(vp(FAKE), fx, C.byref(p), 3, vp(FAKE), 0.0, None, vp(FAKE), vp(FAKE), vp(FAKE), None, None, vp(FAKE), vp(FAKE), need, st) == B.ERR_INVALID_ARG
+    # unfused schedule, static block, stem
+    uf = lib.laud_dyn_bottleneck_unfused
+    needu = lib.laud_dyn_bottleneck_unfused_workspace(fx, C.byref(p), 2)
+    assert needu > need
+    assert uf(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needu - 1, st) == B.ERR_WORKSPACE
+    assert uf(vp(FAKE), fx, C.byref(p), 3, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needu, st) == B.ERR_INVALID_ARG
+    sb = lib.laud_static_bottleneck
+    pw = _bn(64, 16, 128)
+    needs = lib.laud_static_bottleneck_workspace(fx, C.byref(pw), 2)
+    assert needs >= 2 * 64 * 16 * 4 + 2 * 16 * 16 * 4
+    assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, vp(FAKE + (1 << 20)), vp(FAKE), needs - 1, st) == B.ERR_WORKSPACE
+    assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 3, vp(FAKE + (1 << 20)), vp(FAKE), needs, st) == B.ERR_INVALID_ARG
+    assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, vp(FAKE), vp(FAKE), needs, st) == B.ERR_INVALID_ARG  # out == x
+    assert sb(vp(FAKE), fx, C.byref(pw), None, vp(FAKE), vp(FAKE), 2, vp(FAKE + (1 << 20)), vp(FAKE), needs, st) == B.ERR_INVALID_ARG
+    sm = lib.laud_stem
+    nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
+    assert nst == 2 * 32 * 32 * 64 * 2
+    assert sm(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 64, vp(FAKE), vp(FAKE), nst - 1, st) == B.ERR_WORKSPACE
+    assert sm(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 100, vp(FAKE), vp(FAKE), 1 << 30, st) == B.ERR_UNSUPPORTED
+    assert sm(vp(FAKE), 2, 64, 64, 5, vp(FAKE), vp(FAKE), vp(FAKE), 64, vp(FAKE), vp(FAKE), nst, st) == B.ERR_INVALID_ARG
     # channel masker
     km = lib.laud_channel_masker
     wsk = lib.laud_channel_masker_workspace(fx)

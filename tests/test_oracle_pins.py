@@ -481,3 +481,46 @@ def test_channel_masker_vs_pure_python_and_hand_example():
     h = np.maximum(g @ wa.T + ba, 0)
     diff = h @ (wb[0::2] - wb[1::2]).T + (bb[0::2] - bb[1::2])
     assert np.array_equal(O.channel_mask_from_logits(l2), (diff > 0).astype(np.uint8))
+
+
+# --------------------------------------------------------------------------- #
+# static parts of the body: library special cases (torch conv2d / max_pool2d)
+# --------------------------------------------------------------------------- #
+def test_conv2d_maxpool_stem_and_projection_block_vs_torch():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(40)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).double()
+    nchw = lambda a: t(a).permute(0, 3, 1, 2)
+    oihw = lambda w: t(w).permute(0, 3, 1, 2)
+    back = lambda y: y.permute(0, 2, 3, 1).numpy()
+    ch = lambda v: t(v).view(1, -1, 1, 1)
+    x = rng.standard_normal((2, 13, 10, 3))
+    for k, s_, p_ in ((7, 2, 3), (3, 2, 1), (3, 1, 1), (1, 2, 0)):
+        w = rng.standard_normal((5, k, k, 3))
+        np.testing.assert_allclose(O.conv2d(x, w, s_, p_), back(F.conv2d(nchw(x), oihw(w), stride=s_, padding=p_)),
+                                   rtol=1e-11, atol=1e-11)
+    # conv2d with stride 1 pad 1 is the 3x3 the dynamic block uses
+    w3 = rng.standard_normal((4, 3, 3, 3))
+    np.testing.assert_allclose(O.conv2d(x, w3, 1, 1), O.conv3x3(x, w3), rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(O.maxpool3x3_s2(x), back(F.max_pool2d(nchw(x), 3, 2, 1)))
+    xn = -np.abs(x) - 1.0   # all-negative input: zero padding would win, -inf padding must not
+    np.testing.assert_array_equal(O.maxpool3x3_s2(xn), back(F.max_pool2d(nchw(xn), 3, 2, 1)))
+    # stem
+    w7, s, tt = rng.standard_normal((6, 7, 7, 3)), 1 + 0.2 * rng.standard_normal(6), rng.standard_normal(6)
+    xs = rng.standard_normal((2, 32, 24, 3))
+    want = F.max_pool2d(F.relu(F.conv2d(nchw(xs), oihw(w7), stride=2, padding=3) * ch(s) + ch(tt)), 3, 2, 1)
+    np.testing.assert_allclose(O.stem(xs, w7, s, tt), back(want), rtol=1e-11, atol=1e-11)
+    # projection block, stride 1 and 2
+    for stride in (1, 2):
+        c_in, m, c_out = 6, 4, 16
+        xb = rng.standard_normal((2, 8, 6, c_in))
+        p = _rand_params(rng, c_in, m, c_out)
+        wsc, ssc, tsc = rng.standard_normal((c_out, c_in)), 1 + 0.2 * rng.standard_normal(c_out), rng.standard_normal(c_out)
+        xt = nchw(xb)
+        h1 = F.relu(F.conv2d(xt, t(p.w1)[:, :, None, None]) * ch(p.s1) + ch(p.t1))
+        h2 = F.relu(F.conv2d(h1, oihw(p.w2), stride=stride, padding=1) * ch(p.s2) + ch(p.t2))
+        f = F.conv2d(h2, t(p.w3)[:, :, None, None]) * ch(p.s3) + ch(p.t3)
+        sc = F.conv2d(xt, t(wsc)[:, :, None, None], stride=stride) * ch(ssc) + ch(tsc)
+        np.testing.assert_allclose(O.projection_bottleneck(xb, p, wsc, ssc, tsc, stride), back(F.relu(f + sc)),
+                                   rtol=1e-11, atol=1e-11)
