@@ -238,7 +238,7 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
     ex["config3_resnet101_body_b128"] = {
         "p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0), "dynamic_blocks": ndyn,
         "static_blocks": 4, "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()},
-        "note": "stem (direct 7x7 conv + max pool, untuned) + 4 projection blocks + 29 dynamic identity blocks at "
+        "note": "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at "
                 "activation ratio 0.5 each; the stem's kernels carry no stage label"}
     del ops, keep
     # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound

@@ -198,7 +198,7 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
  *
  * laud_stem: x [N,Hin,Win,3] dtype; 7x7 stride-2 pad-3 conv with w7 [c_out][7][7][3] (dtype),
  * affine s,t (float32), ReLU, then 3x3 stride-2 pad-1 max pooling; out [N,Hp,Wp,c_out] with
- * Hc = (Hin-1)/2 + 1, Hp = (Hc-1)/2 + 1; c_out a multiple of 8, at most 96.
+ * Hc = (Hin-1)/2 + 1, Hp = (Hc-1)/2 + 1; c_out a multiple of 8.
  */
 size_t laud_static_bottleneck_workspace(laud_fmap fx, const laud_bottleneck* p, int stride);
 int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, const void* w_sc,

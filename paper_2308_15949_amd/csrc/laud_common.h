@@ -83,6 +83,11 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
                         float* logits, int32_t* idx, int32_t* count, int32_t* sample_offsets, int32_t* block_counts,
                         hipStream_t stream);
 
+// Dense GEMM + per-column affine (+ ReLU) on the MFMA kernels of laud_gemm.hip:
+// Out[r][c] = act(scale[c] * sum_k A[r][k] * Wt[c][k] + shift[c]), A [rows][K], Wt [ncols][K], all of `dtype`.
+int launch_dense_affine(int dtype, const void* A, const void* Wt, const float* scale, const float* shift, void* Out,
+                        long long rows, int K, int ncols, int relu, hipStream_t stream);
+
 // Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
 extern bool g_stage_timing_on;
 void stage_mark(int stage, hipStream_t stream, bool begin);

@@ -777,6 +777,15 @@ static CsWs cs_ws_layout(const laud_fmap& fx, int c_mid) {
   return w;
 }
 
+int launch_dense_affine(int dtype, const void* A, const void* Wt, const float* scale, const float* shift, void* Out,
+                        long long rows, int K, int ncols, int relu, hipStream_t stream) {
+  GemmArgs a{};
+  a.H = 1; a.W = 1; a.S = 1; a.D = 1; a.G = 1; a.Ho = 1; a.Wo = 1; a.stride = 1;  // one "pixel" per row
+  a.A = A; a.Wt = Wt; a.scale = scale; a.shift = shift; a.Out = Out; a.K = K; a.ldw = K; a.Ncols = ncols;
+  a.lda = K; a.ldo = ncols; a.relu = relu; a.m_rows = (int)rows;
+  return launch_gemm<M_SD1>(dtype, a, rows, 1, stream);
+}
+
 }  // namespace laud
 
 using namespace laud;

@@ -120,9 +120,9 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert sb(vp(FAKE), fx, C.byref(pw), None, vp(FAKE), vp(FAKE), 2, vp(FAKE + (1 << 20)), vp(FAKE), needs, st) == B.ERR_INVALID_ARG
     sm = lib.laud_stem
     nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
-    assert nst == 2 * 32 * 32 * 64 * 2
+    assert nst >= 2 * 32 * 32 * (152 + 64) * 2
     assert sm(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 64, vp(FAKE), vp(FAKE), nst - 1, st) == B.ERR_WORKSPACE
-    assert sm(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 100, vp(FAKE), vp(FAKE), 1 << 30, st) == B.ERR_UNSUPPORTED
+    assert sm(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 60, vp(FAKE), vp(FAKE), 1 << 30, st) == B.ERR_UNSUPPORTED
     assert sm(vp(FAKE), 2, 64, 64, 5, vp(FAKE), vp(FAKE), vp(FAKE), 64, vp(FAKE), vp(FAKE), nst, st) == B.ERR_INVALID_ARG
     # channel masker
     km = lib.laud_channel_masker
