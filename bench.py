@@ -163,84 +163,107 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[name + "_p50_us"] = round(_p50_us(t, fn, iters=12, warm=2), 1)
         ex["fusion_ablation_" + tag] = res
         del xb, xs, wsu, wsd
-    # BASELINE config 3: the whole dynamic ResNet-101 body at batch 128, bf16 -- static stem, per stage one
-    # static projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks at granularity
-    # 4-4-2-1, every masker's bias calibrated to ratio 0.5 on the block's actual input; random-init weights
-    # (s3 gain 0.25 so that the residual stream stays O(1)).  The run starts from the image every time.
-    N = 128
-    g = np.random.default_rng(7700)
-    img8 = I.round_to(g.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16)
-    img = D.to_device(img8, I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
-    w7 = D.to_device(I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), I.BF16), I.BF16)
-    s7 = t.from_numpy((1 + 0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
-    t7 = t.from_numpy((0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
-    x0 = t.empty((N, 56, 56, 64), dtype=t.bfloat16, device="cuda")
-    ws_stem = D.workspace(L.stem_workspace(N, 224, 224, 64, I.BF16))
-    ops = [lambda: L.laud_stem(img, N, 224, 224, I.BF16, w7, s7, t7, 64, x0, ws_stem)]
-    ops[0]()
-    cur, c_in, hw = x0, 64, 56
-    keep = [img, w7, s7, t7, x0, ws_stem]
-    ndyn = 0
-    for stage, nblk in ((1, 3), (2, 4), (3, 23), (4, 3)):
-        sg = I.STAGES[stage]
-        m, Ss, stride = sg["m"], sg["S"], (1 if stage == 1 else 2)
-        co = 4 * m
-        hw = (hw - 1) // stride + 1
-        fin = L.fmap_of(cur)
-        dbp = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage, c_in, m, co, I.BF16, relu_out=True, s3_gain=0.5))
-        gs = np.random.default_rng(7801 + 100 * stage)
-        wsc = D.to_device(I.round_to(gs.standard_normal((co, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), I.BF16), I.BF16)
-        ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
-        tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
-        xs = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
-        wsp = D.workspace(L.static_bottleneck_workspace(fin, dbp.desc, stride))
-        op = (lambda cur=cur, fin=fin, dbp=dbp, wsc=wsc, ssc=ssc, tsc=tsc, stride=stride, xs=xs, wsp=wsp:
-              L.laud_static_bottleneck(cur, fin, dbp.desc, wsc, ssc, tsc, stride, xs, wsp))
-        op()
-        ops.append(op)
-        keep += [dbp, wsc, ssc, tsc, xs, wsp]
-        fxs = L.fmap_of(xs)
-        npatch = N * (hw // Ss) ** 2
-        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
-        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
-        cn = t.zeros(1, dtype=t.int32, device="cuda")
-        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
-        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
-        wsd = None
-        for bidx in range(1, nblk):
-            dbs = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage + bidx, co, m, co, I.BF16, relu_out=True,
-                                                         s3_gain=0.25))
-            wm = t.from_numpy(I.masker_weights(7900 + 100 * stage + bidx, co)).cuda()
-            if wsd is None:
-                wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
-            L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
-            t.cuda.synchronize()
-            bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
-            op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, mk=mk, ids=ids, cn=cn, wsd=wsd:
-                  L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, None, mk, ids, cn, None, None, xs, wsd))
+    # BASELINE configs 3 and 5: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
+    # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
+    # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.
+    #   config 3: batch 128, spatial maskers at granularity 4-4-2-1 in all stages, every masker's bias
+    #             calibrated to ratio 0.5 on the block's actual input
+    #   config 5: batch 256, a seeded Bernoulli(0.6) keep gate per sample and block (layer skipping: the kept
+    #             samples are compacted, S = H), AND-ed with spatial maskers (S = 2, ratio 0.5) in stage 3
+    def run_body(N, keep_p, spatial_stages):
+        g = np.random.default_rng(7700)
+        img8 = I.round_to(g.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16)
+        img = D.to_device(img8, I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        w7 = D.to_device(I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), I.BF16), I.BF16)
+        s7 = t.from_numpy((1 + 0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
+        t7 = t.from_numpy((0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
+        x0 = t.empty((N, 56, 56, 64), dtype=t.bfloat16, device="cuda")
+        ws_stem = D.workspace(L.stem_workspace(N, 224, 224, 64, I.BF16))
+        ops = [lambda: L.laud_stem(img, N, 224, 224, I.BF16, w7, s7, t7, 64, x0, ws_stem)]
+        ops[0]()
+        cur, c_in, hw = x0, 64, 56
+        held = [img, w7, s7, t7, x0, ws_stem]
+        ndyn, act = 0, []
+        wc = D.workspace(4096)
+        for stage, nblk in ((1, 3), (2, 4), (3, 23), (4, 3)):
+            sg = I.STAGES[stage]
+            m, stride = sg["m"], (1 if stage == 1 else 2)
+            co = 4 * m
+            hw = (hw - 1) // stride + 1
+            spatial = stage in spatial_stages
+            Ss = sg["S"] if spatial else hw
+            fin = L.fmap_of(cur)
+            dbp = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage, c_in, m, co, I.BF16, relu_out=True, s3_gain=0.5))
+            gs = np.random.default_rng(7801 + 100 * stage)
+            wsc = D.to_device(I.round_to(gs.standard_normal((co, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), I.BF16), I.BF16)
+            ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
+            tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
+            xs = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+            wsp = D.workspace(L.static_bottleneck_workspace(fin, dbp.desc, stride))
+            op = (lambda cur=cur, fin=fin, dbp=dbp, wsc=wsc, ssc=ssc, tsc=tsc, stride=stride, xs=xs, wsp=wsp:
+                  L.laud_static_bottleneck(cur, fin, dbp.desc, wsc, ssc, tsc, stride, xs, wsp))
             op()
             ops.append(op)
-            keep += [dbs, wm]
-            ndyn += 1
-        keep += [mk, ids, cn, lgs, wsm2, wsd]
-        cur, c_in = xs, co
-    t.cuda.synchronize()
+            held += [dbp, wsc, ssc, tsc, xs, wsp]
+            fxs = L.fmap_of(xs)
+            npatch = N * (hw // Ss) ** 2
+            mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+            ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+            cn = t.zeros(1, dtype=t.int32, device="cuda")
+            lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+            wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+            wsd = None
+            for bidx in range(1, nblk):
+                dbs = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage + bidx, co, m, co, I.BF16, relu_out=True,
+                                                             s3_gain=0.25))
+                if wsd is None:
+                    wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+                kp = None
+                if keep_p is not None:
+                    kp = t.from_numpy(I.bernoulli_mask(8000 + 100 * stage + bidx, (N,), keep_p)).cuda()
+                    held.append(kp)
+                if spatial:
+                    wm = t.from_numpy(I.masker_weights(7900 + 100 * stage + bidx, co)).cuda()
+                    L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+                    t.cuda.synchronize()
+                    bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, kp=kp, mk=mk, ids=ids, cn=cn, wsd=wsd:
+                          L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, kp, mk, ids, cn, None, None, xs, wsd))
+                    held.append(wm)
+                else:  # layer skipping only: the gate is the mask, one "patch" per sample
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, kp=kp, ids=ids, cn=cn, wsd=wsd: (
+                          L.laud_layer_skip_compact(kp, N, ids, cn, wc),
+                          L.laud_dyn_bottleneck(xs, fxs, dbs.desc, Ss, ids, cn, xs, wsd)))
+                op()
+                act.append(float(cn.item()) / npatch)
+                ops.append(op)
+                held.append(dbs)
+                ndyn += 1
+            held += [mk, ids, cn, lgs, wsm2, wsd]
+            cur, c_in = xs, co
+        t.cuda.synchronize()
 
-    def body(i):
-        for op in ops:
-            op()
-    us = _p50_us(t, body, iters=5, warm=1)
-    L.laud_stage_timing_enable(True)
-    body(0)
-    t.cuda.synchronize()
-    st_body = L.laud_stage_timing_read()
-    L.laud_stage_timing_enable(False)
-    ex["config3_resnet101_body_b128"] = {
-        "p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0), "dynamic_blocks": ndyn,
-        "static_blocks": 4, "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()},
-        "note": "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at "
-                "activation ratio 0.5 each; the stem's kernels carry no stage label"}
-    del ops, keep
+        def body(i):
+            for op in ops:
+                op()
+        us = _p50_us(t, body, iters=5, warm=1)
+        L.laud_stage_timing_enable(True)
+        body(0)
+        t.cuda.synchronize()
+        st_body = L.laud_stage_timing_read()
+        L.laud_stage_timing_enable(False)
+        return {"p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0), "dynamic_blocks": ndyn,
+                "static_blocks": 4, "mean_activation_ratio": round(float(np.mean(act)), 3),
+                "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()}}
+
+    ex["config3_resnet101_body_b128"] = dict(run_body(128, None, (1, 2, 3, 4)), note=(
+        "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at activation "
+        "ratio 0.5 each; the stem's kernels carry no stage label"))
+    t.cuda.empty_cache()
+    ex["config5_resnet101_body_b256_layer_skip"] = dict(run_body(256, 0.6, (3,)), note=(
+        "per-sample per-block keep gates Bernoulli(0.6): stages 1, 2, 4 skip whole samples (S = H), stage 3 "
+        "combines the gate with spatial maskers S = 2 at ratio 0.5 of the patches"))
+    t.cuda.empty_cache()
     # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound
     sg = I.STAGES[1]
     x1 = D.to_device(I.feature_map(1000, 1, 56, 56, 256, I.F32), I.F32)

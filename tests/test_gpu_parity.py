@@ -287,9 +287,10 @@ def test_dyn_bottleneck_deterministic(G):
 # layer skipping (laud_layer_skip_compact + laud_dyn_bottleneck with S = H, and the gate in mask_gen)
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dt", [I.F32, I.BF16])
-def test_layer_skip_block(G, dt):
+@pytest.mark.parametrize("H,C,m", [(14, 64, 32), (28, 32, 16), (56, 32, 16), (7, 128, 32)])
+def test_layer_skip_block(G, dt, H, C, m):
     t, L, D = G.torch, G.L, G.D
-    N, H, C, m = 6, 14, 64, 32
+    N = 6
     x = I.feature_map(61, N, H, H, C, dt)
     hb = I.bottleneck_params(62, C, m, C, dt, True)
     keep = np.array([1, 0, 0, 1, 1, 0], np.uint8)
