@@ -87,8 +87,6 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
     for stage in (1, 2, 3, 4):
         sg = I.STAGES[stage]
         for name, N in (("dyn", 128), ("chan", 64)):
-            if name == "dyn" and stage == 3:
-                continue
             xs = D.to_device(I.feature_map(7000 + stage, 8, sg["hw"], sg["hw"], sg["c_in"], I.BF16), I.BF16)
             xs = xs.repeat(N // 8, 1, 1, 1).contiguous()
             fxs = L.fmap_of(xs)
@@ -97,18 +95,29 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             xb = [xs.clone() for _ in range(4)]
             flops_img = 2.0 * 17 * sg["m"] ** 2 * sg["hw"] ** 2
             if name == "dyn":
-                Ss = sg["S"]
-                npatch = N * (sg["hw"] // Ss) ** 2
-                mk = t.from_numpy(I.bernoulli_mask(7200 + stage, (npatch,), 0.5)).cuda()
-                ids = t.zeros(npatch, dtype=t.int32, device="cuda")
-                cn = t.zeros(1, dtype=t.int32, device="cuda")
-                L.laud_layer_skip_compact(mk, npatch, ids, cn, D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, npatch)))
-                wss = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
-                us = _p50_us(t, lambda i: L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wss))
-                r = float(cn.item()) / npatch
-                ex[f"dyn_bottleneck_stage{stage}_b128_r050"] = {
-                    "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
-                    "mfma_frac_useful": round(r * N * flops_img / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+                # latency against the granularity S at a fixed ratio (the shape of the paper's Fig. 6(b)):
+                # every S that divides the feature size, Bernoulli(0.5) patches, index list + block
+                curve = {}
+                for Ss in [d for d in range(1, sg["hw"] + 1) if sg["hw"] % d == 0]:
+                    npatch = N * (sg["hw"] // Ss) ** 2
+                    mk = t.from_numpy(I.bernoulli_mask(7200 + stage, (npatch,), 0.5)).cuda()
+                    ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+                    cn = t.zeros(1, dtype=t.int32, device="cuda")
+                    wsc = D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, npatch))
+                    wss = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+
+                    def blk(i):
+                        L.laud_layer_skip_compact(mk, npatch, ids, cn, wsc)
+                        L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wss)
+                    us = _p50_us(t, blk, iters=12, warm=2)
+                    r = float(cn.item()) / npatch
+                    curve[str(Ss)] = {"p50_us": round(us, 1), "ratio": round(r, 3)}
+                    if Ss == sg["S"] and stage != 3:
+                        ex[f"dyn_bottleneck_stage{stage}_b128_r050"] = {
+                            "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
+                            "mfma_frac_useful": round(r * N * flops_img / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+                    del wss
+                ex[f"latency_vs_S_stage{stage}_b128_r050"] = curve
             else:
                 cm = I.bernoulli_mask(7300 + stage, (N, 4), 0.5)
                 rn = cm.mean(axis=1)

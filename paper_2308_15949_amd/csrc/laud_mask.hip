@@ -242,10 +242,6 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
   // number of vector-memory instructions of a kernel that should only stream x, so the block keeps
   // them in LDS (C floats) when they fit.
   extern __shared__ __align__(16) float s_w[];
-  if constexpr (WLDS) {
-    for (int k = threadIdx.x; k < C; k += 256) s_w[k] = w[k];
-    __syncthreads();
-  }
   const int Hp = H / S, Wp = W / S;
   const int npatch = N * Hp * Wp;
   const int team = threadIdx.x / TEAM, tl = threadIdx.x % TEAM;
@@ -253,9 +249,11 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
   const bool live = q < npatch;  // uniform per team
   float acc = 0.f;
   int n = 0;
-  if (live) {
-    n = q / (Hp * Wp);
-    const int r = q - n * (Hp * Wp);
+  {
+    // a team past the end reads the last patch (valid addresses) and writes nothing
+    const int qq = live ? q : npatch - 1;
+    n = qq / (Hp * Wp);
+    const int r = qq - n * (Hp * Wp);
     const int py = r / Wp, px = r - py * Wp;
     const int cpr = C / EPC;          // chunks per pixel row
     const int total = S * S * cpr;    // chunks per patch
@@ -289,7 +287,22 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
                __uint_as_float(raw.w << 16) * w1.z + __uint_as_float(raw.w & 0xffff0000u) * w1.w;
       }
     };
-    int c = tl;
+    // The first eight loads of x are issued before the block fetches the weights, so the two
+    // far-memory latencies overlap instead of adding up (the kernel lives for only a few of them).
+    uint4 first[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) first[u] = *chunk_ptr(min(tl + u * TEAM, total - 1));
+    if constexpr (WLDS) {
+      for (int k = threadIdx.x; k < C; k += 256) s_w[k] = w[k];
+      __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int cc = tl + u * TEAM;
+      const float d = dot(first[u], min(cc, total - 1));
+      acc += cc < total ? d : 0.f;
+    }
+    int c = tl + 8 * TEAM;
     for (; c + 7 * TEAM < total; c += 8 * TEAM) {
       uint4 r[8];
 #pragma unroll
