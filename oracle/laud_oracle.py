@@ -349,3 +349,26 @@ def projection_bottleneck(x: np.ndarray, p: BottleneckParams, w_sc: np.ndarray, 
     f = affine(conv1x1(h2, p.w3), p.s3, p.t3)
     sc = affine(conv2d(x, np.asarray(w_sc, np.float64)[:, None, None, :], stride, 0), s_sc, t_sc)
     return relu(f + sc)
+
+
+def dyn_projection_bottleneck(x: np.ndarray, p: BottleneckParams, w_sc: np.ndarray, s_sc: np.ndarray,
+                              t_sc: np.ndarray, stride: int, S: int, mask_coarse: np.ndarray) -> np.ndarray:
+    """Dynamic first block of a stage: the spatial mask lives on the OUTPUT grid (the mask decides at which
+    output locations the convolutions run, Sec. 3.1), in patches of S x S output pixels; locations that are
+    not selected take the value of the skip connection (Sec. 3.1), which in this block is the strided
+    1x1 projection with its own affine:  out = act(shortcut(x) + M * branch(x)).  Dense-then-mask."""
+    q = p.as_f64()
+    h1 = relu(affine(conv1x1(x, q.w1), q.s1, q.t1))
+    h2 = relu(affine(conv2d(h1, q.w2, stride, 1), q.s2, q.t2))
+    f = affine(conv1x1(h2, q.w3), q.s3, q.t3)
+    sc = affine(conv2d(x, np.asarray(w_sc, np.float64)[:, None, None, :], stride, 0), s_sc, t_sc)
+    up = upsample_mask(mask_coarse, S).astype(np.float64)[..., None]
+    out = sc + up * f
+    return relu(out) if q.relu_out else out
+
+
+def strided_mask_logits(x: np.ndarray, stride: int, S: int, w: np.ndarray, bias: float) -> np.ndarray:
+    """Masker of a strided block (Sec. 3.2 "Masker design"): the input is pooled adaptively to the
+    patch grid of the OUTPUT (Ho/S x Wo/S); with H = stride*Ho that is a mean over windows of
+    stride*S input pixels, followed by the one-channel 1x1 conv."""
+    return mask_logits(x, stride * S, w, bias)

@@ -524,3 +524,85 @@ def test_conv2d_maxpool_stem_and_projection_block_vs_torch():
         sc = F.conv2d(xt, t(wsc)[:, :, None, None], stride=stride) * ch(ssc) + ch(tsc)
         np.testing.assert_allclose(O.projection_bottleneck(xb, p, wsc, ssc, tsc, stride), back(F.relu(f + sc)),
                                    rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# dynamic first block of a stage (mask on the output grid, projection shortcut)
+# --------------------------------------------------------------------------- #
+def _bf_proj_out(x, p, wsc, ssc, tsc, stride, n, yo, xo, o, active, relu_out):
+    """One output element with explicit loops: strided shortcut, plus the branch if the location is active."""
+    C, m = len(x[0][0][0]), len(p["w1"])
+    acc = 0.0
+    for c in range(C):
+        acc += wsc[o][c] * x[n][stride * yo][stride * xo][c]
+    v = ssc[o] * acc + tsc[o]
+    if active:
+        f = 0.0
+        for j in range(m):
+            a2 = 0.0
+            for ky in range(3):
+                for kx in range(3):
+                    for i in range(m):
+                        a2 += p["w2"][j][ky][kx][i] * _bf_h1(x, p, n, stride * yo + ky - 1, stride * xo + kx - 1, i)
+            h2 = p["s2"][j] * a2 + p["t2"][j]
+            f += p["w3"][o][j] * (h2 if h2 > 0.0 else 0.0)
+        v += p["s3"][o] * f + p["t3"][o]
+    return 0.0 if (relu_out and v < 0.0) else v
+
+
+@pytest.mark.parametrize("stride,H,W,S", [(2, 4, 4, 1), (2, 4, 4, 2), (1, 2, 2, 1), (2, 5, 3, 1), (2, 8, 4, 2)])
+@pytest.mark.parametrize("relu_out", [False, True])
+def test_dyn_projection_block_vs_bruteforce_all_masks(stride, H, W, S, relu_out):
+    rng = np.random.default_rng(700 + 10 * H + S + stride)
+    N, c_in, m, c_out = 1, 3, 2, 4
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_out, relu_out)
+    wsc, ssc, tsc = rng.standard_normal((c_out, c_in)), 1 + 0.3 * rng.standard_normal(c_out), rng.standard_normal(c_out)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    hp, wp = Ho // S, Wo // S
+    xl, pl = x.tolist(), _as_lists(p)
+    for bits in itertools.product([0, 1], repeat=hp * wp):
+        mask = np.array(bits, np.uint8).reshape(N, hp, wp)
+        got = O.dyn_projection_bottleneck(x, p, wsc, ssc, tsc, stride, S, mask)
+        assert got.shape == (N, Ho, Wo, c_out)
+        for yo in range(Ho):
+            for xo in range(Wo):
+                for o in range(c_out):
+                    want = _bf_proj_out(xl, pl, wsc.tolist(), ssc.tolist(), tsc.tolist(), stride, 0, yo, xo, o,
+                                        bool(mask[0, yo // S, xo // S]), relu_out)
+                    assert abs(got[0, yo, xo, o] - want) <= 1e-11 * (1 + abs(want))
+
+
+def test_dyn_projection_block_invariants_and_masker():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(77)
+    N, H, W, c_in, m, c_out, stride, S = 2, 12, 8, 6, 4, 8, 2, 2
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_out, True)
+    wsc, ssc, tsc = rng.standard_normal((c_out, c_in)), 1 + 0.2 * rng.standard_normal(c_out), rng.standard_normal(c_out)
+    Ho, Wo = H // stride, W // stride
+    ones = np.ones((N, Ho // S, Wo // S), np.uint8)
+    # every location active: the static first block (itself pinned against torch above)
+    np.testing.assert_allclose(O.dyn_projection_bottleneck(x, p, wsc, ssc, tsc, stride, S, ones),
+                               O.projection_bottleneck(x, p, wsc, ssc, tsc, stride), rtol=1e-12, atol=1e-12)
+    # nothing active: the activated skip connection alone (library strided 1x1)
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2)
+    sc = F.conv2d(xt, torch.from_numpy(wsc)[:, :, None, None], stride=stride)
+    sc = sc * torch.from_numpy(ssc).view(1, -1, 1, 1) + torch.from_numpy(tsc).view(1, -1, 1, 1)
+    np.testing.assert_allclose(O.dyn_projection_bottleneck(x, p, wsc, ssc, tsc, stride, S, 0 * ones),
+                               F.relu(sc).permute(0, 2, 3, 1).numpy(), rtol=1e-11, atol=1e-11)
+    # one flipped patch changes exactly its S x S output pixels
+    mk = (rng.random(ones.shape) < 0.5).astype(np.uint8)
+    mk2 = mk.copy()
+    mk2[1, 1, 0] ^= 1
+    a = O.dyn_projection_bottleneck(x, p, wsc, ssc, tsc, stride, S, mk)
+    b = O.dyn_projection_bottleneck(x, p, wsc, ssc, tsc, stride, S, mk2)
+    diff = np.any(a != b, axis=-1)
+    region = np.zeros_like(diff)
+    region[1, S:2 * S, 0:S] = True
+    assert not np.any(diff & ~region)
+    # masker of a strided block: adaptive average pooling of x to the output patch grid, then the 1x1
+    w = rng.standard_normal(c_in)
+    pooled = F.adaptive_avg_pool2d(xt, (Ho // S, Wo // S)).permute(0, 2, 3, 1).numpy()
+    np.testing.assert_allclose(O.strided_mask_logits(x, stride, S, w, 0.25), pooled @ w + 0.25, rtol=1e-11, atol=1e-11)
