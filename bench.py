@@ -172,6 +172,42 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[name + "_p50_us"] = round(_p50_us(t, fn, iters=12, warm=2), 1)
         ex["fusion_ablation_" + tag] = res
         del xb, xs, wsu, wsd
+    # dynamic first blocks of stages 2-4 (stride 2, projection shortcut, mask on the output grid) against the
+    # static block on the same input: masker at granularity 2S on the input + laud_dyn_projection_bottleneck
+    for stage in (2, 3, 4):
+        sg, sp = I.STAGES[stage], I.STAGES[stage - 1]
+        N, Ss, m, ci, co, hin = 128, sg["S"], sg["m"], sp["c_in"], sg["c_in"], sp["hw"]
+        xs = D.to_device(I.feature_map(8100 + stage, 8, hin, hin, ci, I.BF16), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        fxs = L.fmap_of(xs)
+        dbs = D.DeviceBottleneck(I.bottleneck_params(8110 + stage, ci, m, co, I.BF16, relu_out=True, s3_gain=0.5))
+        gs = np.random.default_rng(8120 + stage)
+        wsc = D.to_device(I.round_to(gs.standard_normal((co, ci), dtype=np.float32) * np.float32(np.sqrt(2.0 / ci)), I.BF16), I.BF16)
+        ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
+        tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
+        wm = t.from_numpy(I.masker_weights(8130 + stage, ci)).cuda()
+        outs = [t.empty((N, sg["hw"], sg["hw"], co), dtype=t.bfloat16, device="cuda") for _ in range(2)]
+        npatch = N * (sg["hw"] // Ss) ** 2
+        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cn = t.zeros(1, dtype=t.int32, device="cuda")
+        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, 2 * Ss))
+        wsp = D.workspace(L.static_bottleneck_workspace(fxs, dbs.desc, 2))
+        wsq = D.workspace(L.dyn_projection_workspace(fxs, dbs.desc, 2))
+        L.laud_mask_gen(xs, fxs, 2 * Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+        t.cuda.synchronize()
+        lg = lgs.cpu().numpy()
+        res = {"static_p50_us": round(_p50_us(t, lambda i: L.laud_static_bottleneck(
+            xs, fxs, dbs.desc, wsc, ssc, tsc, 2, outs[i % 2], wsp), iters=12, warm=2), 1)}
+        for ratio in (0.25, 0.5, 1.0):
+            b2 = I.bias_for_ratio(lg, ratio)[0]
+
+            def dynp(i):
+                L.laud_mask_gen(xs, fxs, 2 * Ss, wm, b2, None, mk, ids, cn, None, None, wsm2)
+                L.laud_dyn_projection_bottleneck(xs, fxs, dbs.desc, wsc, ssc, tsc, 2, Ss, ids, cn, outs[i % 2], wsq)
+            res[f"dynamic_r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, dynp, iters=12, warm=2), 1)
+        ex[f"dyn_first_block_stage{stage}_b128"] = res
+        del xs, outs, wsp, wsq
     # BASELINE configs 3 and 5: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
     # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
     # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.

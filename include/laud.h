@@ -209,6 +209,27 @@ int laud_stem(const void* x, int N, int Hin, int Win, int dtype, const void* w7,
               const float* t, int c_out, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Dynamic first block of a stage (Sec. 3.1: the mask decides at which OUTPUT locations the
+ * convolutions run; locations that are not selected take the value of the skip connection, which in
+ * this block is the strided 1x1 projection):
+ *   out = act(s_sc*conv1x1_stride(x;w_sc)+t_sc + M * (s3*conv1x1(h2;w3)+t3)),
+ * h1, h2 as in laud_static_bottleneck.  The mask lives on the output grid [N,Ho,Wo], Ho = (H-1)/stride+1,
+ * in patches of S x S output pixels (S divides Ho and Wo); idx/count are the ascending list of active
+ * patch indices (n*Hp + py)*Wp + px on that grid and its length, both device memory, e.g. from
+ * laud_mask_gen called on x with granularity stride*S (adaptive pooling of x to the output patch grid,
+ * Sec. 3.2) or from laud_layer_skip_compact.  conv1 runs only on the input pixels under the 3x3 windows
+ * of active output pixels, conv2/conv3 only on active output pixels; the shortcut runs everywhere.
+ * x [N,H,W,c_in], out [N,Ho,Wo,c_out] (must not alias x), stride 1 or 2, act = ReLU iff p->relu_out.
+ * Errors as laud_static_bottleneck; LAUD_ERR_INVALID_ARG if S does not divide the output size.
+ */
+size_t laud_dyn_projection_workspace(laud_fmap fx, const laud_bottleneck* p, int stride);
+int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                   const void* w_sc, const float* s_sc, const float* t_sc, int stride,
+                                   int S, const int32_t* idx, const int32_t* count, void* out,
+                                   void* ws, size_t ws_bytes, void* stream);
+
+
+/*
  * Channel masker (Sec. 3.2 "Masker design"; Fig. 3(b)): g = mean of x over H x W per sample and
  * channel; h = relu(wa*g + ba) (the paper does not name the non-linearity; ReLU is assumed);
  * l = wb*h + bb, 2D logits viewed row-major as [D][2]; group d is kept iff l[d][0] > l[d][1]

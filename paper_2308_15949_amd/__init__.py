@@ -7,7 +7,8 @@ from .binding import (  # noqa: F401
     laud_dyn_bottleneck, laud_gather_patches, laud_layer_skip_compact, laud_mask_gen,
     laud_masker_dyn_bottleneck, laud_channel_masker, channel_masker_workspace,
     laud_dyn_bottleneck_unfused, dyn_bottleneck_unfused_workspace, laud_static_bottleneck,
-    static_bottleneck_workspace, laud_stem, stem_workspace,
+    static_bottleneck_workspace, laud_stem, stem_workspace, laud_dyn_projection_bottleneck,
+    dyn_projection_workspace,
     laud_stage_timing_enable, laud_stage_timing_read, load,
     make_bottleneck, status_string, workspace_size,
 )

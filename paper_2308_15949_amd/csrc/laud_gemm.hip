@@ -120,6 +120,16 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int nvalid) {
   return v;
 }
 
+// first position of a sorted list whose value is not below `key`
+__device__ __forceinline__ int lower_bound_dev(const int32_t* v, int n, int key) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (v[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
 template <int MODE, typename ET, int BM, int BN, int WGN>
 __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // 2 x WGN waves; each wave owns a (BM/2) x (BN/WGN) sub-tile of 32x32 MFMA tiles.
@@ -141,13 +151,18 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   constexpr int MAIN_BYTES = (2 * STAGE_BYTES > BM * CSTR) ? 2 * STAGE_BYTES : BM * CSTR;
   extern __shared__ __align__(16) unsigned char smem[];  // two pipeline stages, reused by the epilogue
   __shared__ int s_row[BM];
+  __shared__ unsigned char s_inact[MODE == M_SD1 ? BM : 1];  // SD1 with a patch list: row lies in an inactive patch
   __shared__ int s_kgrp[CS ? kMaxGroups : 1];
   __shared__ int s_nkept;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int HW = a.H * a.W, SS = a.S * a.S;
-  const int Hp = a.H / a.S, Wp = a.W / a.S;
+  // Dynamic blocks with a spatial stride (a.stride > 1) keep their mask on the output grid Ho x Wo;
+  // everywhere else the output grid is the input grid.
+  const int sy = a.stride > 1 ? a.stride : 1;
+  const int oH = a.stride > 1 ? a.Ho : a.H, oW = a.stride > 1 ? a.Wo : a.W;
+  const int Hp = oH / a.S, Wp = oW / a.S;
   const ET* __restrict__ Ap = (const ET*)a.A;
   const ET* __restrict__ Wp_ = (const ET*)a.Wt;
   // ---- which tile ---------------------------------------------------------------------------
@@ -249,8 +264,8 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         const int q = a.list[p];
         const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
         const int py = r2 / Wp, px = r2 - py * Wp;
-        y = py * a.S + j / a.S;
-        x = px * a.S + j % a.S;
+        y = (py * a.S + j / a.S) * sy;  // centre of the 3x3 on the input grid
+        x = (px * a.S + j % a.S) * sy;
         pixrow = (size_t)n * HW + (size_t)y * a.W + x;
       } else if constexpr (MODE == M_CS2) {
         y = rho / a.W;
@@ -296,12 +311,25 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         const int q = a.list[p];
         const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
         const int py = r2 / Wp, px = r2 - py * Wp;
-        o = n * HW + (py * a.S + j / a.S) * a.W + (px * a.S + j % a.S);
+        o = n * (oH * oW) + (py * a.S + j / a.S) * oW + (px * a.S + j % a.S);
       } else {
         o = sample * HW + rho;
       }
     }
     s_row[tid] = o;
+    if constexpr (MODE == M_SD1) {
+      // shortcut of a dynamic first block: the activation is applied here only where the branch will
+      // not be added (inactive patches); active rows get it in the last conv's epilogue
+      bool inact = true;
+      if (a.list != nullptr && rho < M) {
+        const int n = rho / (a.Ho * a.Wo), r2 = rho - n * (a.Ho * a.Wo);
+        const int q = (n * Hp + (r2 / a.Wo) / a.S) * Wp + (r2 % a.Wo) / a.S;
+        const int cnt = *a.count;
+        const int pos = lower_bound_dev(a.list, cnt, q);
+        inact = !(pos < cnt && a.list[pos] == q);
+      }
+      s_inact[tid] = inact ? 1 : 0;
+    }
   }
 
   // ---- weight-row descriptors -----------------------------------------------------------------
@@ -492,7 +520,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
           const int rl = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           float v = acc[i][j][e] * sc + sh;
           if constexpr (MODE == M_SD1) {
-            if (a.relu) v = fmaxf(v, 0.f);
+            if (a.relu && s_inact[rl]) v = fmaxf(v, 0.f);
           } else if constexpr (!(MODE == M_CONV3 || MODE == M_CS3 || MODE == M_U3 || MODE == M_SD3)) {
             v = fmaxf(v, 0.f);
           }
@@ -574,14 +602,6 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
 // ------------------------------------------------------------------------------------------------
 // dilated active set: which pixels need conv1 (the patch pixels and their one-pixel halo)
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int lower_bound_dev(const int32_t* v, int n, int key) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (v[mid] < key) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
 
 // One block per group of `gs` consecutive samples: writes the ids of the group's needed pixels in
 // ascending order at pix[g*gs*H*W ...] and their number at need_counts[g] (ordered, no atomics, no
@@ -589,13 +609,15 @@ __device__ __forceinline__ int lower_bound_dev(const int32_t* v, int n, int key)
 constexpr int kNeedThreads = 1024;
 __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict__ idx,
                                                        const int32_t* __restrict__ count, int N, int H, int W, int S,
-                                                       int gs, int32_t* __restrict__ need_counts,
+                                                       int stride, int Ho, int Wo, int gs,
+                                                       int32_t* __restrict__ need_counts,
                                                        int32_t* __restrict__ pix) {
   extern __shared__ unsigned char s_pm[];  // [ns*Hp*Wp] patch masks of the group's samples
   constexpr int NW = kNeedThreads / kWave;
   __shared__ int wcnt[NW], woff[NW], s_tot;
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int Hp = H / S, Wp = W / S, pps = Hp * Wp, HW = H * W;
+  // the patch grid lives on the output grid Ho x Wo (= H x W when stride is 1); pixels are input pixels
+  const int Hp = Ho / S, Wp = Wo / S, pps = Hp * Wp, HW = H * W;
   const int n0 = g * gs, ns = min(gs, N - n0);
   const int cnt = *count;
   for (int i = tid; i < ns * pps; i += kNeedThreads) s_pm[i] = 0;
@@ -620,11 +642,13 @@ __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict
     if (pp < ns * HW) {
       const int ln = pp / HW, q = pp - ln * HW;
       const int y = q / W, x = q - y * W;
-      const int py0 = max(y - 1, 0) / S, py1 = min(y + 1, H - 1) / S;
-      const int px0 = max(x - 1, 0) / S, px1 = min(x + 1, W - 1) / S;
+      // output pixel yo reads input rows stride*yo-1 .. stride*yo+1, so input row y serves the output
+      // rows ceil((y-1)/stride) .. floor((y+1)/stride), clipped to the output grid
+      const int yo0 = max((y - 1 + stride - 1) / stride, 0), yo1 = min((y + 1) / stride, Ho - 1);
+      const int xo0 = max((x - 1 + stride - 1) / stride, 0), xo1 = min((x + 1) / stride, Wo - 1);
       const unsigned char* pm = s_pm + ln * pps;
-      for (int py = py0; py <= py1; ++py)
-        for (int px = px0; px <= px1; ++px) need |= pm[py * Wp + px] != 0;
+      for (int py = yo0 / S; py <= yo1 / S; ++py)
+        for (int px = xo0 / S; px <= xo1 / S; ++px) need |= pm[py * Wp + px] != 0;
     }
     const unsigned long long b = __ballot(need);
     if (lane == 0) wcnt[wave] = __popcll(b);
@@ -846,7 +870,7 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   {
     StageScope scope(LAUD_STAGE_NEED, st);
     hipLaunchKernelGGL(k_need, dim3(ngroups), dim3(kNeedThreads), align_up((size_t)gs * pps, 16), st, idx, count,
-                       fx.N, fx.H, fx.W, S, gs, need_counts, pix);
+                       fx.N, fx.H, fx.W, S, 1, fx.H, fx.W, gs, need_counts, pix);
   }
   if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
 
@@ -1069,6 +1093,92 @@ extern "C" int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bo
   a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = out; a.K = p->c_mid;
   a.ldw = p->c_mid; a.Ncols = p->c_out; a.ldo = p->c_out; a.relu = 1;
   return launch_gemm<M_SD3>(fx.dtype, a, nout, 1, st);
+}
+
+namespace {
+struct DynProjWs { size_t need_counts, pix, h1, h2, bytes; };
+DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int stride) {
+  const size_t eb = elem_bytes(fx.dtype), npix = (size_t)fx.N * fx.H * fx.W;
+  const size_t nout = (size_t)fx.N * ((fx.H - 1) / stride + 1) * ((fx.W - 1) / stride + 1);
+  DynProjWs w;
+  size_t o = 0;
+  w.need_counts = o; o += align_up((size_t)fx.N * 4, 256);
+  w.pix = o;         o += align_up(npix * 4, 256);
+  w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
+  w.h2 = o;          o += align_up(nout * c_mid * eb, 256);
+  w.bytes = o;
+  return w;
+}
+}  // namespace
+
+extern "C" size_t laud_dyn_projection_workspace(laud_fmap fx, const laud_bottleneck* p, int stride) {
+  if (!valid_fmap(fx) || !p || p->c_mid <= 0 || (stride != 1 && stride != 2)) return 0;
+  return dyn_proj_ws_layout(fx, p->c_mid, stride).bytes;
+}
+
+extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                              const void* w_sc, const float* s_sc, const float* t_sc, int stride,
+                                              int S, const int32_t* idx, const int32_t* count, void* out, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  if (!x || !out || !p || !w_sc || !s_sc || !t_sc || !idx || !count || !valid_fmap(fx) || x == out)
+    return LAUD_ERR_INVALID_ARG;
+  if (!p->w1 || !p->w2 || !p->w3 || !p->s1 || !p->t1 || !p->s2 || !p->t2 || !p->s3 || !p->t3)
+    return LAUD_ERR_INVALID_ARG;
+  if (p->c_in != fx.C || p->c_mid <= 0 || p->c_out <= 0 || (stride != 1 && stride != 2) || S <= 0)
+    return LAUD_ERR_INVALID_ARG;
+  if (p->c_in % 8 || p->c_mid % 8 || p->c_out % 8) return LAUD_ERR_UNSUPPORTED;
+  const int Ho = (fx.H - 1) / stride + 1, Wo = (fx.W - 1) / stride + 1;
+  if (Ho % S || Wo % S) return LAUD_ERR_INVALID_ARG;
+  const int Hp = Ho / S, Wp = Wo / S;
+  if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
+  const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
+  if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, stride);
+  if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  char* wsb = (char*)ws;
+  int32_t* need_counts = (int32_t*)(wsb + L.need_counts);
+  int32_t* pix = (int32_t*)(wsb + L.pix);
+  void* h1 = wsb + L.h1;
+  void* h2 = wsb + L.h2;
+  int rc;
+
+  GemmArgs a{};
+  a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
+  // shortcut on every output pixel (the skip value of locations that are not selected), activated
+  // only inside inactive patches
+  a.A = x; a.Wt = w_sc; a.scale = s_sc; a.shift = t_sc; a.Out = out; a.K = p->c_in; a.ldw = p->c_in;
+  a.Ncols = p->c_out; a.lda = p->c_in; a.ldo = p->c_out; a.relu = p->relu_out ? 1 : 0; a.m_rows = (int)nout;
+  a.list = idx; a.count = count;
+  if ((rc = launch_gemm<M_SD1>(fx.dtype, a, nout, 1, st)) != LAUD_OK) return rc;
+
+  // input pixels the branch reads: the 3x3 windows (at the block's stride) of the active output pixels
+  const int hw = fx.H * fx.W, pps = Hp * Wp;
+  int gs = (1536 + hw - 1) / hw;
+  if (gs > fx.N) gs = fx.N;
+  while (gs > 1 && (size_t)gs * pps > 60000) --gs;
+  const int ngroups = (fx.N + gs - 1) / gs;
+  {
+    StageScope scope(LAUD_STAGE_NEED, st);
+    hipLaunchKernelGGL(k_need, dim3(ngroups), dim3(kNeedThreads), align_up((size_t)gs * pps, 16), st, idx, count,
+                       fx.N, fx.H, fx.W, S, stride, Ho, Wo, gs, need_counts, pix);
+  }
+  if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+  // conv1 over that set -> h1 at input pixel positions
+  a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
+  a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
+  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+  // conv2: strided 3x3 at the active output pixels -> dense h2
+  a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
+  a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
+  a.lda = p->c_mid; a.ldo = p->c_mid;
+  if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, nout, 1, st)) != LAUD_OK) return rc;
+  // conv3 added onto the shortcut already in `out`, at the active output pixels
+  a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = out;
+  a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
+  a.relu = p->relu_out ? 1 : 0;
+  return launch_gemm<M_CONV3>(fx.dtype, a, nout, 1, st);
 }
 
 extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p, const uint8_t* cmask,

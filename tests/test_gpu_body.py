@@ -73,6 +73,77 @@ def test_static_projection_block(case):
     close(D.to_host(out), ref, TOL[dt])
 
 
+DYN_PROJ_CASES = [
+    # N, H, W, c_in, m, c_out, stride, S, dtype, relu_out, mask kind
+    (2, 12, 8, 16, 8, 32, 2, 1, I.F32, True, "bern"),
+    (2, 12, 8, 16, 8, 32, 2, 2, I.F32, False, "bern"),
+    (2, 12, 12, 16, 8, 32, 1, 3, I.F32, True, "bern"),
+    (3, 9, 7, 40, 24, 64, 2, 1, I.F32, True, "bern"),        # odd input size: Ho = 5, Wo = 4
+    (2, 16, 16, 32, 16, 64, 2, 4, I.F32, True, "ones"),
+    (2, 16, 16, 32, 16, 64, 2, 4, I.BF16, True, "zeros"),
+    (2, 16, 16, 32, 16, 64, 2, 2, I.BF16, True, "single"),
+    (2, 56, 56, 64, 64, 256, 1, 4, I.BF16, True, "bern"),     # first block of stage 1
+    (2, 56, 56, 256, 128, 512, 2, 4, I.BF16, True, "bern"),   # first block of stage 2
+    (2, 28, 28, 512, 256, 1024, 2, 2, I.BF16, True, "bern"),  # first block of stage 3
+    (3, 14, 14, 1024, 512, 2048, 2, 1, I.BF16, True, "bern"),  # first block of stage 4
+    (3, 14, 14, 1024, 512, 2048, 2, 7, I.BF16, True, "bern"),  # ... as a layer gate (S = output size)
+]
+
+
+@pytest.mark.parametrize("case", DYN_PROJ_CASES)
+def test_dyn_projection_block(case):
+    """Dynamic first block of a stage: mask on the output grid, projection shortcut everywhere."""
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    from paper_2308_15949_amd import binding as B
+    N, H, W, ci, m, co, stride, S, dt, relu_out, kind = case
+    x = I.feature_map(630 + ci + S, N, H, W, ci, dt)
+    hb = I.bottleneck_params(631 + ci, ci, m, co, dt, relu_out=relu_out, s3_gain=0.5)
+    hb.t1 = (np.abs(hb.t1) + 0.25).astype(np.float32)   # positive conv1 shift: the 3x3's padding must be on h1
+    wsc, ssc, tsc = shortcut_params(632 + ci, ci, co, dt)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    shape = (N, Ho // S, Wo // S)
+    if kind == "bern":
+        mask = I.bernoulli_mask(633 + S + H, shape, 0.5)
+    elif kind == "ones":
+        mask = np.ones(shape, np.uint8)
+    elif kind == "zeros":
+        mask = np.zeros(shape, np.uint8)
+    else:
+        mask = np.zeros(shape, np.uint8)
+        mask[0, 0, 0] = 1
+        mask[1, -1, -1] = 1
+    ref = O.dyn_projection_bottleneck(x, oparams(hb), wsc, ssc, tsc, stride, S, mask)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    npatch = mask.size
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    L.laud_layer_skip_compact(t.from_numpy(np.ascontiguousarray(mask.reshape(-1))).cuda(), npatch, idx, cnt,
+                              D.workspace(L.workspace_size(B.OP_COMPACT, fx, None, npatch)))
+    out = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+    ws = D.workspace(L.dyn_projection_workspace(fx, db.desc, stride))
+    ws.fill_(0xFF)  # NaN patterns: anything read before it is written shows up
+    print(f"dyn projection case {case}", flush=True)
+    L.laud_dyn_projection_bottleneck(xd, fx, db.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(),
+                                     t.from_numpy(tsc).cuda(), stride, S, idx, cnt, out, ws)
+    t.cuda.synchronize()
+    assert np.array_equal(D.to_host(xd), x)   # the input is left alone
+    got = D.to_host(out)
+    close(got, ref, TOL[dt])
+    # inactive locations hold the activated shortcut alone: the same values the block gives with an empty mask
+    up = O.upsample_mask(mask, S).astype(bool)
+    if kind == "bern":
+        cnt0 = t.zeros(1, dtype=t.int32, device="cuda")
+        out0 = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+        L.laud_dyn_projection_bottleneck(xd, fx, db.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(),
+                                         t.from_numpy(tsc).cuda(), stride, S, idx, cnt0, out0, ws)
+        t.cuda.synchronize()
+        assert np.array_equal(D.to_host(out0)[~up], got[~up])
+
+
 def test_reduced_body_block_by_block():
     """64x64 images, stem to 16x16x64, then stages 1-3 with widths 64/128/256 (x4), granularity 4-4-2: one
     static first block and two dynamic identity blocks per stage, masks from each block's masker at ratio 0.5."""
