@@ -309,6 +309,27 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
         "per-sample per-block keep gates Bernoulli(0.6): stages 1, 2, 4 skip whole samples (S = H), stage 3 "
         "combines the gate with spatial maskers S = 2 at ratio 0.5 of the patches"))
     t.cuda.empty_cache()
+    # yardstick: the vendor GEMM library (through torch.matmul) on plain dense GEMMs of the three conv shapes
+    # of config 2 at r = 0.5 -- no gather, no masker projection, no residual or scatter; context for the
+    # roofline fraction, not part of the path.  Back-to-back launches over rotating cold A operands.
+    yard = {}
+    for name, (M, K, Nc) in (("conv1_25088x1024x256", (25088, 1024, 256)), ("conv2_12544x2304x256", (12544, 2304, 256)),
+                             ("conv3_12544x256x1024", (12544, 256, 1024))):
+        As = [t.randn(M, K, device="cuda", dtype=t.bfloat16) for _ in range(8)]
+        Bm = t.randn(Nc, K, device="cuda", dtype=t.bfloat16)
+        for i in range(5):
+            _ = As[i % 8] @ Bm.t()
+        t.cuda.synchronize()
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(40):
+            _ = As[i % 8] @ Bm.t()
+        e1.record()
+        t.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 40
+        yard[name] = {"us": round(us, 1), "TFLOP_per_s": round(2.0 * M * K * Nc / us / 1e6, 0)}
+        del As, Bm
+    ex["vendor_gemm_yardstick_config2_r050"] = yard
     # config 1: one fp32 image, stage-1 block, S = 4, Bernoulli 0.5 -- latency bound
     sg = I.STAGES[1]
     x1 = D.to_device(I.feature_map(1000, 1, 56, 56, 256, I.F32), I.F32)

@@ -183,6 +183,86 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
   }
 }
 
+// Pooling, threshold and ordered compaction in ONE single-block launch for S = 2 and at most 8192
+// patches (a stage-3 batch of 128 images): the two dependent kernels cost two launch-plus-far-latency
+// chains for a few kilobytes of work.  A thread owns entries 4*tid .. 4*tid+3 of each 4096-entry pass
+// as in k_compact_small, requests all of its projection reads (two 8-byte loads per patch) before
+// using any, and compacts from registers.  Same summation order as pooled_decision.
+constexpr int kPoolFusedMax = 2 * kCompactBlock;
+__global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa, int n, uint8_t* __restrict__ mask,
+                                                                     int32_t* __restrict__ idx,
+                                                                     int32_t* __restrict__ count,
+                                                                     int32_t* __restrict__ sample_offsets,
+                                                                     int per_sample) {
+  __shared__ int wsum[kCompactThreads / kWave];
+  __shared__ int woff[kCompactThreads / kWave];
+  __shared__ int s_tot;
+  const int wave = threadIdx.x / kWave, lane = lane_id();
+  const int Hp = pa.H / 2, Wp = pa.W / 2;
+  float2 top[2][4], bot[2][4];
+  int sample[2][4];
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = p * 4 * kCompactThreads + 4 * (int)threadIdx.x + j;
+      const int q = i < n ? i : n - 1;  // past the end: re-read the last patch, result unused
+      const int s = q / (Hp * Wp), r = q - s * (Hp * Wp);
+      const int py = r / Wp, px = r - py * Wp;
+      const float* base = pa.proj + ((size_t)s * pa.H + py * 2) * pa.W + px * 2;
+      sample[p][j] = s;
+      top[p][j] = *reinterpret_cast<const float2*>(base);
+      bot[p][j] = *reinterpret_cast<const float2*>(base + pa.W);
+    }
+  int running = 0;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
+    if (p * 4 * kCompactThreads >= n) break;  // uniform
+    bool f[4];
+    unsigned long long b[4];
+    int before = 0, mine = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float acc = ((top[p][j].x + top[p][j].y) + bot[p][j].x) + bot[p][j].y;
+      const float logit = acc / 4.0f + pa.bias;
+      bool on = logit > 0.f;  // false for NaN
+      if (pa.keep && pa.keep[sample[p][j]] == 0) on = false;
+      f[j] = (i0 + j < n) && on;
+      if (i0 + j < n) {
+        mask[i0 + j] = on ? 1 : 0;
+        if (pa.logits) pa.logits[i0 + j] = logit;
+      }
+      b[j] = __ballot(f[j]);
+      before += ballot_prefix(b[j]);
+    }
+    int wtot = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
+    if (lane == 0) wsum[wave] = wtot;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
+      s_tot = t;
+    }
+    __syncthreads();
+    const int pos = running + woff[wave] + before;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = i0 + j;
+      if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
+      if (f[j]) { idx[pos + mine] = i; ++mine; }
+    }
+    running += s_tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *count = running;
+    if (sample_offsets) sample_offsets[n / per_sample] = running;
+  }
+}
+
 __global__ void k_write_zero_count(int32_t* count, int32_t* sample_offsets) {
   *count = 0;
   if (sample_offsets) sample_offsets[0] = 0;
@@ -215,6 +295,12 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
                         hipStream_t stream) {
   const int pps = (H / S) * (W / S), npatch = N * pps;
   PoolArgs pa{proj, keep, logits, H, W, S, bias};
+  if (S == 2 && npatch > 0 && npatch <= kPoolFusedMax) {
+    StageScope scope(LAUD_STAGE_COMPACT, stream);
+    hipLaunchKernelGGL(k_pool_compact_s2, dim3(1), dim3(kCompactThreads), 0, stream, pa, npatch, mask, idx, count,
+                       sample_offsets, pps);
+    return check_launch();
+  }
   // One thread per patch over a wide grid: the S*S projection reads of a patch are independent, and a
   // single block walking all patches would serialise their latency.
   {
