@@ -20,6 +20,8 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+from paper_2308_15949_amd import predictor as PRED  # noqa: E402  (host arithmetic only)
+
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the conv2 kernel at the default workload (batch 128, ratio 0.5), from the
@@ -111,7 +113,11 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                         L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wss)
                     us = _p50_us(t, blk, iters=12, warm=2)
                     r = float(cn.item()) / npatch
-                    curve[str(Ss)] = {"p50_us": round(us, 1), "ratio": round(r, 3)}
+                    pred = PRED.predict_block(PRED.MI355X, "spatial", n=N, hw_px=sg["hw"], c_in=sg["c_in"], m=sg["m"],
+                                              S=Ss, r=r, fused_masker=False, with_masker=False)["total_s"]
+                    curve[str(Ss)] = {"p50_us": round(us, 1), "ratio": round(r, 3),
+                                      # + the index list and the dilated-set kernels (one per-kernel constant each)
+                                      "predicted_us": round((pred + 2 * PRED.MI355X.const_s) * 1e6, 1)}
                     if Ss == sg["S"] and stage != 3:
                         ex[f"dyn_bottleneck_stage{stage}_b128_r050"] = {
                             "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
@@ -487,7 +493,11 @@ def main():
                           "p50_us": round(p * 1e3, 1), "p10_us": round(latr[len(latr) // 10] * 1e3, 1),
                           "p90_us": round(latr[(9 * len(latr)) // 10] * 1e3, 1),
                           "images_per_s": round(N / (p * 1e-3), 0),
-                          "mfma_frac_useful": round(useful_flops(Pr) / (p * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4)})
+                          "mfma_frac_useful": round(useful_flops(Pr) / (p * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+                          # latency predictor re-parameterised for MI355X (Sec. 3.3, App. A): host arithmetic only
+                          "predicted_us": round(PRED.predict_block(
+                              PRED.MI355X, "spatial", n=N, hw_px=H, c_in=C, m=m, S=S, r=Pr / npatch,
+                              fused_masker=(a.variant == "fused"))["total_s"] * 1e6, 1)})
         rs = np.array([s["ratio"] for s in sweep])
         ls = np.array([s["p50_us"] for s in sweep])
         A = np.stack([np.ones_like(rs), rs], 1)
@@ -495,7 +505,9 @@ def main():
         res = ls - A @ coef
         r2 = 1.0 - float(res @ res) / float(((ls - ls.mean()) ** 2).sum() or 1.0)
         fit = {"intercept_us": round(float(coef[0]), 1), "slope_us_per_unit_ratio": round(float(coef[1]), 1),
-               "r2": round(r2, 4)}
+               "r2": round(r2, 4),
+               "predictor_mean_abs_rel_err": round(float(np.mean([abs(s_["predicted_us"] - s_["p50_us"]) / s_["p50_us"]
+                                                                   for s_ in sweep])), 3)}
     else:
         fit = None
 
