@@ -2,7 +2,7 @@
 """Benchmark of the dynamic-bottleneck hot path on one MI355X.
 
 A step = one pass of the whole path (laud_mask_gen + laud_dyn_bottleneck, in place) over one
-batch of BASELINE config 2: x 128 x 14 x 14 x 1024 bf16, mid width 256, S = 2, mask from the
+batch of the headline workload (configuration 2 of the benchmark list): x 128 x 14 x 14 x 1024 bf16, mid width 256, S = 2, mask from the
 pooled masker with the bias calibrated to the target activation ratio.  Every step gets its own
 pristine copy of x (the block updates x in place), so inputs are resident in HBM but cold in
 the caches.  Prints ONE JSON line.
@@ -214,7 +214,7 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[f"dynamic_r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, dynp, iters=12, warm=2), 1)
         ex[f"dyn_first_block_stage{stage}_b128"] = res
         del xs, outs, wsp, wsq
-    # BASELINE configs 3 and 5: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
+    # configurations 3 and 5 of the benchmark list: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
     # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
     # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.
     #   config 3: batch 128, spatial maskers at granularity 4-4-2-1 in all stages, every masker's bias
@@ -358,7 +358,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards along the batch with no "
-              "exchange step; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+              "exchange step); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

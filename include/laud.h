@@ -186,7 +186,7 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Static parts of the ResNet body (BASELINE config 3; always executed, no mask).  The paper's
+ * Static parts of the ResNet body (always executed, no mask).  The paper's
  * formulation assumes stride 1 inside dynamic blocks (Sec. 3.1); the first block of every stage
  * (projection shortcut, stride 2 in stages 2-4, placed on the 3x3 as in the torchvision models the
  * paper starts from) and the stem run as ordinary dense layers.

@@ -297,7 +297,7 @@ def channel_flops_ratio(rc: float, c_in: int, m: int, c_out: int) -> float:
 
 
 # --------------------------------------------------------------------------- #
-# static parts of the ResNet body (BASELINE config 3): stem and projection blocks
+# static parts of the ResNet body (the whole-body workload): stem and projection blocks
 # --------------------------------------------------------------------------- #
 def conv2d(x: np.ndarray, w: np.ndarray, stride: int, pad: int) -> np.ndarray:
     """General cross-correlation, NHWC: out[n,yo,xo,o] = sum_{ky,kx,c} w[o,ky,kx,c] *

@@ -1,4 +1,4 @@
-// Static stem of the ResNet body (BASELINE config 3): 7x7 stride-2 conv on the 3-channel image with
+// Static stem of the ResNet body (the whole-body workload): 7x7 stride-2 conv on the 3-channel image with
 // folded-BN affine and ReLU, then 3x3 stride-2 max pooling.  Outside the dynamic hot path (it runs once
 // per image and is not masked): an im2col kernel feeds the dense MFMA GEMM of laud_gemm.hip, a plain
 // kernel pools.

@@ -1,5 +1,5 @@
 """GPU parity of the static parts of the ResNet body (stem, projection blocks) and of a reduced
-body run (BASELINE config 3 in miniature: stem, then per stage one static first block followed by
+body run (the whole-body workload in miniature: stem, then per stage one static first block followed by
 dynamic identity blocks), block by block against the CPU oracle fed with each block's actual input."""
 import numpy as np
 import pytest

@@ -226,7 +226,7 @@ DYN_CASES = [
     (2, 12, 12, 40, 24, 1, I.F32, True),
     (3, 12, 8, 32, 16, 4, I.F32, True),
     (2, 6, 6, 64, 32, 3, I.BF16, False),
-    (1, 56, 56, 256, 64, 4, I.F32, False),  # BASELINE config 1
+    (1, 56, 56, 256, 64, 4, I.F32, False),  # the single-image fp32 workload (configuration 1)
     (4, 14, 14, 1024, 256, 2, I.BF16, False),  # config 2 geometry, 4 samples
     (3, 7, 7, 2048, 512, 1, I.BF16, True),  # stage 4
     (2, 28, 28, 512, 128, 4, I.BF16, True),  # stage 2
@@ -516,7 +516,7 @@ def test_masker_dyn_bottleneck_equals_two_call_path(G):
 
 
 # ------------------------------------------------------------------------------------------
-# BASELINE configs 4 and 5 at full size (sampled images), and a chain of dynamic blocks (config 3's
+# channel-skipping and layer-skipping workloads (configurations 4 and 5) at full size (sampled images), and a chain of dynamic blocks (config 3's
 # identity blocks of one stage)
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("stage", [1, 2, 3, 4])

@@ -118,6 +118,18 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 3, vp(FAKE + (1 << 20)), vp(FAKE), needs, st) == B.ERR_INVALID_ARG
     assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, vp(FAKE), vp(FAKE), needs, st) == B.ERR_INVALID_ARG  # out == x
     assert sb(vp(FAKE), fx, C.byref(pw), None, vp(FAKE), vp(FAKE), 2, vp(FAKE + (1 << 20)), vp(FAKE), needs, st) == B.ERR_INVALID_ARG
+    # dynamic first block of a stage (fx is 2 x 8 x 8 x 64: output 4 x 4 at stride 2)
+    dp = lib.laud_dyn_projection_bottleneck
+    needp = lib.laud_dyn_projection_workspace(fx, C.byref(pw), 2)
+    assert needp >= 2 * 64 * 4 + 2 * 64 * 16 * 4 + 2 * 16 * 16 * 4
+    assert lib.laud_dyn_projection_workspace(fx, C.byref(pw), 3) == 0
+    far = vp(FAKE + (1 << 20))
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needp - 1, st) == B.ERR_WORKSPACE
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 3, vp(FAKE), vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_INVALID_ARG  # 3 does not divide 4
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 3, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_INVALID_ARG  # stride
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, None, vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_INVALID_ARG       # no index list
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needp, st) == B.ERR_INVALID_ARG  # out == x
+    assert dp(vp(FAKE), fx, C.byref(_bn(64, 12, 128)), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_UNSUPPORTED
     sm = lib.laud_stem
     nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
     assert nst >= 2 * 32 * 32 * (152 + 64) * 2
