@@ -43,7 +43,8 @@ typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk
 enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6, M_U1 = 7, M_U2 = 8, M_U3 = 9,
        M_SD1 = 10, M_SD2 = 11, M_SD3 = 12 };
 
-// 256 bytes of zeros in device memory: the source of every chunk that has to read as zero.  Not
+// 256 bytes of zeros in device memory: the source of the zero chunks of the pointer-based weight gather
+// of channel skipping (every other load gets its zeros from the buffer descriptor's range check).  Not
 // declared const on purpose: the compiler must treat a load from it like any other load (it would
 // otherwise fold the zeros in and turn the pointer select back into a branch around the load).
 __device__ uint4 g_zero_page[16];
@@ -217,27 +218,42 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   }
 
   // ---- row descriptors ------------------------------------------------------------------------
-  // Each thread keeps, for the AR activation rows and BR weight rows it loads, one base pointer
+  // Each thread keeps, for the AR activation rows and BR weight rows it loads, one 32-bit byte offset
   // that already includes its 16-byte chunk, plus (tap modes) a 9-bit mask of the taps that fall
-  // inside the image.  Per K slice a load then costs one 64-bit add of a wave-uniform offset and
-  // one pointer select: a chunk that must read as zero (tap outside the image, row past the end,
-  // K tail) is loaded from a page of zeros, so nothing has to be masked afterwards.
+  // inside the image.  A chunk that must read as zero (tap outside the image, row past the end, K
+  // tail) is never masked afterwards: its load is pointed outside the operand's descriptor (below).
   const int cc = tid & 7;    // 16-byte chunk within the 128-byte K slice
   const int lr = tid >> 3;   // first row this thread loads
-  // Hide where the zero page's address comes from (knowing that it is a dereferenceable global, the
-  // compiler would split `load(ok ? row : zeros)` into two loads under a branch) but keep the fact
-  // that it is global memory, so that the loads stay global_load (vmcnt only) and not flat_load.
+  // The kept-channel weight gather of channel skipping (CS2 / CS3) still reads through pointers; its
+  // zero chunks come from a page of zeros.  Hide where that page's address comes from (knowing that it
+  // is a dereferenceable global, the compiler would split `load(ok ? row : zeros)` into two loads under
+  // a branch) but keep the fact that it is global memory, so that the loads stay global_load (vmcnt
+  // only) and not flat_load.
   unsigned long long zaddr = reinterpret_cast<unsigned long long>(&g_zero_page[0]);
 #if defined(__HIP_DEVICE_COMPILE__)  // the constraint names a GPU register class: device pass only
   asm volatile("" : "+s"(zaddr));
 #endif
   const gptr16 zpage = (gptr16)zaddr;
-  const ET* arow[AR];
+  // Activation (and, outside the kept-channel gather of channel skipping, weight) chunks are fetched with
+  // buffer loads: a resource descriptor over the operand, a per-thread 32-bit byte offset that is fixed
+  // for the whole K loop, and a wave-uniform scalar offset per K slice.  A chunk that must read as zero
+  // gets the offset 0x80000000, which lies outside the descriptor's 2 GiB range: the hardware returns
+  // zeros for it.  A load then costs one select instead of 64-bit pointer arithmetic.
+  constexpr unsigned kOob = 0x80000000u;
+  constexpr int ROWW_IS_TILE = (MODE == M_U2);
+  // taps reach one row and one pixel back: the descriptor starts that far before the operand so that
+  // the scalar tap offsets are never negative
+  const long long ashift = TAPS ? (long long)((ROWW_IS_TILE ? a.S + 2 : a.W) + 1) * a.lda * (long long)sizeof(ET) : 0;
+  const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(reinterpret_cast<const char*>(Ap)) - ashift, 0, (int)kOob, 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(reinterpret_cast<const char*>(Wp_)), 0, (int)kOob, 0x00020000);
+  unsigned voffA[AR];        // byte offset of (row, this thread's chunk) inside the activation operand
   unsigned amask[AR];        // tap modes: bit t set = tap t readable; other modes: bit 0 = row valid
 #pragma unroll
   for (int i = 0; i < AR; ++i) {
     const int rho = row0 + lr + RPP * i;
-    arow[i] = Ap;
+    voffA[i] = 0;
     amask[i] = 0;
     if (rho < M) {
       size_t pixrow;  // row of A (pixel id or compact row)
@@ -274,7 +290,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       } else {  // CS1, CS3
         pixrow = (size_t)sample * HW + rho;
       }
-      arow[i] = Ap + pixrow * a.lda + cc * EPC;
+      voffA[i] = (unsigned)((pixrow * a.lda + cc * EPC) * sizeof(ET));
       if constexpr (MODE == M_U2) {
         amask[i] = 0x1ffu;  // every tap lies inside the gathered tile
       } else if constexpr (TAPS) {
@@ -334,6 +350,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
 
   // ---- weight-row descriptors -----------------------------------------------------------------
   const ET* wrow[BR];
+  unsigned voffW[BR];
   bool cvalid[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
@@ -343,6 +360,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     if constexpr (MODE == M_CS1 || MODE == M_CS2) wr = s_kgrp[wr / a.G] * a.G + (wr % a.G);
     wrow[i] = Wp_ + (size_t)wr * a.ldw;
     if constexpr (!(MODE == M_CS2 || MODE == M_CS3)) wrow[i] += cc * EPC;
+    voffW[i] = (unsigned)(((size_t)wr * a.ldw + cc * EPC) * sizeof(ET));
   }
   // DENSE1: the first column tile also accumulates the masker projection of its rows, on the vector
   // ALU, from the A chunks on their way from registers to LDS (each thread: AR rows x one chunk).
@@ -372,18 +390,20 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     const int ke = kbase + cc * EPC;        // this thread's first (compact) K element
     ke_out = ke;
     const bool kv = ke < keff && tap < (TAPS ? 9 : 1);  // slices past the end read as zeros
-    // wave-uniform element offsets of this slice relative to the row base pointers
-    const long long aoff = TAPS ? (long long)(ld_ky * (MODE == M_U2 ? a.S + 2 : gW) + ld_kx) * glda + kbase
-                                : (long long)kbase;
-    const long long woff = (long long)tap * gK + kbase;
+    // wave-uniform byte offsets of this slice (scalar registers)
+    const int rowW = ROWW_IS_TILE ? a.S + 2 : gW;
+    const int asoff = (TAPS ? ((ld_ky + 1) * rowW + (ld_kx + 1)) * glda + kbase : kbase) * (int)sizeof(ET);
+    const int wsoff = (tap * gK + kbase) * (int)sizeof(ET);
+    [[maybe_unused]] const long long woff = (long long)tap * gK + kbase;
+    const unsigned tapbit = tap < (TAPS ? 9 : 1) ? 1u << (TAPS ? tap : 0) : 0u;  // null slices select nothing
     if (++ld_kc == kchunks) {
       ld_kc = 0; ++ld_tap;
       if (++ld_kx == 2) { ld_kx = -1; ++ld_ky; }
     }
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
-      const bool ok = kv && ((amask[i] >> (TAPS ? tap : 0)) & 1u);
-      ra[i] = *(ok ? (gptr16)(arow[i] + aoff) : zpage);
+      const bool ok = ke < keff && (amask[i] & tapbit);
+      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, ok ? voffA[i] : kOob, asoff, 0);
     }
 #pragma unroll
     for (int i = 0; i < BR; ++i) {
@@ -397,7 +417,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
           rb[i] = u32x4{g.x, g.y, g.z, g.w};
         }
       } else {
-        rb[i] = *(kv ? (gptr16)(wrow[i] + woff) : zpage);
+        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, kv ? voffW[i] : kOob, wsoff, 0);
       }
     }
   };
@@ -461,7 +481,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // Software pipeline: PF register sets hold the slices in flight from L2 / HBM, two LDS stages.
   // Step s multiplies slice s out of stage s%2 while slice s+1 moves from its registers to the other
   // stage and slices s+2 .. s+PF are in flight: one barrier per slice, PF-1 slices of load latency
-  // covered.  Every step is identical -- slices past the end are loaded from the zero page and add
+  // covered.  Every step is identical -- slices past the end load zeros (offset outside the descriptor) and add
   // nothing -- so the loop carries no conditional loads and the compiler's load counting holds.
   constexpr int PF = 2;
   static_assert(PF % 2 == 0, "stage parity must be static per unrolled step");
@@ -761,6 +781,13 @@ static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsa
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
 }
 
+// The kernels address an operand through a buffer descriptor with 32-bit byte offsets and keep the upper
+// half of that range for "reads as zero": one operand (activations of a layer, its weights) has to stay
+// below 2 GiB, with a little room for the tap offsets.
+static bool operand_too_big(long long rows, long long row_elems, int dtype) {
+  return (unsigned long long)rows * (unsigned long long)row_elems * elem_bytes(dtype) >= 0x7f000000ull;
+}
+
 static int validate_block(const void* x, const laud_fmap& fx, const laud_bottleneck* p, const void* out) {
   if (!x || !out || !p || !valid_fmap(fx)) return LAUD_ERR_INVALID_ARG;
   if (!p->w1 || !p->w2 || !p->w3 || !p->s1 || !p->t1 || !p->s2 || !p->t2 || !p->s3 || !p->t3)
@@ -769,6 +796,8 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   if (p->c_out != p->c_in) return LAUD_ERR_UNSUPPORTED;
   if (p->c_in % 8 || p->c_mid % 8) return LAUD_ERR_UNSUPPORTED;
   if ((long long)fx.N * fx.H * fx.W > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big((long long)fx.N * fx.H * fx.W, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype))
+    return LAUD_ERR_UNSUPPORTED;
   if (x != out) {  // partial overlap is not allowed
     const size_t bytes = (size_t)fx.N * fx.H * fx.W * fx.C * elem_bytes(fx.dtype);
     const char *a = (const char*)x, *b = (const char*)out;
@@ -803,6 +832,7 @@ static CsWs cs_ws_layout(const laud_fmap& fx, int c_mid) {
 
 int launch_dense_affine(int dtype, const void* A, const void* Wt, const float* scale, const float* shift, void* Out,
                         long long rows, int K, int ncols, int relu, hipStream_t stream) {
+  if (operand_too_big(rows, K, dtype) || operand_too_big(ncols, K, dtype)) return LAUD_ERR_UNSUPPORTED;
   GemmArgs a{};
   a.H = 1; a.W = 1; a.S = 1; a.D = 1; a.G = 1; a.Ho = 1; a.Wo = 1; a.stride = 1;  // one "pixel" per row
   a.A = A; a.Wt = Wt; a.scale = scale; a.shift = shift; a.Out = Out; a.K = K; a.ldw = K; a.Ncols = ncols;
@@ -1008,6 +1038,7 @@ extern "C" int laud_dyn_bottleneck_unfused(const void* x, laud_fmap fx, const la
   const int Hp = fx.H / S, Wp = fx.W / S, E = S + 2;
   const long long npatch = (long long)fx.N * Hp * Wp, npix = (long long)fx.N * fx.H * fx.W;
   if (npatch * E * E > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big(npatch * E * E, fx.C > p->c_mid ? fx.C : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
   const UnfusedWs L = unfused_ws_layout(fx, p->c_mid, S);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -1069,6 +1100,7 @@ extern "C" int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bo
   const int Ho = (fx.H - 1) / stride + 1, Wo = (fx.W - 1) / stride + 1;  // 3x3 pad 1 and 1x1 pad 0 agree on this
   const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
   if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < laud_static_bottleneck_workspace(fx, p, stride)) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -1133,6 +1165,7 @@ extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const
   if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
   const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
   if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
   const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, stride);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
