@@ -14,6 +14,9 @@
  *   - Feature maps are dense NHWC: element (n,y,x,c) at ((n*H + y)*W + x)*C + c.  One
  *     pixel's channel vector is contiguous.  dtype is LAUD_F32 or LAUD_BF16; C, c_in,
  *     c_mid and c_out must be multiples of 8 and every tensor base 16-byte aligned.
+ *     One feature map or scratch activation (N*H*W*max(c_in, c_mid) elements) has to stay
+ *     below 2 GiB (the kernels address an operand with 32-bit byte offsets); larger
+ *     shapes return LAUD_ERR_UNSUPPORTED.
  *   - Weights have the feature map's dtype: w1 [c_mid][c_in], w2 [c_mid][3][3][c_mid]
  *     (out, ky, kx, in; stride 1, zero padding 1, cross-correlation), w3 [c_out][c_mid].
  *     The per-channel affine (folded BN, Sec. 3.4) is float32: s1,t1,s2,t2 [c_mid],
