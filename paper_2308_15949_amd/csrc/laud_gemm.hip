@@ -382,27 +382,43 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // Issues the loads of this thread's 16-byte chunks of the next K slice (A: AR rows, B: BR weight
   // rows).  All loads are unconditional and branch-free, so the compiler can count the loads in
   // flight instead of draining them.  Slices are visited in order; (tap, kc) advance per call.
-  const int gW = a.W, glda = a.lda, gK = a.K, gG = a.G;
-  int ld_tap = 0, ld_kc = 0, ld_ky = -1, ld_kx = -1;
-  auto load_slice = [&](u32x4 (&ra)[AR], u32x4 (&rb)[BR], int& ke_out) __attribute__((always_inline)) {
+  const int gK = a.K, gG = a.G;
+  // Scalar state of the load side, advanced once per slice: byte offsets of the slice in the activation
+  // and weight operands, the position (tap, K chunk) and the tap's bit for the rows' tap masks.  Past the
+  // last tap the bit has left the masks' range and `live` is off, so null slices select nothing.
+  constexpr int NTAPS = TAPS ? 9 : 1;
+  constexpr int SLICE_B = BKE * (int)sizeof(ET);  // 128
+  const int rowW = ROWW_IS_TILE ? a.S + 2 : a.W;
+  const int pix_b = a.lda * (int)sizeof(ET);
+  const int back_b = (kchunks - 1) * SLICE_B;     // from a tap's last slice back to its first
+  const int a_pixjump = pix_b - back_b, a_rowjump = (rowW - 2) * pix_b - back_b;
+  const int w_tapjump = gK * (int)sizeof(ET) - back_b;
+  // only a tap's last K chunk can be partial: whether this thread's chunk of it lies inside K
+  const bool lastok = (kchunks - 1) * BKE + cc * EPC < keff;
+  int ld_tap = 0, ld_kc = 0, ld_kx = -1, s_a = 0, s_w = 0;
+  unsigned tapbit = 1u;
+  bool live = true;
+  auto load_slice = [&](u32x4 (&ra)[AR], u32x4 (&rb)[BR]) __attribute__((always_inline)) -> int {
     const int tap = ld_tap;
-    const int kbase = ld_kc * BKE;          // wave-uniform first K element of the slice
-    const int ke = kbase + cc * EPC;        // this thread's first (compact) K element
-    ke_out = ke;
-    const bool kv = ke < keff && tap < (TAPS ? 9 : 1);  // slices past the end read as zeros
-    // wave-uniform byte offsets of this slice (scalar registers)
-    const int rowW = ROWW_IS_TILE ? a.S + 2 : gW;
-    const int asoff = (TAPS ? ((ld_ky + 1) * rowW + (ld_kx + 1)) * glda + kbase : kbase) * (int)sizeof(ET);
-    const int wsoff = (tap * gK + kbase) * (int)sizeof(ET);
-    [[maybe_unused]] const long long woff = (long long)tap * gK + kbase;
-    const unsigned tapbit = tap < (TAPS ? 9 : 1) ? 1u << (TAPS ? tap : 0) : 0u;  // null slices select nothing
-    if (++ld_kc == kchunks) {
-      ld_kc = 0; ++ld_tap;
-      if (++ld_kx == 2) { ld_kx = -1; ++ld_ky; }
-    }
+    const int ke = ld_kc * BKE + cc * EPC;  // this thread's first (compact) K element
+    // (with an empty reduction -- channel skipping with every group dropped -- kchunks is 0 and no chunk is inside K)
+    const bool kok = ld_kc < kchunks - 1 || (ld_kc == kchunks - 1 && lastok);
+    const bool kv = kok && live;            // slices past the end read as zeros
+    const int asoff = s_a, wsoff = s_w;
+    const unsigned tb = tapbit;
+    // branch-free advance (scalar selects)
+    const bool wrap = ld_kc + 1 == kchunks;       // last K chunk of the tap
+    const bool rowwrap = wrap && ld_kx == 1;      // ... of the last tap of a tap row
+    s_a += wrap ? (rowwrap ? a_rowjump : a_pixjump) : SLICE_B;
+    s_w += wrap ? w_tapjump : SLICE_B;
+    ld_kc = wrap ? 0 : ld_kc + 1;
+    ld_kx = rowwrap ? -1 : ld_kx + (wrap ? 1 : 0);
+    ld_tap += wrap ? 1 : 0;
+    tapbit <<= wrap ? 1 : 0;
+    live = ld_tap < NTAPS;
 #pragma unroll
     for (int i = 0; i < AR; ++i) {
-      const bool ok = ke < keff && (amask[i] & tapbit);
+      const bool ok = kok && (amask[i] & tb);
       ra[i] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, ok ? voffA[i] : kOob, asoff, 0);
     }
 #pragma unroll
@@ -420,6 +436,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         rb[i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, kv ? voffW[i] : kOob, wsoff, 0);
       }
     }
+    return ke;
   };
   auto store_slice = [&](int buf, const u32x4 (&ra)[AR], const u32x4 (&rb)[BR], int ke) __attribute__((always_inline)) {
     unsigned char* sA = smem + buf * STAGE_BYTES;
@@ -488,16 +505,16 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   u32x4 ra[PF][AR], rb[PF][BR];
   int kes[PF];
 #pragma unroll
-  for (int d = 0; d < PF; ++d) load_slice(ra[d], rb[d], kes[d]);
+  for (int d = 0; d < PF; ++d) kes[d] = load_slice(ra[d], rb[d]);
   store_slice(0, ra[0], rb[0], kes[0]);
-  load_slice(ra[0], rb[0], kes[0]);
+  kes[0] = load_slice(ra[0], rb[0]);
   __syncthreads();  // stage 0 is ready; also publishes s_row
   for (int s0 = 0; s0 < KT; s0 += PF) {
 #pragma unroll
     for (int d = 0; d < PF; ++d) {
       const int nx = (d + 1) % PF;            // register set of slice s0+d+1
       store_slice((d + 1) & 1, ra[nx], rb[nx], kes[nx]);
-      load_slice(ra[nx], rb[nx], kes[nx]);
+      kes[nx] = load_slice(ra[nx], rb[nx]);
       compute(d & 1);
       __syncthreads();
     }
