@@ -48,6 +48,25 @@ __device__ __forceinline__ int ballot_prefix(unsigned long long b) {
   return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
 }
 
+// Exclusive scan of one count per wave across the (at most 64) waves of a block: every wave leaves
+// its count in wsum[wave], one barrier, then each wave scans the counts with wave shuffles (no thread
+// walks the list alone).  Returns the sum of the counts of the waves before this one; *total gets the
+// block's sum.  wsum must not be reused by the next call before another barrier: alternate two arrays.
+__device__ __forceinline__ int scan_wave_counts(int count, int nwaves, int* wsum, int* total) {
+  const int lane = lane_id(), wave = (int)threadIdx.x / kWave;
+  if (lane == 0) wsum[wave] = count;
+  __syncthreads();
+  const int v = lane < nwaves ? wsum[lane] : 0;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int t = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += t;
+  }
+  *total = __shfl(incl, kWave - 1, kWave);
+  return __shfl(incl - v, wave, kWave);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
                                                              int32_t* __restrict__ sample_offsets, int per_sample,
                                                              const int32_t* __restrict__ block_counts, int nblocks) {
   __shared__ int wsum[kCompactThreads / kWave];
-  __shared__ int woff[kCompactThreads / kWave];
+  __shared__ int scan[2][kCompactThreads / kWave];
   __shared__ int s_base;
   const int wave = threadIdx.x / kWave, lane = lane_id();
 
@@ -70,19 +70,12 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact(const uint8_t* __re
     const bool f = (i < n) && mask[i] != 0;
     const unsigned long long b = __ballot(f);
     const int lp = ballot_prefix(b);
-    if (lane == 0) wsum[wave] = __popcll(b);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
-      wsum[0] = t;  // chunk total (wsum[0] already consumed above)
-    }
-    __syncthreads();
-    const int pos = running + woff[wave] + lp;  // number of set entries before i
+    int tot;
+    const int wo = scan_wave_counts(__popcll(b), kCompactThreads / kWave, scan[k & 1], &tot);
+    const int pos = running + wo + lp;  // number of set entries before i
     if (f) idx[pos] = i;
     if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos;
-    running += wsum[0];
-    __syncthreads();
+    running += tot;
   }
   if ((int)blockIdx.x == nblocks - 1 && threadIdx.x == 0) {
     *count = running;
@@ -140,12 +133,9 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
                                                                    int32_t* __restrict__ count,
                                                                    int32_t* __restrict__ sample_offsets,
                                                                    int per_sample) {
-  __shared__ int wsum[kCompactThreads / kWave];
-  __shared__ int woff[kCompactThreads / kWave];
-  __shared__ int s_tot;
-  const int wave = threadIdx.x / kWave, lane = lane_id();
-  int running = 0;
-  for (int base = 0; base < n; base += 4 * kCompactThreads) {
+  __shared__ int scan[2][kCompactThreads / kWave];
+  int running = 0, pass = 0;
+  for (int base = 0; base < n; base += 4 * kCompactThreads, ++pass) {
     const int i0 = base + 4 * (int)threadIdx.x;
     bool f[4];
     unsigned long long b[4];
@@ -156,26 +146,18 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
       b[j] = __ballot(f[j]);
       before += ballot_prefix(b[j]);  // set entries of lower lanes at position j
     }
-    int wtot = 0;
+    int wtot = 0, tot;
 #pragma unroll
     for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
-    if (lane == 0) wsum[wave] = wtot;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
-      s_tot = t;
-    }
-    __syncthreads();
-    int pos = running + woff[wave] + before;  // set entries before (this thread, position 0)
+    const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[pass & 1], &tot);
+    int pos = running + wo + before;  // set entries before (this thread, position 0)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i = i0 + j;
       if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
       if (f[j]) { idx[pos + mine] = i; ++mine; }
     }
-    running += s_tot;
-    __syncthreads();
+    running += tot;
   }
   if (threadIdx.x == 0) {
     *count = running;
@@ -194,10 +176,7 @@ __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa
                                                                      int32_t* __restrict__ count,
                                                                      int32_t* __restrict__ sample_offsets,
                                                                      int per_sample) {
-  __shared__ int wsum[kCompactThreads / kWave];
-  __shared__ int woff[kCompactThreads / kWave];
-  __shared__ int s_tot;
-  const int wave = threadIdx.x / kWave, lane = lane_id();
+  __shared__ int scan[2][kCompactThreads / kWave];
   const int Hp = pa.H / 2, Wp = pa.W / 2;
   float2 top[2][4], bot[2][4];
   int sample[2][4];
@@ -236,26 +215,18 @@ __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa
       b[j] = __ballot(f[j]);
       before += ballot_prefix(b[j]);
     }
-    int wtot = 0;
+    int wtot = 0, tot;
 #pragma unroll
     for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
-    if (lane == 0) wsum[wave] = wtot;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int w = 0; w < kCompactThreads / kWave; ++w) { woff[w] = t; t += wsum[w]; }
-      s_tot = t;
-    }
-    __syncthreads();
-    const int pos = running + woff[wave] + before;
+    const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[p & 1], &tot);
+    const int pos = running + wo + before;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i = i0 + j;
       if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
       if (f[j]) { idx[pos + mine] = i; ++mine; }
     }
-    running += s_tot;
-    __syncthreads();
+    running += tot;
   }
   if (threadIdx.x == 0) {
     *count = running;
