@@ -376,11 +376,11 @@ def test_channel_skip(G, case, inplace):
 # ------------------------------------------------------------------------------------------
 # full-size workload of the benchmark (config 2), sampled images
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("r", [0.25, 1.0])
-def test_config2_full_size_sampled(G, r):
+@pytest.mark.parametrize("r,fused", [(0.25, False), (1.0, False), (0.5, True), (0.25, True)])
+def test_config2_full_size_sampled(G, r, fused):
     """128 x 14 x 14 x 1024 bf16, mid 256, S = 2, mask from the masker at ratio r -- the launch
-    configuration the benchmark times.  Samples are independent, so the oracle evaluates a few
-    whole images one by one."""
+    configuration the benchmark times (fused = its default entry point, the masker inside the first 1x1).
+    Samples are independent, so the oracle evaluates a few whole images one by one."""
     t, L, D = G.torch, G.L, G.D
     st = I.STAGES[3]
     N, H, C, m, S, dt = 128, st["hw"], st["c_in"], st["m"], st["S"], I.BF16
@@ -403,12 +403,17 @@ def test_config2_full_size_sampled(G, r):
     L.laud_mask_gen(xd, fx, S, wd, 0.0, None, mask, idx, cnt, None, lg, wsm)
     t.cuda.synchronize()
     bias, _ = I.bias_for_ratio(lg.cpu().numpy(), r)
-    L.laud_mask_gen(xd, fx, S, wd, bias, None, mask, idx, cnt, None, lg, wsm)
     ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
-    L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
+    if fused:
+        mask.zero_(); idx.zero_(); cnt.zero_()
+        L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, wd, bias, None, mask, idx, cnt, None, lg, xd, ws)
+    else:
+        L.laud_mask_gen(xd, fx, S, wd, bias, None, mask, idx, cnt, None, lg, wsm)
+        L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
     t.cuda.synchronize()
     got_mask = mask.cpu().numpy().reshape(N, H // S, H // S)
     assert abs(int(cnt.item()) - round(r * npatch)) <= 16
+    assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(got_mask))
     ref_logits = ref0 + bias
     sure = np.abs(ref_logits) > 1e-4
     assert np.array_equal(got_mask[sample][sure], O.threshold(ref_logits)[sure])
