@@ -135,6 +135,42 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                     "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
                     "mfma_frac_useful": round(useful / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
             del xb, xs
+    # spatially coherent masks (contiguous active regions, like learned masks) against independent patches at
+    # the same ratio: the dilated set conv1 covers shrinks, so the sparse-conv1 path gains (config 2 geometry)
+    sg = I.STAGES[3]
+    N, Ss = 128, sg["S"]
+    xs = D.to_device(I.feature_map(7450, 8, sg["hw"], sg["hw"], sg["c_in"], I.BF16), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+    fxs = L.fmap_of(xs)
+    dbs = D.DeviceBottleneck(I.bottleneck_params(7451, sg["c_in"], sg["m"], sg["c_in"], I.BF16))
+    hp = sg["hw"] // Ss
+    npatch = N * hp * hp
+    ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cn = t.zeros(1, dtype=t.int32, device="cuda")
+    wsc = D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, npatch))
+    wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+    xb = [xs.clone() for _ in range(4)]
+    res = {}
+    for kind in ("bernoulli", "coherent"):
+        for ratio in (0.25, 0.5):
+            mk_h = (I.bernoulli_mask(7452, (N, hp, hp), ratio) if kind == "bernoulli"
+                    else I.coherent_mask(7453, N, hp, hp, ratio))
+            mk = t.from_numpy(np.ascontiguousarray(mk_h.reshape(-1))).cuda()
+            up = np.kron(mk_h, np.ones((1, Ss, Ss), np.uint8)).astype(bool)   # pixels of active patches ...
+            pad = np.zeros((N, sg["hw"] + 2, sg["hw"] + 2), bool)
+            pad[:, 1:-1, 1:-1] = up
+            dil = np.zeros_like(up)
+            for dy in range(3):                                                   # ... and their 3x3 dilation
+                for dx in range(3):
+                    dil |= pad[:, dy:dy + sg["hw"], dx:dx + sg["hw"]]
+
+            def blk(i):
+                L.laud_layer_skip_compact(mk, npatch, ids, cn, wsc)
+                L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, Ss, ids, cn, xb[i % 4], wsd)
+            us = _p50_us(t, blk, iters=12, warm=2)
+            res[f"{kind}_r{int(ratio * 100):03d}"] = {"p50_us": round(us, 1), "ratio": round(float(mk_h.mean()), 3),
+                                                      "dilated_ratio": round(float(dil.mean()), 3)}
+    ex["mask_structure_config2_two_call_block"] = res
+    del xb, xs, wsd
     # operator-fusion ablation in the manner of the paper's Tab. 1 (masker + block, p50 per step):
     #   unfused    = laud_mask_gen, then gather / convs on gathered tiles / scatter-add as separate kernels
     #   two-call   = laud_mask_gen + laud_dyn_bottleneck (gather fused into conv1/conv2, scatter-add fused)
