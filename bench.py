@@ -134,6 +134,18 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                 ex[f"channel_skip_stage{stage}_b64_keep050"] = {
                     "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
                     "mfma_frac_useful": round(useful / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+                # the channel masker that would produce such a mask (global average pooling + 2-layer MLP, D = 4):
+                # HBM-bound, reads x once; cold rotating buffers are not kept here, so the rate is a cache-warm one
+                wa, ba, wb2, bb2, hid = I.channel_masker_weights(7350 + stage, sg["c_in"], 4)
+                dev = lambda v: t.from_numpy(v).cuda()
+                wad, bad, wbd, bbd = dev(wa), dev(ba), dev(wb2), dev(bb2)
+                cmo = t.zeros((N, 4), dtype=t.uint8, device="cuda")
+                wsk = D.workspace(L.channel_masker_workspace(fxs))
+                usm = _p50_us(t, lambda i: L.laud_channel_masker(xb[i % 4], fxs, wad, bad, hid, wbd, bbd, 4, cmo, None, wsk))
+                xbytes_s = xs.numel() * xs.element_size()
+                ex[f"channel_masker_stage{stage}_b64"] = {"p50_us": round(usm, 1),
+                                                          "GB_per_s": round(xbytes_s / usm / 1e3, 0),
+                                                          "hbm_frac": round(xbytes_s / usm / 1e3 / PEAK_HBM_GBS, 3)}
             del xb, xs
     # spatially coherent masks (contiguous active regions, like learned masks) against independent patches at
     # the same ratio: the dilated set conv1 covers shrinks, so the sparse-conv1 path gains (config 2 geometry)

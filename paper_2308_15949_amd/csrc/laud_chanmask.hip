@@ -32,8 +32,23 @@ __global__ __launch_bounds__(kGapThreads) void k_gap_partial(const ET* __restric
 #pragma unroll
     for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
     if (active) {
-      for (int p = p0 + pl; p < p1; p += lanes) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(x + ((size_t)n * HW + p) * C + (size_t)cv * EPC);
+      const ET* col = x + (size_t)n * HW * C + (size_t)cv * EPC;
+      int p = p0 + pl;
+      // four pixels' chunks in flight per thread before any is added (same order of additions as one by one)
+      for (; p + 3 * lanes < p1; p += 4 * lanes) {
+        uint4 raw[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw[u] = *reinterpret_cast<const uint4*>(col + (size_t)(p + u * lanes) * C);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          ET v[EPC];
+          __builtin_memcpy(v, &raw[u], 16);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) acc[e] += elem<ET>::load(&v[e]);
+        }
+      }
+      for (; p < p1; p += lanes) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(col + (size_t)p * C);
         ET v[EPC];
         __builtin_memcpy(v, &raw, 16);
 #pragma unroll
@@ -56,45 +71,77 @@ __global__ __launch_bounds__(kGapThreads) void k_gap_partial(const ET* __restric
   }
 }
 
-__global__ __launch_bounds__(256) void k_channel_mlp(const float* __restrict__ partial, int slabs, int HW, int C,
+constexpr int kMlpThreads = 1024;  // 16 waves: one hidden unit per wave in a single round for the usual 16 units
+__global__ __launch_bounds__(kMlpThreads) void k_channel_mlp(const float* __restrict__ partial, int slabs, int HW, int C,
                                                      const float* __restrict__ wa, const float* __restrict__ ba,
                                                      int hidden, const float* __restrict__ wb,
                                                      const float* __restrict__ bb, int D,
                                                      uint8_t* __restrict__ cmask, float* __restrict__ logits2) {
-  extern __shared__ float sm[];  // g[C], h[hidden], l[2D]
+  extern __shared__ __align__(16) float sm[];  // g[C], h[hidden], l[2D]
   float* g = sm;
   float* h = g + C;
   float* l = h + hidden;
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float inv = 1.0f / (float)HW;
-  for (int c = tid; c < C; c += 256) {
+  for (int c = tid; c < C; c += kMlpThreads) {
     float s = 0.f;
-    for (int k = 0; k < slabs; ++k) s += partial[((size_t)n * slabs + k) * C + c];
+    const float* pc = partial + (size_t)n * slabs * C + c;
+    int k = 0;
+    for (; k + 8 <= slabs; k += 8) {  // eight partial rows requested together, added in slab order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = pc[(size_t)(k + u) * C];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < slabs; ++k) s += pc[(size_t)k * C];
     g[c] = s * inv;
   }
   __syncthreads();
-  for (int j = wave; j < hidden; j += 4) {  // one wave per hidden unit
+  for (int j = wave; j < hidden; j += kMlpThreads / kWave) {  // one wave per hidden unit
+    // the weight row is read in 16-byte pieces, four of them requested before any is used: the row comes
+    // from L2 and a dependent load per element would cost a round trip each
+    const float4* wr = reinterpret_cast<const float4*>(wa + (size_t)j * C);
+    const float4* gv = reinterpret_cast<const float4*>(g);
+    const int nv = C / 4;
     float acc = 0.f;
-    for (int c = lane; c < C; c += kWave) acc += wa[(size_t)j * C + c] * g[c];
+    int c = lane;
+    for (; c + 3 * kWave < nv; c += 4 * kWave) {
+      float4 w4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) w4[u] = wr[c + u * kWave];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float4 g4 = gv[c + u * kWave];
+        acc += w4[u].x * g4.x + w4[u].y * g4.y + w4[u].z * g4.z + w4[u].w * g4.w;
+      }
+    }
+    for (; c < nv; c += kWave) {
+      const float4 w4 = wr[c], g4 = gv[c];
+      acc += w4.x * g4.x + w4.y * g4.y + w4.z * g4.z + w4.w * g4.w;
+    }
     acc = wave_sum(acc);
     if (lane == 0) h[j] = fmaxf(acc + ba[j], 0.f);
   }
   __syncthreads();
-  for (int o = tid; o < 2 * D; o += 256) {
+  for (int o = tid; o < 2 * D; o += kMlpThreads) {
     float acc = bb[o];
     for (int j = 0; j < hidden; ++j) acc += wb[(size_t)o * hidden + j] * h[j];
     l[o] = acc;
     if (logits2) logits2[(size_t)n * 2 * D + o] = acc;
   }
   __syncthreads();
-  for (int d = tid; d < D; d += 256) cmask[(size_t)n * D + d] = (l[2 * d] > l[2 * d + 1]) ? 1 : 0;  // false for NaN
+  for (int d = tid; d < D; d += kMlpThreads) cmask[(size_t)n * D + d] = (l[2 * d] > l[2 * d + 1]) ? 1 : 0;  // false for NaN
 }
 
+// Slabs per sample: about sixteen pixels per block (the partial sums are float32, so every slab writes
+// twice a pixel's bytes: few pixels per slab would write more than the kernel reads), more slabs only
+// while the grid is short of a thousand blocks and a slab keeps at least four pixels.
 static int gap_slabs(int N, int HW) {
-  int s = (2048 + N - 1) / N;  // aim at a couple of thousand blocks
-  if (s > HW) s = HW;
+  int s = HW / 16;
   if (s < 1) s = 1;
   if (s > 64) s = 64;
+  while ((long long)N * s < 1024 && s * 2 <= HW / 4 && s * 2 <= 64) s *= 2;
   return s;
 }
 
@@ -125,7 +172,7 @@ extern "C" int laud_channel_masker(const void* x, laud_fmap fx, const float* wa,
     hipLaunchKernelGGL((k_gap_partial<float>), dim3(fx.N * slabs), dim3(kGapThreads), 0, st, (const float*)x, HW,
                        fx.C, slabs, partial);
   if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
-  hipLaunchKernelGGL(k_channel_mlp, dim3(fx.N), dim3(256), (size_t)(fx.C + hidden + 2 * D) * sizeof(float), st,
+  hipLaunchKernelGGL(k_channel_mlp, dim3(fx.N), dim3(kMlpThreads), (size_t)(fx.C + hidden + 2 * D) * sizeof(float), st,
                      partial, slabs, HW, fx.C, wa, ba, hidden, wb, bb, D, cmask, logits2);
   return check_launch();
 }
