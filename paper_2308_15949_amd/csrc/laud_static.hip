@@ -39,6 +39,93 @@ __global__ __launch_bounds__(256) void k_stem_im2col(const ET* __restrict__ x, i
   for (int q = 0; q < (int)(sizeof(v) / 16); ++q) dst[q] = raw[q];
 }
 
+// ---- fused stem conv for the usual shape (bf16, 64 output channels) -----------------------------
+// The 7x7 stride-2 conv as an implicit GEMM straight from the image: no im2col buffer in HBM (it is
+// 13 times the image).  A block walks the 8 x 16-pixel output tiles of one band of 8 output rows; per tile
+// it puts the 21 x 38 input pixels the tile's windows cover into LDS, four bf16 per pixel (the fourth is
+// zero), and runs 32x32x16 MFMAs whose 8-element A fragments are two neighbouring pixels of one window
+// row: K = 7 rows x 8 taps x 4 channels = 224 with zero weights at the eighth tap and the fourth channel.
+// The weights are rearranged into that K order in LDS once per block.  Folded-BN affine and ReLU in the
+// accumulators, output rows through LDS so that stores are 16 bytes.
+typedef __attribute__((ext_vector_type(16))) float stem_f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 stem_bf16x8;
+constexpr int kSTY = 8, kSTX = 16;                    // output tile: 128 GEMM rows
+constexpr int kSPY = 2 * kSTY + 5, kSPW = 2 * kSTX + 6;  // 21 x 38 input pixels (38 is even and holds the padded 8th tap)
+constexpr int kSK = 7 * 32;                           // reduction length in the padded order
+constexpr int kSWS = kSK * 2 + 16;                    // LDS weight row stride in bytes
+constexpr int kSOS = 64 * 2 + 16;                     // LDS output row stride in bytes
+__global__ __launch_bounds__(256) void k_stem_conv_bf16(const bf16_t* __restrict__ x, int N, int Hin, int Win, int Hc,
+                                                        int Wc, const bf16_t* __restrict__ w7,
+                                                        const float* __restrict__ s, const float* __restrict__ t,
+                                                        bf16_t* __restrict__ out) {
+  __shared__ __align__(16) unsigned char s_w[64 * kSWS];
+  __shared__ __align__(16) unsigned char s_p[kSPY * kSPW * 8];
+  __shared__ __align__(16) unsigned char s_o[kSTY * kSTX * kSOS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+  const int r = lane & 31, h = lane >> 5;
+  for (int i = tid; i < 64 * kSK; i += 256) {
+    const int col = i / kSK, k = i - col * kSK;
+    const int ky = k >> 5, kx = (k & 31) >> 2, c = k & 3;
+    bf16_t v = 0;
+    if (kx < 7 && c < 3) v = w7[col * kStemK + (ky * 7 + kx) * 3 + c];
+    *reinterpret_cast<bf16_t*>(s_w + col * kSWS + k * 2) = v;
+  }
+  const int nbands = (Hc + kSTY - 1) / kSTY;
+  const int n = blockIdx.x / nbands, y0 = (blockIdx.x - n * nbands) * kSTY;
+  const int col = wn * 32 + r;
+  const float sc = s[col], sh = t[col];
+  for (int x0 = 0; x0 < Wc; x0 += kSTX) {
+    __syncthreads();  // the previous tile's reads of s_p and s_o are over (first pass: the weights are in place)
+    for (int p = tid; p < kSPY * kSPW; p += 256) {
+      const int py = p / kSPW, px = p - py * kSPW;
+      const int iy = 2 * y0 - 3 + py, ix = 2 * x0 - 3 + px;
+      bf16_t v0 = 0, v1 = 0, v2 = 0;
+      if (iy >= 0 && iy < Hin && ix >= 0 && ix < Win) {
+        const bf16_t* src = x + (((size_t)n * Hin + iy) * Win + ix) * 3;
+        v0 = src[0]; v1 = src[1]; v2 = src[2];
+      }
+      uint2 pk;
+      pk.x = (unsigned)v0 | ((unsigned)v1 << 16);
+      pk.y = (unsigned)v2;
+      *reinterpret_cast<uint2*>(s_p + p * 8) = pk;
+    }
+    __syncthreads();
+    stem_f32x16 acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+#pragma unroll
+    for (int st = 0; st < kSK / 16; ++st) {
+      const int f = 2 * st + h, ky = f >> 2, j = f & 3;  // this lane's fragment: window row ky, taps 2j and 2j+1
+      const uint4 b = *reinterpret_cast<const uint4*>(s_w + col * kSWS + (st * 16 + h * 8) * 2);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int rr = wm * 64 + i * 32 + r, yo = rr >> 4, xo = rr & 15;
+        const uint4 a = *reinterpret_cast<const uint4*>(s_p + ((2 * yo + ky) * kSPW + 2 * xo + 2 * j) * 8);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(stem_bf16x8, a),
+                                                         __builtin_bit_cast(stem_bf16x8, b), acc[i], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+        *reinterpret_cast<bf16_t*>(s_o + row * kSOS + col * 2) = f32_to_bf16(fmaxf(acc[i][e] * sc + sh, 0.f));
+      }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int id = tid + q * 256, row = id >> 3, ch = id & 7;
+      const int Y = y0 + (row >> 4), X = x0 + (row & 15);
+      if (Y < Hc && X < Wc)
+        *reinterpret_cast<uint4*>(out + (((size_t)n * Hc + Y) * Wc + X) * 64 + ch * 8) =
+            *reinterpret_cast<const uint4*>(s_o + row * kSOS + ch * 16);
+    }
+  }
+}
+
 // Weights [c_out][7][7][3] -> [c_out][kStemKp] with zero padding columns.
 template <typename ET>
 __global__ void k_stem_pack_weights(const ET* __restrict__ w7, int c_out, ET* __restrict__ wp) {
@@ -116,6 +203,16 @@ extern "C" int laud_stem(const void* x, int N, int Hin, int Win, int dtype, cons
   const StemWs L = stem_ws_layout(N, Hin, Win, c_out, dtype);
   char* wsb = (char*)ws;
   void *cols = wsb + L.cols, *wp = wsb + L.wp, *conv = wsb + L.conv;
+  const unsigned pblocks0 = (unsigned)(((long long)N * Hp * Wp * (c_out / 8) + 255) / 256);
+  if (dtype == LAUD_BF16 && c_out == 64) {  // the usual stem: conv straight from the image, then the pooling kernel
+    const unsigned bands = (unsigned)(N * ((Hc + kSTY - 1) / kSTY));
+    hipLaunchKernelGGL(k_stem_conv_bf16, dim3(bands), dim3(256), 0, st, (const bf16_t*)x, N, Hin, Win, Hc, Wc,
+                       (const bf16_t*)w7, s, t, (bf16_t*)conv);
+    if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+    hipLaunchKernelGGL((k_maxpool3x3s2<bf16_t>), dim3(pblocks0), dim3(256), 0, st, (const bf16_t*)conv, N, Hc, Wc, c_out,
+                       Hp, Wp, (bf16_t*)out);
+    return check_launch();
+  }
   const unsigned iblocks = (unsigned)((rows * (kStemKp / 8) + 255) / 256);
   const unsigned wblocks = (unsigned)((c_out * kStemKp + 255) / 256);
   const unsigned pblocks = (unsigned)(((long long)N * Hp * Wp * (c_out / 8) + 255) / 256);

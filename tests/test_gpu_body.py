@@ -28,7 +28,8 @@ def shortcut_params(seed, c_in, c_out, dt):
     return w, (0.5 * (1 + 0.1 * g.standard_normal(c_out))).astype(np.float32), (0.1 * g.standard_normal(c_out)).astype(np.float32)
 
 
-@pytest.mark.parametrize("case", [(2, 33, 21, 16, I.F32), (2, 64, 64, 64, I.BF16), (1, 224, 224, 64, I.BF16)])
+@pytest.mark.parametrize("case", [(2, 33, 21, 16, I.F32), (2, 64, 64, 64, I.BF16), (1, 224, 224, 64, I.BF16),
+                                  (3, 45, 37, 64, I.BF16), (2, 45, 37, 64, I.F32), (2, 30, 30, 32, I.BF16)])
 def test_stem(case):
     import torch as t
     import paper_2308_15949_amd as L
