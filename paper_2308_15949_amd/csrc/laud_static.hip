@@ -1,7 +1,8 @@
 // Static stem of the ResNet body (the whole-body workload): 7x7 stride-2 conv on the 3-channel image with
 // folded-BN affine and ReLU, then 3x3 stride-2 max pooling.  Outside the dynamic hot path (it runs once
-// per image and is not masked): an im2col kernel feeds the dense MFMA GEMM of laud_gemm.hip, a plain
-// kernel pools.
+// per image and is not masked): the usual shape (bf16, 64 channels) is an implicit GEMM straight from the
+// image, other shapes go through an im2col kernel and the dense MFMA GEMM of laud_gemm.hip; a plain kernel
+// pools.
 #include "laud_common.h"
 
 namespace laud {
