@@ -651,7 +651,7 @@ __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict
                                                        int32_t* __restrict__ pix) {
   extern __shared__ unsigned char s_pm[];  // [ns*Hp*Wp] patch masks of the group's samples
   constexpr int NW = kNeedThreads / kWave;
-  __shared__ int wcnt[NW], woff[NW], s_tot;
+  __shared__ int scan[2][NW];
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the patch grid lives on the output grid Ho x Wo (= H x W when stride is 1); pixels are input pixels
   const int Hp = Ho / S, Wp = Wo / S, pps = Hp * Wp, HW = H * W;
@@ -666,14 +666,21 @@ __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict
     lo = lower_bound_dev(idx, cnt, n0 * pps);
     hi = lower_bound_dev(idx, cnt, (n0 + ns) * pps);
   }
-  for (int i = lo + tid; i < hi; i += kNeedThreads) {
-    const unsigned v = (unsigned)(idx[i] - n0 * pps);
-    if (v < (unsigned)(ns * pps)) s_pm[v] = 1;
+  // eight entries per thread requested before any is used: one round trip per batch, not per entry
+  for (int i0 = lo + tid; i0 < hi; i0 += 8 * kNeedThreads) {
+    int e[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) e[u] = idx[min(i0 + u * kNeedThreads, hi - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const unsigned v = (unsigned)(e[u] - n0 * pps);
+      if (i0 + u * kNeedThreads < hi && v < (unsigned)(ns * pps)) s_pm[v] = 1;
+    }
   }
   __syncthreads();
   int32_t* out = pix + (size_t)g * gs * HW;
   int running = 0;
-  for (int p0 = 0; p0 < ns * HW; p0 += kNeedThreads) {
+  for (int p0 = 0, it = 0; p0 < ns * HW; p0 += kNeedThreads, ++it) {
     const int pp = p0 + tid;
     bool need = false;
     if (pp < ns * HW) {
@@ -688,17 +695,10 @@ __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict
         for (int px = xo0 / S; px <= xo1 / S; ++px) need |= pm[py * Wp + px] != 0;
     }
     const unsigned long long b = __ballot(need);
-    if (lane == 0) wcnt[wave] = __popcll(b);
-    __syncthreads();
-    if (tid == 0) {
-      int t = 0;
-      for (int w = 0; w < NW; ++w) { woff[w] = t; t += wcnt[w]; }
-      s_tot = t;
-    }
-    __syncthreads();
-    if (need) out[running + woff[wave] + ballot_prefix(b)] = n0 * HW + pp;
-    running += s_tot;
-    __syncthreads();
+    int tot;
+    const int wo = scan_wave_counts(__popcll(b), NW, scan[it & 1], &tot);
+    if (need) out[running + wo + ballot_prefix(b)] = n0 * HW + pp;
+    running += tot;
   }
   if (tid == 0) need_counts[g] = running;
 }
