@@ -231,6 +231,9 @@ DYN_CASES = [
     (3, 7, 7, 2048, 512, 1, I.BF16, True),  # stage 4
     (2, 28, 28, 512, 128, 4, I.BF16, True),  # stage 2
     (2, 14, 14, 64, 32, 7, I.F32, False),
+    (8, 56, 56, 256, 64, 4, I.BF16, True),    # >= 8192 pixels, K = 64: weight-stationary last 1x1
+    (16, 28, 28, 512, 128, 4, I.BF16, False),  # ... K = 128
+    (48, 14, 14, 256, 256, 2, I.BF16, True),  # ... K = 256, two column tiles, ragged last row tile
     (2, 14, 14, 1024, 256, 7, I.BF16, True),  # stage 3 at the coarse granularity of the 4-4-7-1 set
     (2, 56, 56, 32, 16, 8, I.BF16, True),     # S = 8 (the 8-4-7-1 set), 7x7 patch grid
     (2, 28, 28, 32, 16, 14, I.F32, False),
