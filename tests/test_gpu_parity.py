@@ -626,3 +626,45 @@ def test_chain_of_dynamic_blocks_in_place(G):
         assert np.array_equal(got[~up], x_in[~up])
         assert_close(got[up], ref[up], TOL[dt], f"block {blk}")
         assert got.min() >= 0.0
+
+
+# ------------------------------------------------------------------------------------------
+# HIP graph capture: the entry points only enqueue kernels on the caller's stream
+# ------------------------------------------------------------------------------------------
+def test_fused_block_replays_from_a_hip_graph(G):
+    """Capture masker + block (out of place) once, replay it several times with eager work and
+    synchronisations in between, and compare every replay bit for bit with the eager result."""
+    t, L, D = G.torch, G.L, G.D
+    N, H, C, m, S, dt = 16, 14, 256, 64, 2, I.BF16
+    x = I.feature_map(970, N, H, H, C, dt)
+    hb = I.bottleneck_params(971, C, m, C, dt, True)
+    w = I.masker_weights(972, C)
+    bias, _ = I.bias_for_ratio(O.mask_logits(x, S, w, 0.0), 0.5)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    npatch = N * (H // S) ** 2
+    mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+    wd = t.from_numpy(w).cuda()
+    out = t.zeros_like(xd)
+
+    def call():
+        L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, wd, bias, None, mask, idx, cnt, None, None, out, ws)
+    call()  # eager: the reference (and one-time function attributes are set outside the capture)
+    t.cuda.synchronize()
+    ref_out, ref_idx, ref_cnt = out.clone(), idx.clone(), int(cnt.item())
+    assert 0 < ref_cnt < npatch
+    g = t.cuda.CUDAGraph()
+    with t.cuda.graph(g):
+        call()
+    for rep in range(4):
+        out.fill_(0); idx.fill_(-1); cnt.fill_(-1); mask.fill_(7); ws.fill_(0xFF)   # eager work between replays
+        t.cuda.synchronize()
+        g.replay()
+        t.cuda.synchronize()
+        assert int(cnt.item()) == ref_cnt, f"replay {rep}"
+        assert t.equal(idx[:ref_cnt], ref_idx[:ref_cnt]), f"replay {rep}"
+        assert t.equal(out.view(t.int16), ref_out.view(t.int16)), f"replay {rep}"
