@@ -24,7 +24,9 @@ filter neighbour counts 4/6/9, one-hot inputs); the library special case
 (activation ratio 1 == a standard bottleneck == torch.nn.functional.conv2d
 composition); the invariants ratio 1 == static block and ratio 0 == identity;
 the two-logit argmax == one-channel difference > 0 identity of App. B; the
-pool/1x1-conv commutation of App. B; the FLOP-ratio closed forms of Sec. 3.2.
+pool/1x1-conv commutation of App. B; the FLOP-ratio closed forms of Sec. 3.2;
+the group-convolution + SE block against torch's grouped conv2d / pooling composition (all
+active), a per-element brute force over every mask, and its reduction to dyn_bottleneck.
 No function in this file is "parity unpinned".
 """
 from __future__ import annotations
@@ -253,6 +255,78 @@ def layer_skip_bottleneck(x: np.ndarray, p: BottleneckParams, keep: np.ndarray,
     else:
         full = dyn_bottleneck(x64, p, S, mask_coarse)
     return np.where(keep[:, None, None, None], full, x64)
+
+
+# --------------------------------------------------------------------------- #
+# group convolution + squeeze-and-excitation blocks (Sec. 4: the RegNetY backbones; Sec. 3.2: the
+# design is meant to carry over to arbitrary bottleneck ratios and group convolutions)
+# --------------------------------------------------------------------------- #
+@dataclass
+class GroupSE:
+    """What a RegNetY-style bottleneck adds to BottleneckParams: the 3x3 is a group convolution
+    with g channels per group (w2 is then [m, 3, 3, g]: output channel o reads the input channels
+    (o // g) * g ... (o // g) * g + g - 1), and a squeeze-and-excitation module sits between the 3x3
+    (after its affine and ReLU) and the last 1x1.  se_width 0 (w_se1 None) means no SE module."""
+    g: int
+    w_se1: np.ndarray | None = None  # [se_width, m]
+    b_se1: np.ndarray | None = None  # [se_width]
+    w_se2: np.ndarray | None = None  # [m, se_width]
+    b_se2: np.ndarray | None = None  # [m]
+
+
+def group_conv3x3(h: np.ndarray, w: np.ndarray, g: int) -> np.ndarray:
+    """Stride-1, zero-pad-1 group cross-correlation with g channels per group (as many in as out):
+    out[n,y,x,o] = sum_{ky,kx,c<g} w[o,ky,kx,c] * hpad[n, y+ky, x+kx, (o//g)*g + c]."""
+    h = np.asarray(h, np.float64)
+    w = np.asarray(w, np.float64)
+    m = w.shape[0]
+    if m % g or h.shape[-1] != m or w.shape[-1] != g:
+        raise ValueError("group width must divide the channel count")
+    out = np.zeros(h.shape[:3] + (m,), np.float64)
+    for k in range(m // g):
+        out[..., k * g:(k + 1) * g] = conv3x3(h[..., k * g:(k + 1) * g], w[k * g:(k + 1) * g])
+    return out
+
+
+def se_scale(h2: np.ndarray, m_up: np.ndarray, e: GroupSE) -> np.ndarray:
+    """Squeeze-and-excitation gate per sample and channel, [N, m].  The paper does not say what the
+    squeeze averages over when only some locations are computed; the reading taken here: the mean over
+    the sample's COMPUTED (active) pixels, the only ones whose h2 exists in a sparse evaluation.  With
+    every pixel active this is the ordinary global average.  z = mean, gate = sigmoid(W2 relu(W1 z + b1)
+    + b2).  A sample without an active pixel gets gate 1 (its branch is never added)."""
+    h2 = np.asarray(h2, np.float64)
+    n, _, _, m = h2.shape
+    gate = np.ones((n, m), np.float64)
+    for b in range(n):
+        act = np.asarray(m_up[b]).astype(bool)
+        cnt = int(act.sum())
+        if cnt == 0:
+            continue
+        z = h2[b][act].sum(axis=0) / cnt
+        hid = relu(np.matmul(np.asarray(e.w_se1, np.float64), z) + np.asarray(e.b_se1, np.float64))
+        a = np.matmul(np.asarray(e.w_se2, np.float64), hid) + np.asarray(e.b_se2, np.float64)
+        gate[b] = 1.0 / (1.0 + np.exp(-a))
+    return gate
+
+
+def dyn_group_se_bottleneck(x: np.ndarray, p: BottleneckParams, e: GroupSE, S: int,
+                            mask_coarse: np.ndarray) -> np.ndarray:
+    """Spatially adaptive bottleneck whose 3x3 is a group convolution and which may carry an SE module
+    (the block of the RegNetY backbones, Sec. 4).  Dense-then-mask like dyn_bottleneck:
+        h1 = relu(affine(1x1(x))), h2 = relu(affine(group3x3(h1))) on every pixel,
+        gate = se_scale(h2, M_up) per sample,  f = affine(1x1(h2 * gate)),
+        out = M_up ? act(x + f) : x."""
+    q = p.as_f64()
+    x64 = np.asarray(x, np.float64)
+    m_up = upsample_mask(mask_coarse, S).astype(bool)
+    h1 = relu(affine(conv1x1(x64, q.w1), q.s1, q.t1))
+    h2 = relu(affine(group_conv3x3(h1, q.w2, e.g), q.s2, q.t2))
+    if e.w_se1 is not None:
+        h2 = h2 * se_scale(h2, m_up, e)[:, None, None, :]
+    y = x64 + affine(conv1x1(h2, q.w3), q.s3, q.t3)
+    if q.relu_out:
+        y = relu(y)
+    return np.where(m_up[..., None], y, x64)
 
 
 # --------------------------------------------------------------------------- #

@@ -606,3 +606,157 @@ def test_dyn_projection_block_invariants_and_masker():
     w = rng.standard_normal(c_in)
     pooled = F.adaptive_avg_pool2d(xt, (Ho // S, Wo // S)).permute(0, 2, 3, 1).numpy()
     np.testing.assert_allclose(O.strided_mask_logits(x, stride, S, w, 0.25), pooled @ w + 0.25, rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# group convolution + squeeze-and-excitation block (Sec. 4, RegNetY backbones)
+# --------------------------------------------------------------------------- #
+def _rand_group_se(rng, c, m, g, se_w, relu_out=False):
+    p = _rand_params(rng, c, m, c, relu_out)
+    p.w2 = rng.standard_normal((m, 3, 3, g)) * 0.5
+    e = O.GroupSE(g, rng.standard_normal((se_w, m)) * 0.7, 0.3 * rng.standard_normal(se_w),
+                  rng.standard_normal((m, se_w)) * 0.7, 0.3 * rng.standard_normal(m)) if se_w else O.GroupSE(g)
+    return p, e
+
+
+def _bf_group_se(x, p, e, S, mask):
+    """Sparse, loop-by-loop evaluation: h2 only at active pixels (group-restricted taps), the squeeze
+    as a running sum over exactly those pixels, then the gate, the last 1x1 and the residual."""
+    import math
+    xl, pl = np.asarray(x, np.float64).tolist(), _as_lists(p)
+    N, H, W, C = np.shape(x)
+    m, g = len(pl["w1"]), e.g
+    out = np.array(x, np.float64)
+    for n in range(N):
+        act = [(y, xx) for y in range(H) for xx in range(W) if mask[n][y // S][xx // S]]
+        if not act:
+            continue
+        h2 = {}
+        for (y, xx) in act:
+            row = []
+            for j in range(m):
+                acc = 0.0
+                for ky in range(3):
+                    for kx in range(3):
+                        for c in range(g):
+                            acc += pl["w2"][j][ky][kx][c] * _bf_h1(xl, pl, n, y + ky - 1, xx + kx - 1, (j // g) * g + c)
+                v = pl["s2"][j] * acc + pl["t2"][j]
+                row.append(v if v > 0.0 else 0.0)
+            h2[(y, xx)] = row
+        gate = [1.0] * m
+        if e.w_se1 is not None:
+            z = [sum(h2[q][j] for q in act) / len(act) for j in range(m)]
+            w1, b1, w2, b2 = (np.asarray(a, np.float64).tolist() for a in (e.w_se1, e.b_se1, e.w_se2, e.b_se2))
+            hid = [max(sum(w1[k][j] * z[j] for j in range(m)) + b1[k], 0.0) for k in range(len(b1))]
+            gate = [1.0 / (1.0 + math.exp(-(sum(w2[j][k] * hid[k] for k in range(len(hid))) + b2[j]))) for j in range(m)]
+        for (y, xx) in act:
+            for o in range(C):
+                f = sum(pl["w3"][o][j] * h2[(y, xx)][j] * gate[j] for j in range(m))
+                v = xl[n][y][xx][o] + pl["s3"][o] * f + pl["t3"][o]
+                out[n, y, xx, o] = 0.0 if (p.relu_out and v < 0.0) else v
+    return out
+
+
+@pytest.mark.parametrize("S,g,se_w,relu_out", [(1, 2, 3, True), (2, 2, 3, False), (2, 1, 2, True), (4, 4, 0, True),
+                                               (2, 4, 2, True)])
+def test_group_se_block_vs_bruteforce_all_masks(S, g, se_w, relu_out):
+    rng = np.random.default_rng(800 + 10 * S + g)
+    N, H, W, c, m = 1, 4, 4, 3, 4
+    x = rng.standard_normal((N, H, W, c))
+    p, e = _rand_group_se(rng, c, m, g, se_w, relu_out)
+    hp = H // S
+    masks = list(itertools.product([0, 1], repeat=hp * hp))
+    if len(masks) > 64:
+        masks = [masks[i] for i in rng.choice(len(masks), 48, replace=False)] + [masks[0], masks[-1]]
+    for bits in masks:
+        mask = np.array(bits, np.uint8).reshape(N, hp, hp)
+        np.testing.assert_allclose(O.dyn_group_se_bottleneck(x, p, e, S, mask), _bf_group_se(x, p, e, S, mask),
+                                   rtol=1e-11, atol=1e-11)
+
+
+def test_group_se_block_batched_bruteforce_and_empty_sample():
+    rng = np.random.default_rng(81)
+    N, H, W, c, m, g, S = 3, 4, 6, 4, 6, 3, 2
+    x = rng.standard_normal((N, H, W, c))
+    p, e = _rand_group_se(rng, c, m, g, 2, True)
+    mask = (rng.random((N, H // S, W // S)) < 0.5).astype(np.uint8)
+    mask[1] = 0  # a sample without any active patch stays untouched (and divides nothing by zero)
+    got = O.dyn_group_se_bottleneck(x, p, e, S, mask)
+    np.testing.assert_allclose(got, _bf_group_se(x, p, e, S, mask), rtol=1e-11, atol=1e-11)
+    assert np.array_equal(got[1], x[1])
+
+
+def test_group_se_block_all_active_equals_torch_composition():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(82)
+    N, H, W, c, m, g, se_w, S = 2, 6, 4, 8, 12, 4, 3, 2
+    x = rng.standard_normal((N, H, W, c))
+    p, e = _rand_group_se(rng, c, m, g, se_w, True)
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    aff = lambda z, s, b: z * t(s).view(1, -1, 1, 1) + t(b).view(1, -1, 1, 1)
+    xt = t(x).permute(0, 3, 1, 2)
+    h1 = F.relu(aff(F.conv2d(xt, t(p.w1)[:, :, None, None]), p.s1, p.t1))
+    h2 = F.relu(aff(F.conv2d(h1, t(p.w2).permute(0, 3, 1, 2), padding=1, groups=m // g), p.s2, p.t2))
+    z = F.adaptive_avg_pool2d(h2, 1)
+    gate = torch.sigmoid(F.conv2d(F.relu(F.conv2d(z, t(e.w_se1)[:, :, None, None], t(e.b_se1))),
+                                  t(e.w_se2)[:, :, None, None], t(e.b_se2)))
+    want = F.relu(xt + aff(F.conv2d(h2 * gate, t(p.w3)[:, :, None, None]), p.s3, p.t3)).permute(0, 2, 3, 1).numpy()
+    ones = np.ones((N, H // S, W // S), np.uint8)
+    np.testing.assert_allclose(O.dyn_group_se_bottleneck(x, p, e, S, ones), want, rtol=1e-11, atol=1e-11)
+    # the group convolution alone against the library's
+    hh = rng.standard_normal((N, H, W, m))
+    np.testing.assert_allclose(O.group_conv3x3(hh, p.w2, g),
+                               F.conv2d(t(hh).permute(0, 3, 1, 2), t(p.w2).permute(0, 3, 1, 2), padding=1,
+                                        groups=m // g).permute(0, 2, 3, 1).numpy(), rtol=1e-11, atol=1e-11)
+    # layer skipping (S = H = W): kept samples get exactly this static block, the others stay as they are
+    Hs = 4
+    xs = rng.standard_normal((3, Hs, Hs, c))
+    keep = np.array([1, 0, 1], np.uint8).reshape(3, 1, 1)
+    full = O.dyn_group_se_bottleneck(xs, p, e, 1, np.ones((3, Hs, Hs), np.uint8))
+    got = O.dyn_group_se_bottleneck(xs, p, e, Hs, keep)
+    np.testing.assert_allclose(got[[0, 2]], full[[0, 2]], rtol=1e-12, atol=1e-12)
+    assert np.array_equal(got[1], xs[1])
+
+
+def test_group_se_block_reductions_and_locality():
+    rng = np.random.default_rng(83)
+    N, H, W, c, m, S = 2, 8, 8, 4, 6, 2
+    x = rng.standard_normal((N, H, W, c))
+    mask = (rng.random((N, H // S, W // S)) < 0.4).astype(np.uint8)
+    # one group as wide as the layer and a gate pinned at 1: the plain dynamic bottleneck
+    p, e = _rand_group_se(rng, c, m, m, 2, True)
+    e.w_se2 = np.zeros_like(e.w_se2)
+    e.b_se2 = np.full(m, 50.0)
+    np.testing.assert_allclose(O.dyn_group_se_bottleneck(x, p, e, S, mask), O.dyn_bottleneck(x, p, S, mask),
+                               rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.dyn_group_se_bottleneck(x, p, O.GroupSE(m), S, mask), O.dyn_bottleneck(x, p, S, mask),
+                               rtol=0, atol=0)
+    # a gate pinned at 1/2 (zero logits) halves the branch input of the last 1x1
+    p2, e2 = _rand_group_se(rng, c, m, 3, 2, False)
+    e2.w_se2 = np.zeros_like(e2.w_se2)
+    e2.b_se2 = np.zeros(m)
+    half = O.BottleneckParams(p2.w1, p2.w2, 0.5 * p2.w3, p2.s1, p2.t1, p2.s2, p2.t2, p2.s3, p2.t3, False)
+    np.testing.assert_allclose(O.dyn_group_se_bottleneck(x, p2, e2, S, mask),
+                               O.dyn_group_se_bottleneck(x, half, O.GroupSE(3), S, mask), rtol=1e-12, atol=1e-12)
+    # group-convolution weights embedded block-diagonally in a full 3x3 give the same block
+    p3, e3 = _rand_group_se(rng, c, m, 2, 3, True)
+    wfull = np.zeros((m, 3, 3, m))
+    for o in range(m):
+        wfull[o, :, :, (o // 2) * 2:(o // 2) * 2 + 2] = p3.w2[o]
+    pf = O.BottleneckParams(p3.w1, wfull, p3.w3, p3.s1, p3.t1, p3.s2, p3.t2, p3.s3, p3.t3, True)
+    ef = O.GroupSE(m, e3.w_se1, e3.b_se1, e3.w_se2, e3.b_se2)
+    a = O.dyn_group_se_bottleneck(x, p3, e3, S, mask)
+    np.testing.assert_allclose(a, O.dyn_group_se_bottleneck(x, pf, ef, S, mask), rtol=1e-12, atol=1e-12)
+    # locality of the sparse evaluation: the result depends on x only inside the one-pixel dilation of the
+    # active patches (the squeeze included, since it averages over active pixels only)
+    up = O.upsample_mask(mask, S).astype(bool)
+    pad = np.zeros((N, H + 2, W + 2), bool)
+    pad[:, 1:-1, 1:-1] = up
+    dil = np.zeros_like(up)
+    for dy in range(3):
+        for dx in range(3):
+            dil |= pad[:, dy:dy + H, dx:dx + W]
+    x2 = np.where(dil[..., None], x, x + rng.standard_normal(x.shape))
+    b = O.dyn_group_se_bottleneck(x2, p3, e3, S, mask)
+    assert np.array_equal(a[up], b[up])
