@@ -146,6 +146,38 @@ int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, i
                         const int32_t* idx, const int32_t* count, void* out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* What a group-convolution / squeeze-and-excitation bottleneck adds to laud_bottleneck (the RegNetY
+ * backbones of Sec. 4; Sec. 3.2 states that the dynamic block carries over to group convolutions). */
+typedef struct {
+  int32_t group_width; /* g: channels per group of the 3x3 (as many in as out); divides c_mid; 8, 16, 32 or 64.
+                          The block's w2 is then [c_mid][3][3][g]: output channel o reads the input channels
+                          (o/g)*g .. (o/g)*g + g-1. */
+  int32_t se_width;    /* hidden width of the SE module, <= 1024; 0 = no SE module (pointers below unused) */
+  const float* w_se1;  /* [se_width][c_mid] float32, device */
+  const float* b_se1;  /* [se_width] */
+  const float* w_se2;  /* [c_mid][se_width] */
+  const float* b_se2;  /* [c_mid] */
+} laud_group_se;
+
+/*
+ * Spatially adaptive bottleneck whose 3x3 is a group convolution, with an optional squeeze-and-excitation
+ * module between the 3x3 (after its affine and ReLU) and the last 1x1 (Sec. 4, RegNetY; Fig. 2(b) otherwise).
+ * Everything is as in laud_dyn_bottleneck except
+ *   h2 = relu(s2*groupconv3x3(h1;w2) + t2),
+ *   gate[n][c] = sigmoid(w_se2 * relu(w_se1 * z[n] + b_se1) + b_se2),  z[n] = mean of h2 over the ACTIVE
+ *   pixels of sample n (the paper does not say what the squeeze averages over when only some locations are
+ *   computed; with every patch active, and for layer skipping with S == H == W, this is the ordinary
+ *   global average),
+ *   out = act(x + s3*conv1x1(h2 * gate[n]; w3) + t3) on active pixels.
+ * h2 * gate is rounded to dtype before the last 1x1 (c_mid <= 4096 when se_width > 0).  Workspace:
+ * laud_workspace_size(LAUD_OP_DYN_BOTTLENECK, ...).  Errors as laud_dyn_bottleneck; a group width other
+ * than 8/16/32/64 returns LAUD_ERR_UNSUPPORTED, a null `e` or one that does not divide c_mid
+ * LAUD_ERR_INVALID_ARG.
+ */
+int laud_dyn_group_se_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                 const laud_group_se* e, int S, const int32_t* idx, const int32_t* count,
+                                 void* out, void* ws, size_t ws_bytes, void* stream);
+
 /*
  * The same block with the masker fused into the first 1x1 (Sec. 3.4 "Operator fusion for spatial
  * maskers"; App. B item 1): conv1 is evaluated on EVERY pixel (spatially static) and the masker's
@@ -268,7 +300,8 @@ typedef enum {
   LAUD_STAGE_CS2 = 9,
   LAUD_STAGE_CS3 = 10,
   LAUD_STAGE_SCATTER = 11,    /* stand-alone scatter + residual add (unfused schedule) */
-  LAUD_STAGE_COUNT = 12
+  LAUD_STAGE_SE = 12,         /* squeeze-and-excitation gate + rescale (group-conv / SE blocks) */
+  LAUD_STAGE_COUNT = 13
 } laud_stage;
 int laud_stage_timing_enable(int on);
 int laud_stage_timing_read(double* total_ms, int64_t* launches);

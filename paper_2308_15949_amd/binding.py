@@ -22,8 +22,8 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
-           "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
-STAGE_COUNT = 12
+           "laud_dyn_group_se_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+STAGE_COUNT = 13
 
 
 class Fmap(C.Structure):
@@ -35,6 +35,11 @@ class Bottleneck(C.Structure):
                 ("w1", C.c_void_p), ("w2", C.c_void_p), ("w3", C.c_void_p),
                 ("s1", C.c_void_p), ("t1", C.c_void_p), ("s2", C.c_void_p), ("t2", C.c_void_p),
                 ("s3", C.c_void_p), ("t3", C.c_void_p), ("relu_out", C.c_int32)]
+
+
+class GroupSE(C.Structure):
+    _fields_ = [("group_width", C.c_int32), ("se_width", C.c_int32), ("w_se1", C.c_void_p), ("b_se1", C.c_void_p),
+                ("w_se2", C.c_void_p), ("b_se2", C.c_void_p)]
 
 
 class LaudError(RuntimeError):
@@ -70,6 +75,9 @@ def load() -> C.CDLL:
     lib.laud_gather_patches.argtypes = [vp, Fmap, i32, i32, vp, vp, vp, vp]
     lib.laud_dyn_bottleneck.restype = i32
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
+    lib.laud_dyn_group_se_bottleneck.restype = i32
+    lib.laud_dyn_group_se_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), C.POINTER(GroupSE), i32, vp, vp, vp, vp,
+                                                 sz, vp]
     lib.laud_channel_skip_conv.restype = i32
     lib.laud_channel_skip_conv.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, i32, vp, vp, sz, vp]
     lib.laud_masker_dyn_bottleneck.restype = i32
@@ -185,6 +193,22 @@ def laud_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws)
     wp, wb = _ws_args(ws)
     _check(load().laud_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
                                       wp, wb, _stream()), "laud_dyn_bottleneck")
+
+
+def make_group_se(group_width: int, w_se1=None, b_se1=None, w_se2=None, b_se2=None) -> GroupSE:
+    """Descriptor of the group-convolution / SE extension over float32 device tensors (w_se1 [se_width, c_mid],
+    w_se2 [c_mid, se_width]); without tensors: group convolution only.  The caller keeps the tensors alive."""
+    if w_se1 is None:
+        return GroupSE(int(group_width), 0, None, None, None, None)
+    return GroupSE(int(group_width), int(w_se1.shape[0]), w_se1.data_ptr(), b_se1.data_ptr(), w_se2.data_ptr(),
+                   b_se2.data_ptr())
+
+
+def laud_dyn_group_se_bottleneck(x, fx: Fmap, p: Bottleneck, e: GroupSE, S: int, idx, count, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_dyn_group_se_bottleneck(_ptr(x), fx, C.byref(p), C.byref(e) if e is not None else None, int(S),
+                                               _ptr(idx), _ptr(count), _ptr(out), wp, wb, _stream()),
+           "laud_dyn_group_se_bottleneck")
 
 
 def laud_channel_skip_conv(x, fx: Fmap, p: Bottleneck, cmask, D: int, out, ws) -> None:

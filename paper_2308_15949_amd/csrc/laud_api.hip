@@ -55,7 +55,7 @@ extern "C" const char* laud_status_string(int status) {
   }
 }
 
-extern "C" int laud_abi_version(void) { return 1; }
+extern "C" int laud_abi_version(void) { return 2; }
 
 extern "C" int laud_stage_timing_enable(int on) {
   laud::recycle();
@@ -81,6 +81,6 @@ extern "C" int laud_stage_timing_read(double* total_ms, int64_t* launches) {
 
 extern "C" const char* laud_stage_name(int stage) {
   static const char* names[LAUD_STAGE_COUNT] = {"mask_logits", "compact", "gather", "copy_inactive", "need",
-                                               "conv1", "conv2", "conv3", "cs1", "cs2", "cs3", "scatter"};
+                                               "conv1", "conv2", "conv3", "cs1", "cs2", "cs3", "scatter", "se"};
   return (stage >= 0 && stage < LAUD_STAGE_COUNT) ? names[stage] : "?";
 }

@@ -23,6 +23,10 @@
 //   SD1..3 static dense convs of the always-executed first block of a stage: 1x1 with a spatial stride
 //          (SD1: conv1 with stride 1, shortcut with the block's stride), 3x3 with stride (SD2), last
 //          1x1 with the shortcut already in the output buffer as residual (SD3).
+//   G2     CONV2 as a group convolution (the RegNetY blocks of Sec. 4; Sec. 3.2 on group convolutions):
+//          the tile's BN output channels read only the BN input channels of their own groups, so the
+//          reduction per tap is that window of channels and the weight tile is block-diagonal -- chunks
+//          outside an output channel's group read as zeros, the ones inside come from w2 [m][3][3][g].
 //   CS1..3 the same three convs for channel skipping (Fig. 2(c)): one sample per blockIdx.y,
 //          output channels / reduction channels gathered through the sample's kept-group list,
 //          i.e. the weight gather is fused into the conv (Sec. 3.4).
@@ -41,7 +45,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* gptr16;  // 16-byte chunk in global memory
 
 enum { M_CONV1 = 0, M_CONV2 = 1, M_CONV3 = 2, M_CS1 = 3, M_CS2 = 4, M_CS3 = 5, M_DENSE1 = 6, M_U1 = 7, M_U2 = 8, M_U3 = 9,
-       M_SD1 = 10, M_SD2 = 11, M_SD3 = 12 };
+       M_SD1 = 10, M_SD2 = 11, M_SD3 = 12, M_G2 = 13 };
 
 // 256 bytes of zeros in device memory: the source of the zero chunks of the pointer-based weight gather
 // of channel skipping (every other load gets its zeros from the buffer descriptor's range check).  Not
@@ -73,6 +77,7 @@ struct GemmArgs {
   int group_rows, tiles_per_group;  // CONV1: pixel lists are kept per group of samples
   int m_rows;            // DENSE1, SD1..3: number of rows (all output pixels), known on the host
   int stride, Ho, Wo;    // SD1, SD2: spatial stride and output size (H, W are the input size)
+  int gw;                // G2: channels per group of the 3x3
   const float* wmask;    // DENSE1: masker weights [K] or null
   float* proj;           // DENSE1: per-pixel masker projection sum_c w[c]*x[pixel][c], [m_rows]
 };
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   constexpr int AR = BM / RPP, BR = BN / RPP;
   constexpr int TM = BM / 64, TN = BN / (32 * WGN);
   static_assert(AR >= 1 && BR >= 1 && TN >= 1, "tile too small for this many waves");
-  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2 || MODE == M_U2 || MODE == M_SD2);
+  constexpr bool TAPS = (MODE == M_CONV2 || MODE == M_CS2 || MODE == M_U2 || MODE == M_SD2 || MODE == M_G2);
   constexpr bool CS = (MODE >= M_CS1 && MODE <= M_CS3);
 
   constexpr int A_BYTES = BM * LSTR, B_BYTES = BN * LSTR, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       rt -= g * a.tiles_per_group;
       listp += (size_t)g * a.group_rows;
       M = a.count[g];
-    } else if constexpr (MODE == M_DENSE1 || MODE >= M_SD1) {
+    } else if constexpr (MODE == M_DENSE1 || (MODE >= M_SD1 && MODE <= M_SD3)) {
       M = a.m_rows;
     } else {
       M = *a.count * (MODE == M_U1 ? (a.S + 2) * (a.S + 2) : SS);
@@ -216,6 +221,9 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     if (MODE != M_CS1) keff = kw;
     if (col0 >= ncols) return;
   }
+  // group convolution: the reduction runs over the input channels col0 .. col0+BN-1 (the groups of this
+  // tile's output channels; the launcher makes BN a multiple of the group width)
+  if constexpr (MODE == M_G2) keff = min(BN, a.K - col0);
 
   // ---- row descriptors ------------------------------------------------------------------------
   // Each thread keeps, for the AR activation rows and BR weight rows it loads, one 32-bit byte offset
@@ -275,7 +283,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         const int E = a.S + 2;
         const int p = rho / SS, j = rho - p * SS;
         pixrow = (size_t)p * E * E + (size_t)(j / a.S + 1) * E + (j % a.S + 1);
-      } else if constexpr (MODE == M_CONV2) {
+      } else if constexpr (MODE == M_CONV2 || MODE == M_G2) {
         const int p = rho / SS, j = rho - p * SS;
         const int q = a.list[p];
         const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       } else {  // CS1, CS3
         pixrow = (size_t)sample * HW + rho;
       }
-      voffA[i] = (unsigned)((pixrow * a.lda + cc * EPC) * sizeof(ET));
+      voffA[i] = (unsigned)((pixrow * a.lda + cc * EPC + (MODE == M_G2 ? col0 : 0)) * sizeof(ET));
       if constexpr (MODE == M_U2) {
         amask[i] = 0x1ffu;  // every tap lies inside the gathered tile
       } else if constexpr (TAPS) {
@@ -313,7 +321,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       if constexpr (MODE == M_CONV1) {
         o = listp[rho];
       } else if constexpr (MODE == M_CONV2 || MODE == M_DENSE1 || MODE == M_U2 || MODE == M_U3 || MODE >= M_SD1) {
-        o = rho;
+        o = rho;  // (G2 included)
       } else if constexpr (MODE == M_U1) {
         // gathered position (p, e): inside the image -> row rho, outside -> -2 - rho (stored as zeros)
         const int E = a.S + 2;
@@ -351,6 +359,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // ---- weight-row descriptors -----------------------------------------------------------------
   const ET* wrow[BR];
   unsigned voffW[BR];
+  int wrel[BR];  // G2: first channel of this thread's chunk of the window's first slice, relative to the row's group
   bool cvalid[BR];
 #pragma unroll
   for (int i = 0; i < BR; ++i) {
@@ -361,6 +370,11 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     wrow[i] = Wp_ + (size_t)wr * a.ldw;
     if constexpr (!(MODE == M_CS2 || MODE == M_CS3)) wrow[i] += cc * EPC;
     voffW[i] = (unsigned)(((size_t)wr * a.ldw + cc * EPC) * sizeof(ET));
+    wrel[i] = 0;
+    if constexpr (MODE == M_G2) {
+      voffW[i] = (unsigned)((size_t)wr * a.ldw * sizeof(ET));
+      wrel[i] = col0 + cc * EPC - (wr / a.gw) * a.gw;
+    }
   }
   // DENSE1: the first column tile also accumulates the masker projection of its rows, on the vector
   // ALU, from the A chunks on their way from registers to LDS (each thread: AR rows x one chunk).
@@ -392,7 +406,10 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   const int pix_b = a.lda * (int)sizeof(ET);
   const int back_b = (kchunks - 1) * SLICE_B;     // from a tap's last slice back to its first
   const int a_pixjump = pix_b - back_b, a_rowjump = (rowW - 2) * pix_b - back_b;
-  const int w_tapjump = gK * (int)sizeof(ET) - back_b;
+  // weights: next slice of the same tap / first slice of the next tap (G2: a tap is gw channels wide and
+  // the slice position inside it goes into the per-thread offset)
+  const int w_step = MODE == M_G2 ? 0 : SLICE_B;
+  const int w_tapjump = MODE == M_G2 ? a.gw * (int)sizeof(ET) : gK * (int)sizeof(ET) - back_b;
   // only a tap's last K chunk can be partial: whether this thread's chunk of it lies inside K
   const bool lastok = (kchunks - 1) * BKE + cc * EPC < keff;
   int ld_tap = 0, ld_kc = 0, ld_kx = -1, s_a = 0, s_w = 0;
@@ -401,6 +418,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   auto load_slice = [&](u32x4 (&ra)[AR], u32x4 (&rb)[BR]) __attribute__((always_inline)) -> int {
     const int tap = ld_tap;
     const int ke = ld_kc * BKE + cc * EPC;  // this thread's first (compact) K element
+    const int kcb = ld_kc * BKE;
     // (with an empty reduction -- channel skipping with every group dropped -- kchunks is 0 and no chunk is inside K)
     const bool kok = ld_kc < kchunks - 1 || (ld_kc == kchunks - 1 && lastok);
     const bool kv = kok && live;            // slices past the end read as zeros
@@ -410,7 +428,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
     const bool wrap = ld_kc + 1 == kchunks;       // last K chunk of the tap
     const bool rowwrap = wrap && ld_kx == 1;      // ... of the last tap of a tap row
     s_a += wrap ? (rowwrap ? a_rowjump : a_pixjump) : SLICE_B;
-    s_w += wrap ? w_tapjump : SLICE_B;
+    s_w += wrap ? w_tapjump : w_step;
     ld_kc = wrap ? 0 : ld_kc + 1;
     ld_kx = rowwrap ? -1 : ld_kx + (wrap ? 1 : 0);
     ld_tap += wrap ? 1 : 0;
@@ -432,6 +450,11 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
           if (kv) g = gather_elems<ET>(wtap, s_kgrp, gG, ke, keff);
           rb[i] = u32x4{g.x, g.y, g.z, g.w};
         }
+      } else if constexpr (MODE == M_G2) {
+        const int rel = wrel[i] + kcb;  // chunk's first channel inside the row's group, if it is in it
+        const bool ing = kv && (unsigned)rel < (unsigned)a.gw;
+        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, ing ? voffW[i] + (unsigned)rel * (unsigned)sizeof(ET) : kOob,
+                                                      wsoff, 0);
       } else {
         rb[i] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, kv ? voffW[i] : kOob, wsoff, 0);
       }
@@ -722,6 +745,108 @@ __global__ __launch_bounds__(256) void k_copy_inactive(const uint4* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// squeeze-and-excitation on the compact rows of the active patches (RegNetY blocks, Sec. 4)
+// ------------------------------------------------------------------------------------------------
+
+// One block per sample.  The sample's active patches are a contiguous range of the ascending index list,
+// so its h2 rows are contiguous too: sum them per channel (fixed order: deterministic), divide by their
+// number, run the two small fully connected layers, and multiply the rows by the gate in place.  The
+// squeeze therefore averages over the sample's computed pixels; a sample without active patches has no rows.
+constexpr int kSeThreads = 512;
+constexpr int kSeMaxC = 4096, kSeMaxHidden = 1024;
+template <typename ET>
+__global__ __launch_bounds__(kSeThreads) void k_se_gate_scale(ET* __restrict__ h2, const int32_t* __restrict__ idx,
+                                                              const int32_t* __restrict__ count, int pps, int SS, int C,
+                                                              int se_w, const float* __restrict__ w1,
+                                                              const float* __restrict__ b1,
+                                                              const float* __restrict__ w2,
+                                                              const float* __restrict__ b2) {
+  constexpr int EPC = elem<ET>::per16;
+  __shared__ __align__(16) float s_part[kSeThreads * EPC];  // [row phase][chunk lane][EPC]
+  __shared__ __align__(16) float s_z[kSeMaxC];               // channel means, then the gate
+  __shared__ float s_hid[kSeMaxHidden];
+  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cnt = *count;
+  const int lo = lower_bound_dev(idx, cnt, n * pps), hi = lower_bound_dev(idx, cnt, (n + 1) * pps);
+  if (hi == lo) return;  // whole block: no barrier is skipped by some threads only
+  const long long r0 = (long long)lo * SS;
+  const int rows = (hi - lo) * SS;
+  const int cpr = C / EPC;  // 16-byte chunks per row
+  int CP = 1;
+  while (CP < cpr && CP < 128) CP <<= 1;  // chunk lanes: a power of two that divides the thread count
+  const int RP = kSeThreads / CP, cl = tid % CP, rp = tid / CP;
+  const uint4* base = reinterpret_cast<const uint4*>(h2 + r0 * C);
+  for (int cb = 0; cb < cpr; cb += CP) {
+    const int c = cb + cl;
+    float acc[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
+    if (c < cpr) {
+      int r = rp;
+      for (; r + 3 * RP < rows; r += 4 * RP) {  // four rows in flight
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = base[(size_t)(r + u * RP) * cpr + c];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          ET t[EPC];
+          __builtin_memcpy(t, &v[u], 16);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) acc[e] += elem<ET>::load(&t[e]);
+        }
+      }
+      for (; r < rows; r += RP) {
+        const uint4 v = base[(size_t)r * cpr + c];
+        ET t[EPC];
+        __builtin_memcpy(t, &v, 16);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] += elem<ET>::load(&t[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) s_part[(rp * CP + cl) * EPC + e] = acc[e];
+    __syncthreads();
+    // channel k of this chunk block: add the RP row phases in order
+    for (int k = tid; k < CP * EPC; k += kSeThreads) {
+      const int ch = cb * EPC + k;
+      if (ch < C) {
+        float t = 0.f;
+        for (int q = 0; q < RP; ++q) t += s_part[q * CP * EPC + k];
+        s_z[ch] = t / (float)rows;
+      }
+    }
+    __syncthreads();
+  }
+  // hidden layer: one wave per output, lanes stride over the channels
+  for (int k = wave; k < se_w; k += kSeThreads / kWave) {
+    float t = 0.f;
+    for (int c = lane; c < C; c += kWave) t += w1[(size_t)k * C + c] * s_z[c];
+    t = wave_sum(t);
+    if (lane == 0) s_hid[k] = fmaxf(t + b1[k], 0.f);
+  }
+  __syncthreads();
+  // gate: one thread per channel (overwrites the means, which are no longer needed)
+  for (int c = tid; c < C; c += kSeThreads) {
+    float t = b2[c];
+    for (int k = 0; k < se_w; ++k) t += w2[(size_t)c * se_w + k] * s_hid[k];
+    s_z[c] = 1.f / (1.f + __expf(-t));
+  }
+  __syncthreads();
+  uint4* wbase = reinterpret_cast<uint4*>(h2 + r0 * C);
+  const int total = rows * cpr;
+  for (int i = tid; i < total; i += kSeThreads) {
+    const int c = i % cpr;
+    uint4 v = wbase[i];
+    ET t[EPC];
+    __builtin_memcpy(t, &v, 16);
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) elem<ET>::store(&t[e], elem<ET>::load(&t[e]) * s_z[c * EPC + e]);
+    __builtin_memcpy(&v, t, 16);
+    wbase[i] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 struct Tile { int bm, bn, waves; };
@@ -790,9 +915,9 @@ static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hi
 
 template <int MODE>
 static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
-  constexpr int kStage[13] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CS1, LAUD_STAGE_CS2,
+  constexpr int kStage[14] = {LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CS1, LAUD_STAGE_CS2,
                               LAUD_STAGE_CS3,   LAUD_STAGE_CONV1, LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3,
-                              LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3};
+                              LAUD_STAGE_CONV1, LAUD_STAGE_CONV2, LAUD_STAGE_CONV3, LAUD_STAGE_CONV2};
   StageScope scope(kStage[MODE], st);
   return dtype == LAUD_BF16 ? launch_gemm_e<MODE, bf16_t>(a, cap_rows, nsamples, st)
                             : launch_gemm_e<MODE, float>(a, cap_rows, nsamples, st);
@@ -882,13 +1007,23 @@ extern "C" size_t laud_workspace_size(int op, laud_fmap fx, const laud_bottlenec
   }
 }
 
-extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S, const int32_t* idx,
-                                   const int32_t* count, void* out, void* ws, size_t ws_bytes, void* stream) {
+// The spatially adaptive block on an index list; `e` adds the group convolution / SE variant (or is null).
+static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, const laud_group_se* e, int S,
+                         const int32_t* idx, const int32_t* count, void* out, void* ws, size_t ws_bytes,
+                         void* stream) {
   int rc = validate_block(x, fx, p, out);
   if (rc != LAUD_OK) return rc;
   if (!idx || !count || S <= 0 || fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
   const int Hp = fx.H / S, Wp = fx.W / S;
   if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
+  if (e) {
+    if (e->group_width <= 0 || p->c_mid % e->group_width || e->se_width < 0) return LAUD_ERR_INVALID_ARG;
+    if (e->se_width > 0 && (!e->w_se1 || !e->b_se1 || !e->w_se2 || !e->b_se2)) return LAUD_ERR_INVALID_ARG;
+    // a 64-channel output tile must hold whole groups, and a group whole 16-byte chunks
+    const int g = e->group_width;
+    if (!(g == 8 || g == 16 || g == 32 || g == 64)) return LAUD_ERR_UNSUPPORTED;
+    if (e->se_width > kSeMaxHidden || (e->se_width > 0 && p->c_mid > kSeMaxC)) return LAUD_ERR_UNSUPPORTED;
+  }
   const DynWs L = dyn_ws_layout(fx, p->c_mid);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -932,12 +1067,46 @@ extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottl
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
   a.lda = p->c_mid; a.ldo = p->c_mid;
-  if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  if (!e) {
+    if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  } else {
+    // group convolution: w2 is [c_mid][3][3][g]; 64-channel output tiles read their own 64 input channels
+    a.gw = e->group_width;
+    a.ldw = 9 * e->group_width;
+    {
+      StageScope scope(LAUD_STAGE_CONV2, st);
+      rc = fx.dtype == LAUD_BF16 ? launch_gemm_t<M_G2, bf16_t, 64, 64, 2>(a, npix, 1, st)
+                                 : launch_gemm_t<M_G2, float, 64, 64, 2>(a, npix, 1, st);
+    }
+    if (rc != LAUD_OK) return rc;
+    if (e->se_width > 0) {
+      StageScope scope(LAUD_STAGE_SE, st);
+      if (fx.dtype == LAUD_BF16)
+        hipLaunchKernelGGL(k_se_gate_scale<bf16_t>, dim3((unsigned)fx.N), dim3(kSeThreads), 0, st, (bf16_t*)h2, idx, count,
+                           Hp * Wp, S * S, p->c_mid, e->se_width, e->w_se1, e->b_se1, e->w_se2, e->b_se2);
+      else
+        hipLaunchKernelGGL(k_se_gate_scale<float>, dim3((unsigned)fx.N), dim3(kSeThreads), 0, st, (float*)h2, idx, count,
+                           Hp * Wp, S * S, p->c_mid, e->se_width, e->w_se1, e->b_se1, e->w_se2, e->b_se2);
+      if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
+    }
+  }
   // conv3: 1x1 on dense h2 with the scatter-add epilogue
   a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
   a.relu = p->relu_out ? 1 : 0;
   return launch_gemm<M_CONV3>(fx.dtype, a, npix, 1, st);
+}
+
+extern "C" int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S, const int32_t* idx,
+                                   const int32_t* count, void* out, void* ws, size_t ws_bytes, void* stream) {
+  return run_dyn_block(x, fx, p, nullptr, S, idx, count, out, ws, ws_bytes, stream);
+}
+
+extern "C" int laud_dyn_group_se_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                            const laud_group_se* e, int S, const int32_t* idx, const int32_t* count,
+                                            void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!e) return LAUD_ERR_INVALID_ARG;
+  return run_dyn_block(x, fx, p, e, S, idx, count, out, ws, ws_bytes, stream);
 }
 
 extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,

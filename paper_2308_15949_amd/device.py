@@ -38,6 +38,19 @@ class DeviceBottleneck:
                                       self.s3, self.t3, hb.relu_out)
 
 
+class DeviceGroupSE:
+    """Device tensors of the SE module (if any) and the C descriptor of the group-conv / SE extension."""
+
+    def __init__(self, group_width: int, se=None, device: str = "cuda:0"):
+        import torch
+        self.t = None
+        if se is not None:
+            self.t = [torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(device) for v in se]
+            self.desc = B.make_group_se(group_width, *self.t)
+        else:
+            self.desc = B.make_group_se(group_width)
+
+
 def workspace(nbytes: int, device: str = "cuda:0"):
     import torch
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

@@ -70,9 +70,11 @@ class HostBottleneck:
 
 
 def bottleneck_params(seed: int, c_in: int, m: int, c_out: int, dtype: int,
-                      relu_out: bool = False, s3_gain: float = 1.0) -> HostBottleneck:
+                      relu_out: bool = False, s3_gain: float = 1.0, group_width: int | None = None) -> HostBottleneck:
     """Kaiming-normal weights (std = sqrt(2/fan_in)); affine s = 1 + 0.1 N(0,1),
-    t = 0.1 N(0,1) in float32 (the affine is never rounded to bf16)."""
+    t = 0.1 N(0,1) in float32 (the affine is never rounded to bf16).  With group_width g the 3x3 is
+    a group convolution: w2 [m, 3, 3, g], fan-in 9g."""
+    g2 = m if group_width is None else group_width
     def w(k, shape, fan_in):
         g = np.random.default_rng(seed + k)
         return round_to(g.standard_normal(shape, dtype=np.float32) * np.float32(np.sqrt(2.0 / fan_in)), dtype)
@@ -86,7 +88,7 @@ def bottleneck_params(seed: int, c_in: int, m: int, c_out: int, dtype: int,
     s2, t2 = aff(m)
     s3, t3 = aff(c_out, s3_gain)
     return HostBottleneck(c_in, m, c_out,
-                          w(1, (m, c_in), c_in), w(2, (m, 3, 3, m), 9 * m), w(3, (c_out, m), m),
+                          w(1, (m, c_in), c_in), w(2, (m, 3, 3, g2), 9 * g2), w(3, (c_out, m), m),
                           s1, t1, s2, t2, s3, t3, relu_out, dtype)
 
 
@@ -169,3 +171,23 @@ def channel_masker_weights(seed: int, c: int, d: int, hidden: int | None = None)
     wb = (g.standard_normal((2 * d, hidden)) / np.sqrt(hidden)).astype(np.float32)
     bb = (0.1 * g.standard_normal(2 * d)).astype(np.float32)
     return wa, ba, wb, bb, hidden
+
+
+def se_weights(seed: int, c: int, se_width: int):
+    """Squeeze-and-excitation weights (float32): w1 [se_width, C] ~ N(0, 2/C), b1 ~ 0.1 N(0,1),
+    w2 [C, se_width] ~ N(0, 4/se_width) (so that the gates spread over (0,1)), b2 ~ 0.5 N(0,1)."""
+    g = np.random.default_rng(seed)
+    w1 = (g.standard_normal((se_width, c)) * np.sqrt(2.0 / c)).astype(np.float32)
+    b1 = (0.1 * g.standard_normal(se_width)).astype(np.float32)
+    w2 = (g.standard_normal((c, se_width)) * np.sqrt(4.0 / se_width)).astype(np.float32)
+    b2 = (0.5 * g.standard_normal(c)).astype(np.float32)
+    return w1, b1, w2, b2
+
+
+# Identity blocks of the RegNetY-800MF stages at 224^2 (widths 64-144-320-784, group width 16, bottleneck
+# ratio 1; the SE module's hidden width is a quarter of the block's input width) and of RegNetY-400MF
+# (48-104-208-440, group width 8), the two lightweight backbones of Sec. 4.
+REGNETY = {
+    "800MF": dict(g=16, stages={1: dict(c=64, hw=56), 2: dict(c=144, hw=28), 3: dict(c=320, hw=14), 4: dict(c=784, hw=7)}),
+    "400MF": dict(g=8, stages={1: dict(c=48, hw=56), 2: dict(c=104, hw=28), 3: dict(c=208, hw=14), 4: dict(c=440, hw=7)}),
+}

@@ -30,7 +30,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == sorted(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert L.abi_version() == 1
+    assert L.abi_version() == 2
     assert L.status_string(0) == "LAUD_OK"
     for code in (-1, -2, -3, -4):
         assert L.status_string(code).startswith("LAUD_ERR_")
@@ -40,6 +40,7 @@ def test_struct_layout_matches_header():
     assert C.sizeof(B.Fmap) == 20
     # 3 ints (+4 pad), 9 pointers, 1 int (+4 pad)
     assert C.sizeof(B.Bottleneck) == 16 + 72 + 8
+    assert C.sizeof(B.GroupSE) == 8 + 32
 
 
 FAKE = 0x10000  # never dereferenced: validation happens on the host before any launch
@@ -130,6 +131,20 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, None, vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_INVALID_ARG       # no index list
     assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needp, st) == B.ERR_INVALID_ARG  # out == x
     assert dp(vp(FAKE), fx, C.byref(_bn(64, 12, 128)), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_UNSUPPORTED
+    # group-convolution / SE variant of the dynamic block
+    gs = lib.laud_dyn_group_se_bottleneck
+    pg = _bn(64, 64, 64)
+    needg = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, pg, 2)
+    ge = lambda g, w=0, ptr=FAKE: C.byref(B.GroupSE(g, w, ptr, ptr, ptr, ptr))
+    assert gs(vp(FAKE), fx, C.byref(pg), None, 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(0), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(24), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG  # 24 does not divide 64
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(4), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_UNSUPPORTED
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 8, None), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 2048), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_UNSUPPORTED
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(16, -1), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 8), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg - 1, st) == B.ERR_WORKSPACE
+    assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 8), 3, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG  # 3 does not divide 8
     sm = lib.laud_stem
     nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
     assert nst >= 2 * 32 * 32 * (152 + 64) * 2
