@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-extras", action="store_true", help="skip the short per-entry-point measurements")
+    ap.add_argument("--extras-only", choices=["regnety"], default=None,
+                    help="run only this group of the short measurements (for profiling one group)")
     ap.add_argument("--variant", choices=["fused", "two-call"], default="fused",
                     help="fused: laud_masker_dyn_bottleneck (masker fused into a static conv1); "
                          "two-call: laud_mask_gen + laud_dyn_bottleneck (sparse conv1)")
@@ -62,6 +64,68 @@ def _p50_us(t, fn, iters=20, warm=3, prep=None):
     t.cuda.synchronize()
     lat = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
     return lat[len(lat) // 2] * 1e3
+
+
+def measure_regnety(t, L, B, D, I):
+    ex = {}
+    # the lightweight backbone of Sec. 4: identity blocks of the RegNetY-800MF stages (group-convolution 3x3, group
+    # width 16, SE module; batch 128, bf16): masker + laud_dyn_group_se_bottleneck against the activation ratio
+    # (ratio 1 = every patch active = the static block's work plus the masker), layer skipping (S = H, a seeded
+    # Bernoulli(0.5) keep gate) and the per-stage kernel times at ratio 0.5.  The input is restored, untimed,
+    # before every step so that the masks stay at the calibrated ratio.
+    for stage, sg in I.REGNETY["800MF"]["stages"].items():
+        N, Cc, hw, gw, Ss = 128, sg["c"], sg["hw"], I.REGNETY["800MF"]["g"], I.STAGES[stage]["S"]
+        xs = D.to_device(I.feature_map(8200 + stage, 8, hw, hw, Cc, I.BF16), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        fxs = L.fmap_of(xs)
+        dbs = D.DeviceBottleneck(I.bottleneck_params(8210 + stage, Cc, Cc, Cc, I.BF16, relu_out=True, s3_gain=0.25,
+                                                     group_width=gw))
+        des = D.DeviceGroupSE(gw, I.se_weights(8220 + stage, Cc, max(8, Cc // 4 // 4 * 4)))
+        wm = t.from_numpy(I.masker_weights(8230 + stage, Cc)).cuda()
+        npatch = N * (hw // Ss) ** 2
+        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cn = t.zeros(1, dtype=t.int32, device="cuda")
+        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+        wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+        wsl = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, hw))
+        L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+        t.cuda.synchronize()
+        lg = lgs.cpu().numpy()
+        xb = [xs.clone() for _ in range(4)]
+        cell = {"i": 0}
+
+        def restore():
+            xb[cell["i"] % 4].copy_(xs)
+        res = {}
+        for ratio in (0.0, 0.25, 0.5, 0.75, 1.0):
+            b2 = I.bias_for_ratio(lg, ratio)[0]
+
+            def blk(i):
+                cell["i"] = i + 1
+                L.laud_mask_gen(xb[i % 4], fxs, Ss, wm, b2, None, mk, ids, cn, None, None, wsm2)
+                L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, Ss, ids, cn, xb[i % 4], wsd)
+            cell["i"] = 0
+            res[f"r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, blk, iters=12, warm=2, prep=restore), 1)
+            if ratio == 0.5:
+                L.laud_stage_timing_enable(True)
+                for i in range(8):
+                    cell["i"] = i
+                    restore()
+                    blk(i)
+                t.cuda.synchronize()
+                res["stage_us_r050"] = {k: round(v[0] / v[1] * 1e3, 1) for k, v in L.laud_stage_timing_read().items()}
+                L.laud_stage_timing_enable(False)
+        keep = t.from_numpy(I.bernoulli_mask(8240 + stage, (N,), 0.5)).cuda()
+        wsc = D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, N))
+
+        def lskip(i):
+            L.laud_layer_skip_compact(keep, N, ids, cn, wsc)
+            L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, hw, ids, cn, xb[i % 4], wsl)
+        res["layer_skip_keep050_p50_us"] = round(_p50_us(t, lskip, iters=12, warm=2), 1)
+        ex[f"regnety800mf_stage{stage}_b128"] = res
+        del xb, xs, wsd, wsl
+    return ex
 
 
 def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm):
@@ -262,63 +326,7 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[f"dynamic_r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, dynp, iters=12, warm=2), 1)
         ex[f"dyn_first_block_stage{stage}_b128"] = res
         del xs, outs, wsp, wsq
-    # the lightweight backbone of Sec. 4: identity blocks of the RegNetY-800MF stages (group-convolution 3x3, group
-    # width 16, SE module; batch 128, bf16): masker + laud_dyn_group_se_bottleneck against the activation ratio
-    # (ratio 1 = every patch active = the static block's work plus the masker), layer skipping (S = H, a seeded
-    # Bernoulli(0.5) keep gate) and the per-stage kernel times at ratio 0.5.  The input is restored, untimed,
-    # before every step so that the masks stay at the calibrated ratio.
-    for stage, sg in I.REGNETY["800MF"]["stages"].items():
-        N, Cc, hw, gw, Ss = 128, sg["c"], sg["hw"], I.REGNETY["800MF"]["g"], I.STAGES[stage]["S"]
-        xs = D.to_device(I.feature_map(8200 + stage, 8, hw, hw, Cc, I.BF16), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
-        fxs = L.fmap_of(xs)
-        dbs = D.DeviceBottleneck(I.bottleneck_params(8210 + stage, Cc, Cc, Cc, I.BF16, relu_out=True, s3_gain=0.25,
-                                                     group_width=gw))
-        des = D.DeviceGroupSE(gw, I.se_weights(8220 + stage, Cc, max(8, Cc // 4 // 4 * 4)))
-        wm = t.from_numpy(I.masker_weights(8230 + stage, Cc)).cuda()
-        npatch = N * (hw // Ss) ** 2
-        mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
-        ids = t.zeros(npatch, dtype=t.int32, device="cuda")
-        cn = t.zeros(1, dtype=t.int32, device="cuda")
-        lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
-        wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
-        wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
-        wsl = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, hw))
-        L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
-        t.cuda.synchronize()
-        lg = lgs.cpu().numpy()
-        xb = [xs.clone() for _ in range(4)]
-        cell = {"i": 0}
-
-        def restore():
-            xb[cell["i"] % 4].copy_(xs)
-        res = {}
-        for ratio in (0.0, 0.25, 0.5, 0.75, 1.0):
-            b2 = I.bias_for_ratio(lg, ratio)[0]
-
-            def blk(i):
-                cell["i"] = i + 1
-                L.laud_mask_gen(xb[i % 4], fxs, Ss, wm, b2, None, mk, ids, cn, None, None, wsm2)
-                L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, Ss, ids, cn, xb[i % 4], wsd)
-            cell["i"] = 0
-            res[f"r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, blk, iters=12, warm=2, prep=restore), 1)
-            if ratio == 0.5:
-                L.laud_stage_timing_enable(True)
-                for i in range(8):
-                    cell["i"] = i
-                    restore()
-                    blk(i)
-                t.cuda.synchronize()
-                res["stage_us_r050"] = {k: round(v[0] / v[1] * 1e3, 1) for k, v in L.laud_stage_timing_read().items()}
-                L.laud_stage_timing_enable(False)
-        keep = t.from_numpy(I.bernoulli_mask(8240 + stage, (N,), 0.5)).cuda()
-        wsc = D.workspace(L.workspace_size(B.OP_COMPACT, fxs, None, N))
-
-        def lskip(i):
-            L.laud_layer_skip_compact(keep, N, ids, cn, wsc)
-            L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, hw, ids, cn, xb[i % 4], wsl)
-        res["layer_skip_keep050_p50_us"] = round(_p50_us(t, lskip, iters=12, warm=2), 1)
-        ex[f"regnety800mf_stage{stage}_b128"] = res
-        del xb, xs, wsd, wsl
+    ex.update(measure_regnety(t, L, B, D, I))
     # configurations 3 and 5 of the benchmark list: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
     # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
     # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.
@@ -621,7 +629,10 @@ def main():
     if not a.no_extras:
         del bufs[12:]
         t.cuda.empty_cache()
-        extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm)
+        if a.extras_only == "regnety":
+            extras = measure_regnety(t, L, B, D, I)
+        else:
+            extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload --------
     cpu = None
