@@ -26,7 +26,8 @@ composition); the invariants ratio 1 == static block and ratio 0 == identity;
 the two-logit argmax == one-channel difference > 0 identity of App. B; the
 pool/1x1-conv commutation of App. B; the FLOP-ratio closed forms of Sec. 3.2;
 the group-convolution + SE block against torch's grouped conv2d / pooling composition (all
-active), a per-element brute force over every mask, and its reduction to dyn_bottleneck.
+active), a per-element brute force over every mask, and its reduction to dyn_bottleneck (the
+strided first-block form likewise: brute force, torch composition, reduction to dyn_projection_bottleneck).
 No function in this file is "parity unpinned".
 """
 from __future__ import annotations
@@ -446,3 +447,35 @@ def strided_mask_logits(x: np.ndarray, stride: int, S: int, w: np.ndarray, bias:
     patch grid of the OUTPUT (Ho/S x Wo/S); with H = stride*Ho that is a mean over windows of
     stride*S input pixels, followed by the one-channel 1x1 conv."""
     return mask_logits(x, stride * S, w, bias)
+
+
+def group_conv2d(h: np.ndarray, w: np.ndarray, g: int, stride: int) -> np.ndarray:
+    """3x3 group cross-correlation with zero padding 1 and a spatial stride, g channels per group:
+    out[n,yo,xo,o] = sum_{ky,kx,c<g} w[o,ky,kx,c] * hpad[n, yo*stride + ky, xo*stride + kx, (o//g)*g + c]."""
+    h = np.asarray(h, np.float64)
+    w = np.asarray(w, np.float64)
+    m = w.shape[0]
+    if m % g or h.shape[-1] != m or w.shape[-1] != g:
+        raise ValueError("group width must divide the channel count")
+    return np.concatenate([conv2d(h[..., k * g:(k + 1) * g], w[k * g:(k + 1) * g], stride, 1) for k in range(m // g)],
+                          axis=-1)
+
+
+def dyn_group_se_projection_bottleneck(x: np.ndarray, p: BottleneckParams, e: GroupSE, w_sc: np.ndarray,
+                                       s_sc: np.ndarray, t_sc: np.ndarray, stride: int, S: int,
+                                       mask_coarse: np.ndarray) -> np.ndarray:
+    """First block of a stage of the group-convolution / SE backbones (Sec. 4): as dyn_projection_bottleneck
+    (mask on the output grid, unselected locations keep the strided projection shortcut), with the stride on
+    the group 3x3 and the SE gate of se_scale taken over the sample's active OUTPUT pixels:
+        out = act(shortcut(x) + M_up * affine(1x1(h2 * gate))),  h2 = relu(affine(group3x3_stride(h1))).
+    With every location active this is the static first block."""
+    q = p.as_f64()
+    h1 = relu(affine(conv1x1(x, q.w1), q.s1, q.t1))
+    h2 = relu(affine(group_conv2d(h1, q.w2, e.g, stride), q.s2, q.t2))
+    m_up = upsample_mask(mask_coarse, S).astype(bool)
+    if e.w_se1 is not None:
+        h2 = h2 * se_scale(h2, m_up, e)[:, None, None, :]
+    f = affine(conv1x1(h2, q.w3), q.s3, q.t3)
+    sc = affine(conv2d(x, np.asarray(w_sc, np.float64)[:, None, None, :], stride, 0), s_sc, t_sc)
+    out = sc + m_up[..., None].astype(np.float64) * f
+    return relu(out) if q.relu_out else out

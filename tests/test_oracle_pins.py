@@ -760,3 +760,102 @@ def test_group_se_block_reductions_and_locality():
     x2 = np.where(dil[..., None], x, x + rng.standard_normal(x.shape))
     b = O.dyn_group_se_bottleneck(x2, p3, e3, S, mask)
     assert np.array_equal(a[up], b[up])
+
+
+def _bf_group_se_proj(x, p, e, wsc, ssc, tsc, stride, S, mask):
+    """Explicit loops: strided shortcut everywhere; at active output pixels the group 3x3 (stride on it) from
+    h1 with zero padding, the squeeze over exactly those pixels, gate, last 1x1."""
+    import math
+    xl, pl = np.asarray(x, np.float64).tolist(), _as_lists(p)
+    N, H, W, C = np.shape(x)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    m, g, co = len(pl["w1"]), e.g, len(pl["w3"])
+    out = np.zeros((N, Ho, Wo, co))
+    for n in range(N):
+        act = [(yo, xo) for yo in range(Ho) for xo in range(Wo) if mask[n][yo // S][xo // S]]
+        h2 = {}
+        for (yo, xo) in act:
+            row = []
+            for j in range(m):
+                acc = 0.0
+                for ky in range(3):
+                    for kx in range(3):
+                        for c in range(g):
+                            acc += pl["w2"][j][ky][kx][c] * _bf_h1(xl, pl, n, stride * yo + ky - 1, stride * xo + kx - 1,
+                                                                 (j // g) * g + c)
+                v = pl["s2"][j] * acc + pl["t2"][j]
+                row.append(v if v > 0.0 else 0.0)
+            h2[(yo, xo)] = row
+        gate = [1.0] * m
+        if act and e.w_se1 is not None:
+            z = [sum(h2[q][j] for q in act) / len(act) for j in range(m)]
+            w1, b1, w2, b2 = (np.asarray(a, np.float64).tolist() for a in (e.w_se1, e.b_se1, e.w_se2, e.b_se2))
+            hid = [max(sum(w1[k][j] * z[j] for j in range(m)) + b1[k], 0.0) for k in range(len(b1))]
+            gate = [1.0 / (1.0 + math.exp(-(sum(w2[j][k] * hid[k] for k in range(len(hid))) + b2[j]))) for j in range(m)]
+        for yo in range(Ho):
+            for xo in range(Wo):
+                for o in range(co):
+                    v = ssc[o] * sum(wsc[o][c] * xl[n][stride * yo][stride * xo][c] for c in range(C)) + tsc[o]
+                    if (yo, xo) in h2:
+                        f = sum(pl["w3"][o][j] * h2[(yo, xo)][j] * gate[j] for j in range(m))
+                        v += pl["s3"][o] * f + pl["t3"][o]
+                    out[n, yo, xo, o] = 0.0 if (p.relu_out and v < 0.0) else v
+    return out
+
+
+@pytest.mark.parametrize("stride,H,W,S,g,se_w", [(2, 4, 4, 1, 2, 3), (2, 4, 4, 2, 2, 0), (1, 2, 2, 1, 4, 2), (2, 5, 3, 1, 1, 2),
+                                                 (2, 8, 4, 2, 2, 3)])
+def test_group_se_projection_block_vs_bruteforce_all_masks(stride, H, W, S, g, se_w):
+    rng = np.random.default_rng(900 + 10 * H + S + stride)
+    N, c_in, m, c_out = 1, 3, 4, 5
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_out, True)
+    p.w2 = rng.standard_normal((m, 3, 3, g)) * 0.5
+    e = O.GroupSE(g, rng.standard_normal((se_w, m)), 0.3 * rng.standard_normal(se_w), rng.standard_normal((m, se_w)),
+                  0.3 * rng.standard_normal(m)) if se_w else O.GroupSE(g)
+    wsc, ssc, tsc = rng.standard_normal((c_out, c_in)), 1 + 0.3 * rng.standard_normal(c_out), rng.standard_normal(c_out)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    hp, wp = Ho // S, Wo // S
+    for bits in itertools.product([0, 1], repeat=hp * wp):
+        mask = np.array(bits, np.uint8).reshape(N, hp, wp)
+        got = O.dyn_group_se_projection_bottleneck(x, p, e, wsc, ssc, tsc, stride, S, mask)
+        want = _bf_group_se_proj(x, p, e, wsc.tolist(), ssc.tolist(), tsc.tolist(), stride, S, mask)
+        np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-11)
+
+
+def test_group_se_projection_block_special_cases():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(91)
+    N, H, W, c_in, m, c_out, g, se_w, stride, S = 2, 8, 12, 6, 8, 10, 4, 3, 2, 2
+    x = rng.standard_normal((N, H, W, c_in))
+    p = _rand_params(rng, c_in, m, c_out, True)
+    p.w2 = rng.standard_normal((m, 3, 3, g)) * 0.5
+    e = O.GroupSE(g, rng.standard_normal((se_w, m)), 0.3 * rng.standard_normal(se_w), rng.standard_normal((m, se_w)),
+                  0.3 * rng.standard_normal(m))
+    wsc, ssc, tsc = rng.standard_normal((c_out, c_in)), 1 + 0.2 * rng.standard_normal(c_out), rng.standard_normal(c_out)
+    Ho, Wo = H // stride, W // stride
+    ones = np.ones((N, Ho // S, Wo // S), np.uint8)
+    # every location active: the static strided block as a composition of library routines
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    aff = lambda z, s, b: z * t(s).view(1, -1, 1, 1) + t(b).view(1, -1, 1, 1)
+    xt = t(x).permute(0, 3, 1, 2)
+    h1 = F.relu(aff(F.conv2d(xt, t(p.w1)[:, :, None, None]), p.s1, p.t1))
+    h2 = F.relu(aff(F.conv2d(h1, t(p.w2).permute(0, 3, 1, 2), stride=stride, padding=1, groups=m // g), p.s2, p.t2))
+    gate = torch.sigmoid(F.conv2d(F.relu(F.conv2d(F.adaptive_avg_pool2d(h2, 1), t(e.w_se1)[:, :, None, None], t(e.b_se1))),
+                                  t(e.w_se2)[:, :, None, None], t(e.b_se2)))
+    sc = aff(F.conv2d(xt, t(wsc)[:, :, None, None], stride=stride), ssc, tsc)
+    want = F.relu(sc + aff(F.conv2d(h2 * gate, t(p.w3)[:, :, None, None]), p.s3, p.t3)).permute(0, 2, 3, 1).numpy()
+    np.testing.assert_allclose(O.dyn_group_se_projection_bottleneck(x, p, e, wsc, ssc, tsc, stride, S, ones), want,
+                               rtol=1e-11, atol=1e-11)
+    # one group as wide as the layer and no SE module: the plain dynamic first block
+    mk = (rng.random(ones.shape) < 0.5).astype(np.uint8)
+    pf = _rand_params(rng, c_in, m, c_out, True)
+    np.testing.assert_allclose(O.dyn_group_se_projection_bottleneck(x, pf, O.GroupSE(m), wsc, ssc, tsc, stride, S, mk),
+                               O.dyn_projection_bottleneck(x, pf, wsc, ssc, tsc, stride, S, mk), rtol=1e-12, atol=1e-12)
+    # stride 1: the group convolution with a stride reduces to the one without
+    hh = rng.standard_normal((N, H, W, m))
+    np.testing.assert_allclose(O.group_conv2d(hh, p.w2, g, 1), O.group_conv3x3(hh, p.w2, g), rtol=1e-12, atol=1e-12)
+    # nothing active: the activated shortcut alone
+    np.testing.assert_allclose(O.dyn_group_se_projection_bottleneck(x, p, e, wsc, ssc, tsc, stride, S, 0 * ones),
+                               F.relu(sc).permute(0, 2, 3, 1).numpy(), rtol=1e-11, atol=1e-11)
