@@ -263,6 +263,19 @@ int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottl
                                    int S, const int32_t* idx, const int32_t* count, void* out,
                                    void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * The same first block for the group-convolution / SE backbones (Sec. 4, RegNetY): the stride sits on the group
+ * 3x3 (w2 [c_mid][3][3][g]), and the SE gate (see laud_dyn_group_se_bottleneck) is taken over the sample's active
+ * OUTPUT pixels.  With every patch of the output grid in the index list this is the static first block of a
+ * stage.  Arguments, workspace (laud_dyn_projection_workspace) and errors as laud_dyn_projection_bottleneck and
+ * laud_dyn_group_se_bottleneck.
+ */
+int laud_dyn_group_se_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                            const laud_group_se* e, const void* w_sc, const float* s_sc,
+                                            const float* t_sc, int stride, int S, const int32_t* idx,
+                                            const int32_t* count, void* out, void* ws, size_t ws_bytes,
+                                            void* stream);
+
 
 /*
  * Channel masker (Sec. 3.2 "Masker design"; Fig. 3(b)): g = mean of x over H x W per sample and

@@ -22,7 +22,7 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
-           "laud_dyn_group_se_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+           "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
 STAGE_COUNT = 13
 
 
@@ -96,6 +96,9 @@ def load() -> C.CDLL:
     lib.laud_dyn_projection_bottleneck.restype = i32
     lib.laud_dyn_projection_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), vp, vp, vp, i32, i32, vp, vp, vp, vp,
                                                    sz, vp]
+    lib.laud_dyn_group_se_projection_bottleneck.restype = i32
+    lib.laud_dyn_group_se_projection_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), C.POINTER(GroupSE), vp, vp, vp,
+                                                            i32, i32, vp, vp, vp, vp, sz, vp]
     lib.laud_stem_workspace.restype = sz
     lib.laud_stem_workspace.argtypes = [i32, i32, i32, i32, i32]
     lib.laud_stem.restype = i32
@@ -255,6 +258,15 @@ def laud_dyn_projection_bottleneck(x, fx: Fmap, p: Bottleneck, w_sc, s_sc, t_sc,
     _check(load().laud_dyn_projection_bottleneck(_ptr(x), fx, C.byref(p), _ptr(w_sc), _ptr(s_sc), _ptr(t_sc),
                                                  int(stride), int(S), _ptr(idx), _ptr(count), _ptr(out), wp, wb,
                                                  _stream()), "laud_dyn_projection_bottleneck")
+
+
+def laud_dyn_group_se_projection_bottleneck(x, fx: Fmap, p: Bottleneck, e: GroupSE, w_sc, s_sc, t_sc, stride: int, S: int,
+                                            idx, count, out, ws) -> None:
+    wp, wb = _ws_args(ws)
+    _check(load().laud_dyn_group_se_projection_bottleneck(_ptr(x), fx, C.byref(p), C.byref(e) if e is not None else None,
+                                                          _ptr(w_sc), _ptr(s_sc), _ptr(t_sc), int(stride), int(S),
+                                                          _ptr(idx), _ptr(count), _ptr(out), wp, wb, _stream()),
+           "laud_dyn_group_se_projection_bottleneck")
 
 
 def stem_workspace(n: int, hin: int, win: int, c_out: int, dtype: int) -> int:

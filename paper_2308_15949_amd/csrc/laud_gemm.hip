@@ -1135,6 +1135,60 @@ extern "C" size_t laud_workspace_size(int op, laud_fmap fx, const laud_bottlenec
   }
 }
 
+// Checks the group-convolution / SE extension of a block; hw = pixels per sample of the map h1 lives on.
+static int validate_group_se(const laud_bottleneck* p, const laud_group_se* e, const laud_fmap& fx) {
+  if (e->group_width <= 0 || p->c_mid % e->group_width || e->se_width < 0) return LAUD_ERR_INVALID_ARG;
+  if (e->se_width > 0 && (!e->w_se1 || !e->b_se1 || !e->w_se2 || !e->b_se2)) return LAUD_ERR_INVALID_ARG;
+  // a 64-channel output tile must hold whole groups, and a group whole 16-byte chunks
+  const int g = e->group_width;
+  if (!(g == 8 || g == 16 || g == 32 || g == 64)) return LAUD_ERR_UNSUPPORTED;
+  if (e->se_width > kSeMaxHidden || (e->se_width > 0 && p->c_mid > kSeMaxC)) return LAUD_ERR_UNSUPPORTED;
+  // the SE module's means, gates and hidden units are kept in the scratch region of h1 (N*H*W*c_mid elements)
+  if (e->se_width > 0 && 4 * (2 * (size_t)p->c_mid + e->se_width) > (size_t)fx.H * fx.W * p->c_mid * elem_bytes(fx.dtype))
+    return LAUD_ERR_UNSUPPORTED;
+  return LAUD_OK;
+}
+
+// The 3x3 of a block on the active patches: `a` is set up for the plain convolution (w2 [c_mid][3][3][c_mid]);
+// with `e` it runs as a group convolution (w2 [c_mid][3][3][g]; 64-channel output tiles read their own 64 input
+// channels).
+static int launch_conv2(int dtype, GemmArgs a, const laud_group_se* e, long long cap_rows, hipStream_t st) {
+  if (!e) return launch_gemm<M_CONV2>(dtype, a, cap_rows, 1, st);
+  a.gw = e->group_width;
+  a.ldw = 9 * e->group_width;
+  StageScope scope(LAUD_STAGE_CONV2, st);
+  return dtype == LAUD_BF16 ? launch_gemm_t<M_G2, bf16_t, 64, 64, 2>(a, cap_rows, 1, st)
+                            : launch_gemm_t<M_G2, float, 64, 64, 2>(a, cap_rows, 1, st);
+}
+
+// The SE module on the compact rows h2 [rows][C] of the active patches (pps patches per sample, SS pixels per
+// patch, at most cap_rows rows).  `scratch` (float32: means [N][C], gates [N][C], hidden units [N][se_w]) must not
+// be in use: the callers pass the h1 region, which is dead once the 3x3 has run.
+static int launch_se(int dtype, int N, int pps, int SS, int C, const laud_group_se* e, void* h2, const int32_t* idx,
+                     const int32_t* count, float* scratch, long long cap_rows, hipStream_t st) {
+  StageScope scope(LAUD_STAGE_SE, st);
+  const int sw = e->se_width;
+  float* z = scratch;
+  float* gate = z + (size_t)N * C;
+  float* hid = gate + (size_t)N * C;
+  const int cpr = (int)(C * elem_bytes(dtype) / 16);
+  const dim3 sq((unsigned)((cpr + kSqChunks - 1) / kSqChunks), (unsigned)N);
+  const unsigned ngrp = (unsigned)((N + kFcSamples - 1) / kFcSamples);
+  const dim3 g1((unsigned)((sw + kFc1Tile - 1) / kFc1Tile), ngrp), g2((unsigned)((C + kFc2Tile - 1) / kFc2Tile), ngrp);
+  const unsigned sblocks = (unsigned)std::min<long long>((cap_rows * cpr + 1023) / 1024, 8192);
+  if (dtype == LAUD_BF16)
+    hipLaunchKernelGGL(k_se_squeeze<bf16_t>, sq, dim3(kSqThreads), 0, st, (const bf16_t*)h2, idx, count, pps, SS, C, z);
+  else
+    hipLaunchKernelGGL(k_se_squeeze<float>, sq, dim3(kSqThreads), 0, st, (const float*)h2, idx, count, pps, SS, C, z);
+  hipLaunchKernelGGL(k_se_fc1, g1, dim3(kFcThreads), 0, st, z, N, C, sw, e->w_se1, e->b_se1, hid);
+  hipLaunchKernelGGL(k_se_fc2, g2, dim3(kFcThreads), 0, st, hid, N, C, sw, e->w_se2, e->b_se2, gate);
+  if (dtype == LAUD_BF16)
+    hipLaunchKernelGGL(k_se_scale<bf16_t>, dim3(sblocks), dim3(256), 0, st, (bf16_t*)h2, idx, count, pps, SS, C, gate);
+  else
+    hipLaunchKernelGGL(k_se_scale<float>, dim3(sblocks), dim3(256), 0, st, (float*)h2, idx, count, pps, SS, C, gate);
+  return check_launch();
+}
+
 // The spatially adaptive block on an index list; `e` adds the group convolution / SE variant (or is null).
 static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, const laud_group_se* e, int S,
                          const int32_t* idx, const int32_t* count, void* out, void* ws, size_t ws_bytes,
@@ -1144,17 +1198,7 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   if (!idx || !count || S <= 0 || fx.H % S || fx.W % S) return LAUD_ERR_INVALID_ARG;
   const int Hp = fx.H / S, Wp = fx.W / S;
   if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
-  if (e) {
-    if (e->group_width <= 0 || p->c_mid % e->group_width || e->se_width < 0) return LAUD_ERR_INVALID_ARG;
-    if (e->se_width > 0 && (!e->w_se1 || !e->b_se1 || !e->w_se2 || !e->b_se2)) return LAUD_ERR_INVALID_ARG;
-    // a 64-channel output tile must hold whole groups, and a group whole 16-byte chunks
-    const int g = e->group_width;
-    if (!(g == 8 || g == 16 || g == 32 || g == 64)) return LAUD_ERR_UNSUPPORTED;
-    if (e->se_width > kSeMaxHidden || (e->se_width > 0 && p->c_mid > kSeMaxC)) return LAUD_ERR_UNSUPPORTED;
-    // the SE module's means, gates and hidden units are kept in the scratch region of h1 (N*H*W*c_mid elements)
-    if (e->se_width > 0 && 4 * (2 * (size_t)p->c_mid + e->se_width) > (size_t)fx.H * fx.W * p->c_mid * elem_bytes(fx.dtype))
-      return LAUD_ERR_UNSUPPORTED;
-  }
+  if (e && (rc = validate_group_se(p, e, fx)) != LAUD_OK) return rc;
   const DynWs L = dyn_ws_layout(fx, p->c_mid);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -1198,48 +1242,10 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
   a.lda = p->c_mid; a.ldo = p->c_mid;
-  if (!e) {
-    if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
-  } else {
-    // group convolution: w2 is [c_mid][3][3][g]; 64-channel output tiles read their own 64 input channels
-    a.gw = e->group_width;
-    a.ldw = 9 * e->group_width;
-    {
-      StageScope scope(LAUD_STAGE_CONV2, st);
-      rc = fx.dtype == LAUD_BF16 ? launch_gemm_t<M_G2, bf16_t, 64, 64, 2>(a, npix, 1, st)
-                                 : launch_gemm_t<M_G2, float, 64, 64, 2>(a, npix, 1, st);
-    }
-    if (rc != LAUD_OK) return rc;
-    if (e->se_width > 0) {
-      // h1 is dead from here on: the samples' channel means [N][C], gates [N][C] and hidden units [N][se_w]
-      // (float32) live there
-      StageScope scope(LAUD_STAGE_SE, st);
-      const int C = p->c_mid, sw = e->se_width;
-      float* z = (float*)h1;
-      float* gate = z + (size_t)fx.N * C;
-      float* hid = gate + (size_t)fx.N * C;
-      const int cpr = (int)(C * elem_bytes(fx.dtype) / 16);
-      const dim3 sq((unsigned)((cpr + kSqChunks - 1) / kSqChunks), (unsigned)fx.N);
-      const unsigned ngrp = (unsigned)((fx.N + kFcSamples - 1) / kFcSamples);
-      const dim3 g1((unsigned)((sw + kFc1Tile - 1) / kFc1Tile), ngrp), g2((unsigned)((C + kFc2Tile - 1) / kFc2Tile), ngrp);
-      const unsigned sblocks = (unsigned)std::min<long long>((npix * cpr + 1023) / 1024, 8192);
-      if (fx.dtype == LAUD_BF16)
-        hipLaunchKernelGGL(k_se_squeeze<bf16_t>, sq, dim3(kSqThreads), 0, st, (const bf16_t*)h2, idx, count, Hp * Wp,
-                           S * S, C, z);
-      else
-        hipLaunchKernelGGL(k_se_squeeze<float>, sq, dim3(kSqThreads), 0, st, (const float*)h2, idx, count, Hp * Wp,
-                           S * S, C, z);
-      hipLaunchKernelGGL(k_se_fc1, g1, dim3(kFcThreads), 0, st, z, fx.N, C, sw, e->w_se1, e->b_se1, hid);
-      hipLaunchKernelGGL(k_se_fc2, g2, dim3(kFcThreads), 0, st, hid, fx.N, C, sw, e->w_se2, e->b_se2, gate);
-      if (fx.dtype == LAUD_BF16)
-        hipLaunchKernelGGL(k_se_scale<bf16_t>, dim3(sblocks), dim3(256), 0, st, (bf16_t*)h2, idx, count, Hp * Wp, S * S,
-                           C, gate);
-      else
-        hipLaunchKernelGGL(k_se_scale<float>, dim3(sblocks), dim3(256), 0, st, (float*)h2, idx, count, Hp * Wp, S * S,
-                           C, gate);
-      if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
-    }
-  }
+  if ((rc = launch_conv2(fx.dtype, a, e, npix, st)) != LAUD_OK) return rc;
+  if (e && e->se_width > 0 &&
+      (rc = launch_se(fx.dtype, fx.N, Hp * Wp, S * S, p->c_mid, e, h2, idx, count, (float*)h1, npix, st)) != LAUD_OK)
+    return rc;
   // conv3: 1x1 on dense h2 with the scatter-add epilogue
   a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = x;
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
@@ -1484,10 +1490,11 @@ extern "C" size_t laud_dyn_projection_workspace(laud_fmap fx, const laud_bottlen
   return dyn_proj_ws_layout(fx, p->c_mid, stride).bytes;
 }
 
-extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
-                                              const void* w_sc, const float* s_sc, const float* t_sc, int stride,
-                                              int S, const int32_t* idx, const int32_t* count, void* out, void* ws,
-                                              size_t ws_bytes, void* stream) {
+// Dynamic first block of a stage; `e` adds the group convolution / SE variant (or is null).
+static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck* p, const laud_group_se* e,
+                              const void* w_sc, const float* s_sc, const float* t_sc, int stride, int S,
+                              const int32_t* idx, const int32_t* count, void* out, void* ws, size_t ws_bytes,
+                              void* stream) {
   if (!x || !out || !p || !w_sc || !s_sc || !t_sc || !idx || !count || !valid_fmap(fx) || x == out)
     return LAUD_ERR_INVALID_ARG;
   if (!p->w1 || !p->w2 || !p->w3 || !p->s1 || !p->t1 || !p->s2 || !p->t2 || !p->s3 || !p->t3)
@@ -1502,6 +1509,8 @@ extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const
   const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
   if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
   if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
+  int rc;
+  if (e && (rc = validate_group_se(p, e, fx)) != LAUD_OK) return rc;
   const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, stride);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -1511,7 +1520,6 @@ extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const
   int32_t* pix = (int32_t*)(wsb + L.pix);
   void* h1 = wsb + L.h1;
   void* h2 = wsb + L.h2;
-  int rc;
 
   GemmArgs a{};
   a.H = fx.H; a.W = fx.W; a.S = S; a.D = 1; a.G = 1; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
@@ -1542,12 +1550,31 @@ extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
   a.lda = p->c_mid; a.ldo = p->c_mid;
-  if ((rc = launch_gemm<M_CONV2>(fx.dtype, a, nout, 1, st)) != LAUD_OK) return rc;
+  if ((rc = launch_conv2(fx.dtype, a, e, nout, st)) != LAUD_OK) return rc;
+  if (e && e->se_width > 0 &&
+      (rc = launch_se(fx.dtype, fx.N, pps, S * S, p->c_mid, e, h2, idx, count, (float*)h1, nout, st)) != LAUD_OK)
+    return rc;
   // conv3 added onto the shortcut already in `out`, at the active output pixels
   a.A = h2; a.Wt = p->w3; a.scale = p->s3; a.shift = p->t3; a.Out = out; a.Res = out;
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
   a.relu = p->relu_out ? 1 : 0;
   return launch_gemm<M_CONV3>(fx.dtype, a, nout, 1, st);
+}
+
+extern "C" int laud_dyn_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                              const void* w_sc, const float* s_sc, const float* t_sc, int stride,
+                                              int S, const int32_t* idx, const int32_t* count, void* out, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  return run_dyn_projection(x, fx, p, nullptr, w_sc, s_sc, t_sc, stride, S, idx, count, out, ws, ws_bytes, stream);
+}
+
+extern "C" int laud_dyn_group_se_projection_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p,
+                                                       const laud_group_se* e, const void* w_sc, const float* s_sc,
+                                                       const float* t_sc, int stride, int S, const int32_t* idx,
+                                                       const int32_t* count, void* out, void* ws, size_t ws_bytes,
+                                                       void* stream) {
+  if (!e) return LAUD_ERR_INVALID_ARG;
+  return run_dyn_projection(x, fx, p, e, w_sc, s_sc, t_sc, stride, S, idx, count, out, ws, ws_bytes, stream);
 }
 
 extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p, const uint8_t* cmask,

@@ -135,3 +135,68 @@ def test_group_se_block_rejects_bad_arguments(G):
         L.laud_dyn_group_se_bottleneck(xd, fx, db.desc, bad, S, idx, cnt, xd, ws)
     assert ei.value.status == L.binding.ERR_INVALID_ARG
     t.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------
+# first block of a stage: stride on the group 3x3, projection shortcut, mask on the output grid
+# ------------------------------------------------------------------------------------------
+PROJ_CASES = [
+    # N, H, W, c_in, c_out (= mid), g, se_width, stride, S, dtype, mask kind
+    (2, 12, 8, 16, 32, 8, 4, 2, 1, I.F32, "bern"),
+    (2, 12, 8, 16, 32, 8, 0, 2, 2, I.F32, "bern"),            # group convolution only
+    (3, 9, 7, 40, 48, 16, 8, 2, 1, I.F32, "bern"),            # odd input size: Ho = 5, Wo = 4
+    (2, 16, 16, 32, 64, 16, 8, 2, 4, I.BF16, "ones"),         # every location active: the static first block
+    (2, 16, 16, 32, 64, 16, 8, 2, 4, I.BF16, "zeros"),
+    (2, 16, 16, 32, 64, 16, 8, 1, 2, I.BF16, "one_sample_empty"),
+    (2, 112, 112, 32, 64, 16, 8, 2, 4, I.BF16, "bern"),       # RegNetY-800MF: first block of stage 1
+    (2, 56, 56, 64, 144, 16, 16, 2, 4, I.BF16, "bern"),       # ... stage 2
+    (2, 28, 28, 144, 320, 16, 36, 2, 2, I.BF16, "bern"),      # ... stage 3
+    (3, 14, 14, 320, 784, 16, 80, 2, 1, I.BF16, "bern"),      # ... stage 4
+    (3, 14, 14, 320, 784, 16, 80, 2, 7, I.BF16, "bern"),      # ... as a layer gate (S = output size)
+    (2, 28, 28, 104, 208, 8, 26, 2, 2, I.BF16, "ones"),       # RegNetY-400MF stage 3 (group width 8, SE width 26)
+]
+
+
+@pytest.mark.parametrize("case", PROJ_CASES)
+def test_group_se_projection_block(G, case):
+    t, L, D = G.torch, G.L, G.D
+    N, H, W, ci, co, g, se_w, stride, S, dt, kind = case
+    x = I.feature_map(3300 + ci + S, N, H, W, ci, dt)
+    hb = I.bottleneck_params(3310 + ci, ci, co, co, dt, relu_out=True, s3_gain=0.5, group_width=g)
+    hb.t1 = (np.abs(hb.t1) + 0.25).astype(np.float32)   # positive conv1 shift: the 3x3's padding must be on h1
+    se = I.se_weights(3320 + ci, co, se_w) if se_w else None
+    gs = np.random.default_rng(3330 + ci)
+    wsc = I.round_to(gs.standard_normal((co, ci), dtype=np.float32) * np.float32(np.sqrt(2.0 / ci)), dt)
+    ssc = (0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)
+    tsc = (0.1 * gs.standard_normal(co)).astype(np.float32)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    shape = (N, Ho // S, Wo // S)
+    if kind == "bern":
+        mask = I.bernoulli_mask(3340 + S + H, shape, 0.5)
+    elif kind == "ones":
+        mask = np.ones(shape, np.uint8)
+    elif kind == "zeros":
+        mask = np.zeros(shape, np.uint8)
+    else:
+        mask = I.bernoulli_mask(3341, shape, 0.5)
+        mask[0] = 0
+    e = O.GroupSE(g, *se) if se is not None else O.GroupSE(g)
+    ref = O.dyn_group_se_projection_bottleneck(x, oracle_params(hb), e, wsc, ssc, tsc, stride, S, mask)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    de = D.DeviceGroupSE(g, se)
+    npatch = mask.size
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    L.laud_layer_skip_compact(t.from_numpy(np.ascontiguousarray(mask.reshape(-1))).cuda(), npatch, idx, cnt,
+                              D.workspace(L.workspace_size(L.binding.OP_COMPACT, fx, None, npatch)))
+    out = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+    ws = D.workspace(L.dyn_projection_workspace(fx, db.desc, stride))
+    ws.fill_(0xFF)  # NaN patterns: anything read before it is written shows up
+    print(f"group/SE projection case {case}", flush=True)
+    L.laud_dyn_group_se_projection_bottleneck(xd, fx, db.desc, de.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(),
+                                              t.from_numpy(tsc).cuda(), stride, S, idx, cnt, out, ws)
+    t.cuda.synchronize()
+    assert np.array_equal(D.to_host(xd), x)   # the input is left alone
+    assert_close(D.to_host(out), ref, TOL[dt], "group/SE first block")

@@ -145,6 +145,16 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert gs(vp(FAKE), fx, C.byref(pg), ge(16, -1), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG
     assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 8), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg - 1, st) == B.ERR_WORKSPACE
     assert gs(vp(FAKE), fx, C.byref(pg), ge(16, 8), 3, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), needg, st) == B.ERR_INVALID_ARG  # 3 does not divide 8
+    gp = lib.laud_dyn_group_se_projection_bottleneck
+    pq = _bn(64, 128, 128)
+    needq = lib.laud_dyn_projection_workspace(fx, C.byref(pq), 2)
+    far = vp(FAKE + (1 << 20))
+    assert gp(vp(FAKE), fx, C.byref(pq), None, vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
+    assert gp(vp(FAKE), fx, C.byref(pq), ge(24), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
+    assert gp(vp(FAKE), fx, C.byref(pq), ge(4), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_UNSUPPORTED
+    assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq - 1, st) == B.ERR_WORKSPACE
+    assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), vp(FAKE), vp(FAKE), vp(FAKE), 2, 3, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
+    assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), None, vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
     sm = lib.laud_stem
     nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
     assert nst >= 2 * 32 * 32 * (152 + 64) * 2
