@@ -125,6 +125,95 @@ def measure_regnety(t, L, B, D, I):
         res["layer_skip_keep050_p50_us"] = round(_p50_us(t, lskip, iters=12, warm=2), 1)
         ex[f"regnety800mf_stage{stage}_b128"] = res
         del xb, xs, wsd, wsl
+    # the whole RegNetY-800MF body without its stem (input: the stem's 112 x 112 x 32 output), batch 128, bf16,
+    # random-init weights: per stage a static first block (stride 2 on the group 3x3, projection shortcut: every
+    # output patch in the index list) and 0 / 2 / 7 / 1 dynamic identity blocks, either with spatial maskers
+    # (granularity 4-4-2-1, each bias calibrated to ratio 0.5 on the block's actual input) or with a seeded
+    # Bernoulli(0.6) keep gate per sample and block (layer skipping, S = H).  Every run starts from the input.
+    def regnety_body(N, keep_p):
+        cfg = I.REGNETY["800MF"]
+        gw = cfg["g"]
+        x0 = D.to_device(I.feature_map(8300, 8, 112, 112, 32, I.BF16, nonneg=True), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        cur, c_in, hw = x0, 32, 112
+        ops, held, act = [], [x0], []
+        wc = D.workspace(4096)
+        for stage, nblk in ((1, 1), (2, 3), (3, 8), (4, 2)):
+            co, hw = cfg["stages"][stage]["c"], hw // 2
+            Ss = I.STAGES[stage]["S"] if keep_p is None else hw
+            fin = L.fmap_of(cur)
+            dbp = D.DeviceBottleneck(I.bottleneck_params(8310 + 100 * stage, c_in, co, co, I.BF16, relu_out=True, s3_gain=0.5,
+                                                         group_width=gw))
+            dep = D.DeviceGroupSE(gw, I.se_weights(8311 + 100 * stage, co, max(8, c_in // 4)))
+            gs = np.random.default_rng(8312 + 100 * stage)
+            wsc = D.to_device(I.round_to(gs.standard_normal((co, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), I.BF16), I.BF16)
+            ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
+            tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
+            xs = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+            nall = N * (hw // 4) ** 2 if hw % 4 == 0 else N * hw * hw
+            Sf = 4 if hw % 4 == 0 else 1
+            all_idx = t.arange(nall, dtype=t.int32, device="cuda")
+            all_cnt = t.full((1,), nall, dtype=t.int32, device="cuda")
+            wsp = D.workspace(L.dyn_projection_workspace(fin, dbp.desc, 2))
+            op = (lambda cur=cur, fin=fin, dbp=dbp, dep=dep, wsc=wsc, ssc=ssc, tsc=tsc, Sf=Sf, all_idx=all_idx, all_cnt=all_cnt,
+                  xs=xs, wsp=wsp: L.laud_dyn_group_se_projection_bottleneck(cur, fin, dbp.desc, dep.desc, wsc, ssc, tsc, 2, Sf,
+                                                                            all_idx, all_cnt, xs, wsp))
+            op()
+            ops.append(op)
+            held += [dbp, dep, wsc, ssc, tsc, xs, all_idx, all_cnt, wsp]
+            fxs = L.fmap_of(xs)
+            npatch = N * (hw // Ss) ** 2
+            mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+            ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+            cn = t.zeros(1, dtype=t.int32, device="cuda")
+            lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+            wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+            wsd = None
+            for bidx in range(1, nblk):
+                dbs = D.DeviceBottleneck(I.bottleneck_params(8310 + 100 * stage + bidx, co, co, co, I.BF16, relu_out=True,
+                                                             s3_gain=0.25, group_width=gw))
+                des = D.DeviceGroupSE(gw, I.se_weights(8350 + 100 * stage + bidx, co, co // 4))
+                if wsd is None:
+                    wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+                if keep_p is None:
+                    wm = t.from_numpy(I.masker_weights(8360 + 100 * stage + bidx, co)).cuda()
+                    L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+                    t.cuda.synchronize()
+                    bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, des=des, Ss=Ss, wm=wm, bb=bb, mk=mk, ids=ids, cn=cn, wsm2=wsm2, wsd=wsd: (
+                          L.laud_mask_gen(xs, fxs, Ss, wm, bb, None, mk, ids, cn, None, None, wsm2),
+                          L.laud_dyn_group_se_bottleneck(xs, fxs, dbs.desc, des.desc, Ss, ids, cn, xs, wsd)))
+                    held.append(wm)
+                else:
+                    kp = t.from_numpy(I.bernoulli_mask(8370 + 100 * stage + bidx, (N,), keep_p)).cuda()
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, des=des, Ss=Ss, kp=kp, ids=ids, cn=cn, wsd=wsd: (
+                          L.laud_layer_skip_compact(kp, N, ids, cn, wc),
+                          L.laud_dyn_group_se_bottleneck(xs, fxs, dbs.desc, des.desc, Ss, ids, cn, xs, wsd)))
+                    held.append(kp)
+                op()
+                act.append(float(cn.item()) / npatch)
+                ops.append(op)
+                held += [dbs, des]
+            held += [mk, ids, cn, lgs, wsm2, wsd]
+            cur, c_in = xs, co
+        t.cuda.synchronize()
+
+        def body(i):
+            for op in ops:
+                op()
+        us = _p50_us(t, body, iters=5, warm=1)
+        L.laud_stage_timing_enable(True)
+        body(0)
+        t.cuda.synchronize()
+        st_body = L.laud_stage_timing_read()
+        L.laud_stage_timing_enable(False)
+        return {"p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0), "static_first_blocks": 4,
+                "dynamic_blocks": len(act), "mean_activation_ratio": round(float(np.mean(act)), 3),
+                "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()}}
+
+    ex["regnety800mf_body_b128_spatial_r050"] = regnety_body(128, None)
+    t.cuda.empty_cache()
+    ex["regnety800mf_body_b128_layer_skip_keep060"] = regnety_body(128, 0.6)
+    t.cuda.empty_cache()
     return ex
 
 
