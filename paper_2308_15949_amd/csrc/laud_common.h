@@ -107,6 +107,12 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
 int launch_dense_affine(int dtype, const void* A, const void* Wt, const float* scale, const float* shift, void* Out,
                         long long rows, int K, int ncols, int relu, hipStream_t stream);
 
+// The SE module on the compact rows h2 [rows][C] of the active patches (pps patches per sample, SS pixels per
+// patch, at most cap_rows rows); see laud_se.hip.  `scratch` holds N*(2*C + se_width) floats.
+constexpr int kSeMaxC = 4096, kSeMaxHidden = 1024;  // widest layer / SE hidden layer the kernels keep in LDS
+int launch_se(int dtype, int N, int pps, int SS, int C, const laud_group_se* e, void* h2, const int32_t* idx,
+              const int32_t* count, float* scratch, long long cap_rows, hipStream_t stream);
+
 // Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
 extern bool g_stage_timing_on;
 void stage_mark(int stage, hipStream_t stream, bool begin);
