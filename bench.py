@@ -107,6 +107,10 @@ def measure_regnety(t, L, B, D, I):
                 L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, Ss, ids, cn, xb[i % 4], wsd)
             cell["i"] = 0
             res[f"r{int(ratio * 100):03d}_p50_us"] = round(_p50_us(t, blk, iters=12, warm=2, prep=restore), 1)
+            pred = PRED.predict_block(PRED.MI355X, "spatial", n=N, hw_px=hw, c_in=Cc, m=Cc, S=Ss, r=ratio, fused_masker=False,
+                                      group_width=gw, se_width=Cc // 4)["total_s"]
+            # + the dilated-set kernel and the second launch of the index list (one per-kernel constant each)
+            res[f"r{int(ratio * 100):03d}_predicted_us"] = round((pred + 2 * PRED.MI355X.const_s) * 1e6, 1)
             if ratio == 0.5:
                 L.laud_stage_timing_enable(True)
                 for i in range(8):
@@ -123,6 +127,8 @@ def measure_regnety(t, L, B, D, I):
             L.laud_layer_skip_compact(keep, N, ids, cn, wsc)
             L.laud_dyn_group_se_bottleneck(xb[i % 4], fxs, dbs.desc, des.desc, hw, ids, cn, xb[i % 4], wsl)
         res["layer_skip_keep050_p50_us"] = round(_p50_us(t, lskip, iters=12, warm=2), 1)
+        res["predictor_mean_abs_rel_err"] = round(float(np.mean([
+            abs(res[f"r{q:03d}_predicted_us"] - res[f"r{q:03d}_p50_us"]) / res[f"r{q:03d}_p50_us"] for q in (0, 25, 50, 75, 100)])), 3)
         ex[f"regnety800mf_stage{stage}_b128"] = res
         del xb, xs, wsd, wsl
     # the whole RegNetY-800MF body without its stem (input: the stem's 112 x 112 x 32 output), batch 128, bf16,

@@ -118,13 +118,17 @@ def expected_dilated_ratio(r: float, S: int) -> float:
 
 def predict_block(hw: Hardware, paradigm: str, *, n: int, hw_px: int, c_in: int, m: int, dtype: str = "bf16",
                   S: int = 1, r: float = 1.0, r_dil: float | None = None, fused_masker: bool = True,
-                  with_masker: bool = True) -> dict:
+                  with_masker: bool = True, group_width: int | None = None, se_width: int = 0) -> dict:
     """Latency of one identity bottleneck (c_in -> m -> m -> c_in) on a batch of n feature maps of
     hw_px x hw_px pixels: l = G(H, P, D, S, r) of Sec. 3.3.
 
     paradigm "spatial": activation ratio r over S x S patches (r_dil: ratio of the dilated set, default
     the Bernoulli expectation); "channel": r is the kept fraction of the m mid channels; "layer": r is
     the kept fraction of samples (S = feature size); "static": the plain block.
+    group_width g turns the 3x3 into a group convolution (spatial / layer / static paradigms): FLOPs count the g
+    input channels a kernel really reads; the time is that of the 64-channel window the kernel multiplies.
+    se_width adds the SE module between the 3x3 and the last 1x1: four small kernels that stream the active
+    rows (read for the mean, read and written for the gate) and the two fully connected layers.
     Returns {"kernels": [KernelPrediction...], "total_s": ..., "flops": ...}."""
     eb = 2 if dtype == "bf16" else 4
     npix = n * hw_px * hw_px
@@ -149,7 +153,21 @@ def predict_block(hw: Hardware, paradigm: str, *, n: int, hw_px: int, c_in: int,
             rows1 = int(round(r_dil * npix))
             ks.append(_gemm(hw, "conv1 (dilated active set)", rows1, m, c_in, 1, eb, dtype, float(rows1 * c_in * eb), False))
         rows = int(round(r * npix))
-        ks.append(_gemm(hw, "conv2 (active patches)", rows, m, m, 9, eb, dtype, float(min(r_dil, 1.0) * npix * m * eb), False))
+        if group_width is None:
+            ks.append(_gemm(hw, "conv2 (active patches)", rows, m, m, 9, eb, dtype, float(min(r_dil, 1.0) * npix * m * eb), False))
+        else:
+            # one 64-channel output tile reduces over its own 64 input channels: the executed reduction length
+            kwin = min(64, m)
+            k2 = _gemm(hw, "group conv2 (active patches)", rows, m, kwin, 9, eb, dtype, float(min(r_dil, 1.0) * npix * m * eb),
+                       False, tile=(64, 64))
+            k2.flops = 2.0 * rows * m * group_width * 9
+            ks.append(k2)
+        if se_width > 0:
+            ks.append(_stream(hw, "SE squeeze", float(rows * m * eb)))
+            fc = KernelPrediction("SE fc1", (0, 0), 0, 0, 2.0 * n * m * se_width, 4.0 * m * se_width, 0.0, 0.0, 0.0, hw.const_s)
+            ks.append(fc)
+            ks.append(KernelPrediction("SE fc2", (0, 0), 0, 0, 2.0 * n * m * se_width, 4.0 * m * se_width, 0.0, 0.0, 0.0, hw.const_s))
+            ks.append(_stream(hw, "SE gate", float(2 * rows * m * eb)))
         ks.append(_gemm(hw, "conv3 + scatter-add", rows, c_in, m, 1, eb, dtype, float(rows * m * eb), True))
     elif paradigm == "channel":
         mk = max(int(round(r * m)), 0)

@@ -73,3 +73,21 @@ def test_hardware_table_of_the_paper():
         assert hw.n_pe * hw.pe_flops("f32") == pytest.approx(int(pe) * int(fp32) * 2 * float(mhz) * 1e6)
     v100 = P.paper_device("V100", 80, 64, 1500, 700)
     assert v100.n_pe * v100.pe_flops("f32") == pytest.approx(15.36e12)   # the V100's 15.4 TFLOP/s FP32
+
+
+def test_group_convolution_and_se_in_the_prediction():
+    kw = dict(n=128, hw_px=14, c_in=320, m=320, S=2, r=0.5, fused_masker=False)
+    plain = P.predict_block(P.MI355X, "spatial", **kw)
+    grp = P.predict_block(P.MI355X, "spatial", group_width=16, **kw)
+    se = P.predict_block(P.MI355X, "spatial", group_width=16, se_width=80, **kw)
+    # FLOPs of the 3x3 shrink by m / g; the two 1x1 convs are untouched
+    f = lambda p_, name: sum(k.flops for k in p_["kernels"] if name in k.name)
+    assert f(grp, "conv2") == pytest.approx(f(plain, "conv2") * 16 / 320)
+    assert f(grp, "conv1") == f(plain, "conv1") and f(grp, "conv3") == f(plain, "conv3")
+    # the group convolution is never slower than the full one; the SE module adds four kernels and their constants
+    assert grp["total_s"] <= plain["total_s"]
+    assert len(se["kernels"]) == len(grp["kernels"]) + 4
+    assert se["total_s"] >= grp["total_s"] + 4 * P.MI355X.const_s
+    # the 3x3's share of FLOPs as the oracle counts them for one group
+    rows = 0.5 * 128 * 14 * 14
+    assert f(grp, "conv2") == pytest.approx(2.0 * rows * 9 * 16 * 320, rel=1e-3)
