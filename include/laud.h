@@ -169,7 +169,7 @@ typedef struct {
  *   computed; with every patch active, and for layer skipping with S == H == W, this is the ordinary
  *   global average),
  *   out = act(x + s3*conv1x1(h2 * gate[n]; w3) + t3) on active pixels.
- * h2 * gate is rounded to dtype before the last 1x1 (c_mid <= 4096 when se_width > 0).  Workspace:
+ * h2 * gate is rounded to dtype before the last 1x1 (c_mid <= 4096 and N <= 65535 when se_width > 0).  Workspace:
  * laud_workspace_size(LAUD_OP_DYN_BOTTLENECK, ...).  Errors as laud_dyn_bottleneck; a group width other
  * than 8/16/32/64 returns LAUD_ERR_UNSUPPORTED, a null `e` or one that does not divide c_mid
  * LAUD_ERR_INVALID_ARG.

@@ -914,6 +914,7 @@ static int validate_group_se(const laud_bottleneck* p, const laud_group_se* e, c
   const int g = e->group_width;
   if (!(g == 8 || g == 16 || g == 32 || g == 64)) return LAUD_ERR_UNSUPPORTED;
   if (e->se_width > kSeMaxHidden || (e->se_width > 0 && p->c_mid > kSeMaxC)) return LAUD_ERR_UNSUPPORTED;
+  if (e->se_width > 0 && fx.N > 65535) return LAUD_ERR_UNSUPPORTED;  // one grid row of the squeeze per sample
   // the SE module's means, gates and hidden units are kept in the scratch region of h1 (N*H*W*c_mid elements)
   if (e->se_width > 0 && 4 * (2 * (size_t)p->c_mid + e->se_width) > (size_t)fx.H * fx.W * p->c_mid * elem_bytes(fx.dtype))
     return LAUD_ERR_UNSUPPORTED;

@@ -200,3 +200,22 @@ def test_group_se_projection_block(G, case):
     t.cuda.synchronize()
     assert np.array_equal(D.to_host(xd), x)   # the input is left alone
     assert_close(D.to_host(out), ref, TOL[dt], "group/SE first block")
+
+
+@pytest.mark.parametrize("stage", [1, 3, 4])
+def test_group_se_block_full_batch_sampled(G, stage):
+    """The bench shapes (RegNetY-800MF stage blocks, batch 128, bf16, masker-calibrated ratio 0.5 replaced by a
+    seeded Bernoulli mask): the whole batch runs on the GPU, the oracle checks a few samples (samples are
+    independent: mask, squeeze and gate are per sample)."""
+    cfg = I.REGNETY["800MF"]
+    N, C, hw, g, S = 128, cfg["stages"][stage]["c"], cfg["stages"][stage]["hw"], cfg["g"], I.STAGES[stage]["S"]
+    x8 = I.feature_map(3400 + stage, 8, hw, hw, C, I.BF16)
+    x = np.concatenate([x8] * (N // 8), axis=0)
+    hb = I.bottleneck_params(3410 + stage, C, C, C, I.BF16, True, s3_gain=0.25, group_width=g)
+    se = I.se_weights(3420 + stage, C, C // 4)
+    mask = I.bernoulli_mask(3430 + stage, (N, hw // S, hw // S), 0.5)
+    mask[5] = 0      # a sample without active patches in the middle of the batch
+    mask[6] = 1
+    got = run_group_se(G, x, hb, g, se, S, mask, True)
+    for n in (0, 5, 6, 37, 127):
+        check_group_se(got[n:n + 1], x[n:n + 1], hb, g, se, S, mask[n:n + 1])
