@@ -1,6 +1,6 @@
 """GPU parity of the static parts of the ResNet body (stem, projection blocks) and of a reduced
 body run (the whole-body workload in miniature: stem, then per stage one static first block followed by
-dynamic identity blocks), block by block against the CPU oracle fed with each block's actual input."""
+dynamic identity blocks), block by block against the CPU oracle's own run of the same body from the same image."""
 import numpy as np
 import pytest
 
@@ -145,37 +145,50 @@ def test_dyn_projection_block(case):
         assert np.array_equal(D.to_host(out0)[~up], got[~up])
 
 
-def test_reduced_body_block_by_block():
+@pytest.mark.parametrize("dt", [I.F32, I.BF16])
+def test_reduced_body_block_by_block(dt):
     """64x64 images, stem to 16x16x64, then stages 1-3 with widths 64/128/256 (x4), granularity 4-4-2: one
-    static first block and two dynamic identity blocks per stage, masks from each block's masker at ratio 0.5."""
+    static first block and two dynamic identity blocks per stage, masks from each block's masker at ratio 0.5.
+    The oracle runs the same body on its own from the image (float64, nothing rounded, nothing from the GPU) and
+    the GPU is compared with it after every block.  float32: the per-operation tolerance holds along the whole
+    chain.  bf16: every block stores its output rounded to bf16 and hands that on, the residual path carries the
+    difference forward with gain one, so after k operations the difference to an unrounded chain is bounded by
+    k times the per-operation tolerance (the per-operation parity itself is what the other tests check, on
+    seeded inputs)."""
     import torch as t
     import paper_2308_15949_amd as L
     from paper_2308_15949_amd import device as D
-    dt, N = I.BF16, 4
+    N = 4
+    nops = [0]
+
+    def chain_tol():
+        nops[0] += 1
+        return TOL[dt] * (nops[0] if dt == I.BF16 else 1)
     g = np.random.default_rng(620)
     img = I.round_to(g.standard_normal((N, 64, 64, 3), dtype=np.float32), dt)
     w7 = I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), dt)
     s7, t7 = (1 + 0.1 * g.standard_normal(64)).astype(np.float32), (0.1 * g.standard_normal(64)).astype(np.float32)
-    xd = t.empty((N, 16, 16, 64), dtype=t.bfloat16, device="cuda")
+    xd = t.empty((N, 16, 16, 64), dtype=t.bfloat16 if dt == I.BF16 else t.float32, device="cuda")
     L.laud_stem(D.to_device(img, dt), N, 64, 64, dt, D.to_device(w7, dt), t.from_numpy(s7).cuda(), t.from_numpy(t7).cuda(),
                 64, xd, D.workspace(L.stem_workspace(N, 64, 64, 64, dt)))
     t.cuda.synchronize()
-    close(D.to_host(xd), O.stem(img, w7, s7, t7), TOL[dt])
+    x_ref = O.stem(img, w7, s7, t7)   # the oracle's own chain: float64, nothing rounded, nothing from the GPU
+    close(D.to_host(xd), x_ref, chain_tol())
     c_in, hw = 64, 16
     for stage, (m, S, stride) in enumerate(((64, 4, 1), (128, 4, 2), (256, 2, 2)), start=1):
         co = 4 * m
         # static first block
-        x_in = D.to_host(xd)
         hb = I.bottleneck_params(630 + stage, c_in, m, co, dt, relu_out=True, s3_gain=0.5)
         wsc, ssc, tsc = shortcut_params(640 + stage, c_in, co, dt)
         fx = L.fmap_of(xd)
         db = D.DeviceBottleneck(hb)
         hw = (hw - 1) // stride + 1
-        out = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+        out = t.empty((N, hw, hw, co), dtype=xd.dtype, device="cuda")
         L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, dt), t.from_numpy(ssc).cuda(), t.from_numpy(tsc).cuda(),
                                  stride, out, D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride)))
         t.cuda.synchronize()
-        close(D.to_host(out), O.projection_bottleneck(x_in, oparams(hb), wsc, ssc, tsc, stride), TOL[dt])
+        x_ref = O.projection_bottleneck(x_ref, oparams(hb), wsc, ssc, tsc, stride)
+        close(D.to_host(out), x_ref, chain_tol())
         xd, c_in = out, co
         fx = L.fmap_of(xd)
         npatch = N * (hw // S) ** 2
@@ -183,19 +196,21 @@ def test_reduced_body_block_by_block():
         idx = t.zeros(npatch, dtype=t.int32, device="cuda")
         cnt = t.zeros(1, dtype=t.int32, device="cuda")
         for blk in range(2):
-            x_in = D.to_host(xd)
+            gpu_in = D.to_host(xd)
             hb = I.bottleneck_params(650 + 10 * stage + blk, co, m, co, dt, relu_out=True, s3_gain=0.25)
             w = I.masker_weights(660 + 10 * stage + blk, co)
-            ref0 = O.mask_logits(x_in, S, w, 0.0)
-            bias, _ = I.bias_for_ratio(ref0, 0.5)
+            ref0 = O.mask_logits(x_ref, S, w, 0.0)
+            bias, half_gap = I.bias_for_ratio(ref0, 0.5)
+            ref_mask = O.threshold(ref0 + bias)
+            # the GPU's features carry the storage rounding of the blocks before: the threshold sits in a wide gap
+            assert half_gap > 1e-3 * float(np.sqrt(np.mean(ref0 * ref0)))
             db = D.DeviceBottleneck(hb)
             L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None,
                                          None, xd, D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S)))
             t.cuda.synchronize()
-            gm = mask.cpu().numpy().reshape(N, hw // S, hw // S)
-            assert np.array_equal(gm, O.threshold(ref0 + bias))
+            assert np.array_equal(mask.cpu().numpy().reshape(N, hw // S, hw // S), ref_mask)
             got = D.to_host(xd)
-            ref = O.dyn_bottleneck(x_in, oparams(hb), S, gm)
-            up = O.upsample_mask(gm, S).astype(bool)
-            assert np.array_equal(got[~up], x_in[~up])
-            close(got[up], ref[up], TOL[dt])
+            x_ref = O.dyn_bottleneck(x_ref, oparams(hb), S, ref_mask)
+            up = O.upsample_mask(ref_mask, S).astype(bool)
+            assert np.array_equal(got[~up], gpu_in[~up])   # inactive pixels: bit for bit what the GPU held before
+            close(got, x_ref, chain_tol())

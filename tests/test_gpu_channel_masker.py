@@ -68,7 +68,12 @@ def test_channel_masker_feeds_channel_skip_conv():
     t.cuda.synchronize()
     gm = cmask.cpu().numpy()
     p = O.BottleneckParams(hb.w1, hb.w2, hb.w3, hb.s1, hb.t1, hb.s2, hb.t2, hb.s3, hb.t3, hb.relu_out)
-    ref = O.channel_skip_bottleneck(x, p, gm)   # teacher-forced with the GPU's decisions
+    lr = O.channel_masker_logits(x, wa, ba, wb, bb)
+    ref_mask = O.channel_mask_from_logits(lr)
+    # no decision of this seeded case lies within float32 rounding of a tie, so the GPU's mask is the oracle's
+    assert (np.abs(lr[..., 0] - lr[..., 1]) > 1e-4 * float(np.sqrt(np.mean(lr * lr)))).all()
+    assert np.array_equal(gm, ref_mask)
+    ref = O.channel_skip_bottleneck(x, p, ref_mask)
     got = D_.to_host(xd).astype(np.float64)
     rms = float(np.sqrt(np.mean(ref * ref)))
     assert np.all(np.abs(got - ref) <= 2e-2 * (np.abs(ref) + rms))

@@ -122,18 +122,17 @@ def test_mask_gen(G, case, use_keep):
     scale = float(np.sqrt(np.mean(ref0 * ref0))) + abs(bias)
     assert np.abs(got_logits - ref_logits).max() <= 2e-5 * scale + 1e-6
     got_mask = mask.cpu().numpy().reshape(N, hp, wp)
-    # decisions may differ only where the oracle's logit is within rounding of the threshold;
-    # the bias sits in the middle of a gap, so none should
+    # decisions could differ only where the oracle's logit is within rounding of the threshold; the bias
+    # sits in the middle of a gap wider than that, so none does and everything downstream is the oracle's
     eps = 2e-5 * scale + 1e-6
-    sure = np.abs(ref_logits) > eps
-    assert np.array_equal(got_mask[sure], ref_mask[sure])
-    assert half_gap <= eps or sure.all()
-    # index generation is bit-exact given the mask the GPU produced
+    assert half_gap > eps and (np.abs(ref_logits) > eps).all()
+    assert np.array_equal(got_mask, ref_mask)
+    # index generation: bit-exact
     c = int(cnt.item())
-    assert c == int(got_mask.sum())
-    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(got_mask))
+    assert c == int(ref_mask.sum())
+    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(ref_mask))
     assert np.all(idx.cpu().numpy()[c:] == -7)
-    assert np.array_equal(so.cpu().numpy(), O.sample_offsets(got_mask))
+    assert np.array_equal(so.cpu().numpy(), O.sample_offsets(ref_mask))
     assert set(np.unique(got_mask)) <= {0, 1}
 
 
@@ -401,11 +400,10 @@ def test_config2_full_size_sampled(G, r, fused):
     wsm = D.workspace(L.workspace_size(L.binding.OP_MASK_GEN, fx, None, S))
     wd = t.from_numpy(w).cuda()
     sample = [0, 1, 63, 127]
-    ref0 = O.mask_logits(x[sample], S, w, 0.0)
-    # bias from the GPU's own logits of the whole batch (as the benchmark does), then both sides use it
-    L.laud_mask_gen(xd, fx, S, wd, 0.0, None, mask, idx, cnt, None, lg, wsm)
-    t.cuda.synchronize()
-    bias, _ = I.bias_for_ratio(lg.cpu().numpy(), r)
+    # bias from the oracle's logits of the whole batch (the pooled 1x1 is cheap on the CPU), in the middle of a gap
+    ref0 = O.mask_logits(x, S, w, 0.0)
+    bias, half_gap = I.bias_for_ratio(ref0, r)
+    ref_mask = O.threshold(ref0 + bias)
     ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
     if fused:
         mask.zero_(); idx.zero_(); cnt.zero_()
@@ -416,13 +414,13 @@ def test_config2_full_size_sampled(G, r, fused):
     t.cuda.synchronize()
     got_mask = mask.cpu().numpy().reshape(N, H // S, H // S)
     assert abs(int(cnt.item()) - round(r * npatch)) <= 16
-    assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(got_mask))
-    ref_logits = ref0 + bias
-    sure = np.abs(ref_logits) > 1e-4
-    assert np.array_equal(got_mask[sample][sure], O.threshold(ref_logits)[sure])
+    scale = float(np.sqrt(np.mean(ref0 * ref0))) + abs(bias)
+    assert r >= 1.0 or half_gap > 2e-5 * scale + 1e-6   # no decision within float32 rounding of the threshold
+    assert np.array_equal(got_mask, ref_mask)
+    assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(ref_mask))
     got = D.to_host(xd[sample])
-    ref = O.dyn_bottleneck(x[sample], oracle_params(hb), S, got_mask[sample])  # teacher-forced mask
-    up = O.upsample_mask(got_mask[sample], S).astype(bool)
+    ref = O.dyn_bottleneck(x[sample], oracle_params(hb), S, ref_mask[sample])
+    up = O.upsample_mask(ref_mask[sample], S).astype(bool)
     assert np.array_equal(got[~up], x[sample][~up])
     assert_close(got[up], ref[up], TOL[dt], "config 2 sampled images")
 
@@ -479,16 +477,16 @@ def test_masker_dyn_bottleneck(G, case, inplace, use_keep):
     got_logits = lg.cpu().numpy().reshape(N, hp, wp)
     assert np.abs(got_logits - (ref0 + bias)).max() <= eps
     got_mask = mask.cpu().numpy().reshape(N, hp, wp)
-    sure = np.abs(ref0 + bias) > eps
-    assert np.array_equal(got_mask[sure], ref_mask[sure])
+    assert (np.abs(ref0 + bias) > eps).all()   # the bias sits in a gap: no decision within rounding of the threshold
+    assert np.array_equal(got_mask, ref_mask)
     c = int(cnt.item())
-    assert c == int(got_mask.sum())
-    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(got_mask))
+    assert c == int(ref_mask.sum())
+    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(ref_mask))
     assert np.all(idx.cpu().numpy()[c:] == -7)
-    assert np.array_equal(so.cpu().numpy(), O.sample_offsets(got_mask))
+    assert np.array_equal(so.cpu().numpy(), O.sample_offsets(ref_mask))
     got = D.to_host(out)
-    ref = O.dyn_bottleneck(x, oracle_params(hb), S, got_mask)
-    up = O.upsample_mask(got_mask, S).astype(bool)
+    ref = O.dyn_bottleneck(x, oracle_params(hb), S, ref_mask)
+    up = O.upsample_mask(ref_mask, S).astype(bool)
     assert np.array_equal(got[~up], x[~up])
     assert_close(got[up], ref[up], TOL[dt], "fused masker block")
 
@@ -595,8 +593,9 @@ def test_config5_layer_gate_and_spatial_full_size_sampled(G):
 
 def test_chain_of_dynamic_blocks_in_place(G):
     """Three consecutive stage-3 identity blocks (each with its own masker and weights) applied in place,
-    as in the body of the network; every block is checked against the oracle fed with the block's actual
-    input (per-block parity; end-to-end bf16 drift is not gated)."""
+    as in the body of the network.  The oracle runs its own chain from the same seeded input (float64, nothing
+    rounded, nothing taken from the GPU); after every block the GPU's mask must be the oracle's and its
+    features within the bf16 tolerance of the oracle's (the storage rounding of three blocks stays far inside it)."""
     t, L, D = G.torch, G.L, G.D
     sg = I.STAGES[3]
     N, H, C, m, S, dt = 8, sg["hw"], sg["c_in"], sg["m"], sg["S"], I.BF16
@@ -607,24 +606,28 @@ def test_chain_of_dynamic_blocks_in_place(G):
     mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
     idx = t.zeros(npatch, dtype=t.int32, device="cuda")
     cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    x_ref = np.asarray(x, np.float64)   # the oracle's own chain
     for blk in range(3):
         hb = I.bottleneck_params(I.seed_for(3, 0, blk + 1), C, m, C, dt, relu_out=True, s3_gain=0.25)
         w = I.masker_weights(I.seed_for(3, 5, blk + 1), C)
         db = D.DeviceBottleneck(hb)
-        x_in = D.to_host(xd)
-        ref0 = O.mask_logits(x_in, S, w, 0.0)
-        bias, _ = I.bias_for_ratio(ref0, 0.5)
+        gpu_in = D.to_host(xd)
+        ref0 = O.mask_logits(x_ref, S, w, 0.0)
+        bias, half_gap = I.bias_for_ratio(ref0, 0.5)
+        ref_mask = O.threshold(ref0 + bias)
+        # the GPU's logits come from features that carry the rounding of the earlier blocks: the threshold has
+        # to sit in a gap much wider than that
+        assert half_gap > 1e-3 * float(np.sqrt(np.mean(ref0 * ref0)))
         ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
         L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None,
                                      None, xd, ws)
         t.cuda.synchronize()
-        got_mask = mask.cpu().numpy().reshape(N, 7, 7)
-        assert np.array_equal(got_mask, O.threshold(ref0 + bias))
+        assert np.array_equal(mask.cpu().numpy().reshape(N, 7, 7), ref_mask)
         got = D.to_host(xd)
-        ref = O.dyn_bottleneck(x_in, oracle_params(hb), S, got_mask)
-        up = O.upsample_mask(got_mask, S).astype(bool)
-        assert np.array_equal(got[~up], x_in[~up])
-        assert_close(got[up], ref[up], TOL[dt], f"block {blk}")
+        x_ref = O.dyn_bottleneck(x_ref, oracle_params(hb), S, ref_mask)
+        up = O.upsample_mask(ref_mask, S).astype(bool)
+        assert np.array_equal(got[~up], gpu_in[~up])   # inactive pixels: bit for bit what the GPU held before
+        assert_close(got, x_ref, TOL[dt], f"after block {blk}")
         assert got.min() >= 0.0
 
 
