@@ -479,3 +479,9 @@ def dyn_group_se_projection_bottleneck(x: np.ndarray, p: BottleneckParams, e: Gr
     sc = affine(conv2d(x, np.asarray(w_sc, np.float64)[:, None, None, :], stride, 0), s_sc, t_sc)
     out = sc + m_up[..., None].astype(np.float64) * f
     return relu(out) if q.relu_out else out
+
+
+def stem3x3(x: np.ndarray, w3: np.ndarray, s: np.ndarray, t: np.ndarray) -> np.ndarray:
+    """Stem of the RegNet backbones (Sec. 4): 3x3 stride-2 pad-1 conv from the image, affine (folded BN), ReLU;
+    no pooling.  x [N,H,W,3], w3 [c_out,3,3,3] -> [N, (H-1)//2+1, (W-1)//2+1, c_out]."""
+    return relu(affine(conv2d(x, w3, 2, 1), s, t))

@@ -859,3 +859,19 @@ def test_group_se_projection_block_special_cases():
     # nothing active: the activated shortcut alone
     np.testing.assert_allclose(O.dyn_group_se_projection_bottleneck(x, p, e, wsc, ssc, tsc, stride, S, 0 * ones),
                                F.relu(sc).permute(0, 2, 3, 1).numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_stem3x3_vs_torch_and_hand_case():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(95)
+    for (H, W) in ((8, 8), (9, 7)):
+        x = rng.standard_normal((2, H, W, 3))
+        w = rng.standard_normal((5, 3, 3, 3))
+        s, b = 1 + 0.2 * rng.standard_normal(5), rng.standard_normal(5)
+        y = F.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(w).permute(0, 3, 1, 2), stride=2, padding=1)
+        want = F.relu(y * torch.from_numpy(s).view(1, -1, 1, 1) + torch.from_numpy(b).view(1, -1, 1, 1)).permute(0, 2, 3, 1)
+        np.testing.assert_allclose(O.stem3x3(x, w, s, b), want.numpy(), rtol=1e-12, atol=1e-12)
+    # an all-ones 4x4 image under an all-ones kernel: the corner window holds 2x2 pixels, the others 3x2 / 2x3 / 3x3
+    one = O.stem3x3(np.ones((1, 4, 4, 3)), np.ones((1, 3, 3, 3)), np.ones(1), np.zeros(1))[0, :, :, 0]
+    assert np.array_equal(one, 3.0 * np.array([[4, 6], [6, 9]]))
