@@ -131,17 +131,25 @@ def measure_regnety(t, L, B, D, I):
             abs(res[f"r{q:03d}_predicted_us"] - res[f"r{q:03d}_p50_us"]) / res[f"r{q:03d}_p50_us"] for q in (0, 25, 50, 75, 100)])), 3)
         ex[f"regnety800mf_stage{stage}_b128"] = res
         del xb, xs, wsd, wsl
-    # the whole RegNetY-800MF body without its stem (input: the stem's 112 x 112 x 32 output), batch 128, bf16,
-    # random-init weights: per stage a static first block (stride 2 on the group 3x3, projection shortcut: every
+    # the whole RegNetY-800MF body from the 224 x 224 image, batch 128, bf16, random-init weights: the stem (3x3
+    # stride-2 conv to 32 channels), then per stage a static first block (stride 2 on the group 3x3, projection shortcut: every
     # output patch in the index list) and 0 / 2 / 7 / 1 dynamic identity blocks, either with spatial maskers
     # (granularity 4-4-2-1, each bias calibrated to ratio 0.5 on the block's actual input) or with a seeded
     # Bernoulli(0.6) keep gate per sample and block (layer skipping, S = H).  Every run starts from the input.
     def regnety_body(N, keep_p):
         cfg = I.REGNETY["800MF"]
         gw = cfg["g"]
-        x0 = D.to_device(I.feature_map(8300, 8, 112, 112, 32, I.BF16, nonneg=True), I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        g0 = np.random.default_rng(8300)
+        img = D.to_device(I.round_to(g0.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16), I.BF16)
+        img = img.repeat(N // 8, 1, 1, 1).contiguous()
+        w3 = D.to_device(I.round_to(g0.standard_normal((32, 3, 3, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 27)), I.BF16), I.BF16)
+        s3 = t.from_numpy((1 + 0.1 * g0.standard_normal(32)).astype(np.float32)).cuda()
+        t3 = t.from_numpy((0.1 * g0.standard_normal(32)).astype(np.float32)).cuda()
+        x0 = t.empty((N, 112, 112, 32), dtype=t.bfloat16, device="cuda")
+        ops = [lambda: L.laud_stem3x3(img, N, 224, 224, I.BF16, w3, s3, t3, 32, x0)]
+        ops[0]()
         cur, c_in, hw = x0, 32, 112
-        ops, held, act = [], [x0], []
+        held, act = [img, w3, s3, t3, x0], []
         wc = D.workspace(4096)
         for stage, nblk in ((1, 1), (2, 3), (3, 8), (4, 2)):
             co, hw = cfg["stages"][stage]["c"], hw // 2

@@ -234,12 +234,18 @@ int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p
  * laud_stem: x [N,Hin,Win,3] dtype; 7x7 stride-2 pad-3 conv with w7 [c_out][7][7][3] (dtype),
  * affine s,t (float32), ReLU, then 3x3 stride-2 pad-1 max pooling; out [N,Hp,Wp,c_out] with
  * Hc = (Hin-1)/2 + 1, Hp = (Hc-1)/2 + 1; c_out a multiple of 8.
+ *
+ * laud_stem3x3 (the stem of the RegNet backbones, Sec. 4): x [N,Hin,Win,3] dtype; 3x3 stride-2 pad-1 conv with
+ * w3 [c_out][3][3][3] (dtype), affine s,t (float32), ReLU, no pooling; out [N,Ho,Wo,c_out], Ho = (Hin-1)/2 + 1;
+ * c_out a multiple of 8, at most 256.  No workspace.
  */
 size_t laud_static_bottleneck_workspace(laud_fmap fx, const laud_bottleneck* p, int stride);
 int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, const void* w_sc,
                            const float* s_sc, const float* t_sc, int stride, void* out,
                            void* ws, size_t ws_bytes, void* stream);
 size_t laud_stem_workspace(int N, int Hin, int Win, int c_out, int dtype);
+int laud_stem3x3(const void* x, int N, int Hin, int Win, int dtype, const void* w3, const float* s,
+                 const float* t, int c_out, void* out, void* stream);
 int laud_stem(const void* x, int N, int Hin, int Win, int dtype, const void* w7, const float* s,
               const float* t, int c_out, void* out, void* ws, size_t ws_bytes, void* stream);
 

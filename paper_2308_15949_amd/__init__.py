@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     laud_dyn_bottleneck, laud_gather_patches, laud_layer_skip_compact, laud_mask_gen,
     laud_masker_dyn_bottleneck, laud_channel_masker, channel_masker_workspace,
     laud_dyn_bottleneck_unfused, dyn_bottleneck_unfused_workspace, laud_static_bottleneck,
-    static_bottleneck_workspace, laud_stem, stem_workspace, laud_dyn_projection_bottleneck,
+    static_bottleneck_workspace, laud_stem, laud_stem3x3, stem_workspace, laud_dyn_projection_bottleneck,
     dyn_projection_workspace, GroupSE, laud_dyn_group_se_bottleneck, laud_dyn_group_se_projection_bottleneck, make_group_se,
     laud_stage_timing_enable, laud_stage_timing_read, load,
     make_bottleneck, status_string, workspace_size,

@@ -21,7 +21,7 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
            "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
-           "laud_stem", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
+           "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
            "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
 STAGE_COUNT = 13
 
@@ -103,6 +103,8 @@ def load() -> C.CDLL:
     lib.laud_stem_workspace.argtypes = [i32, i32, i32, i32, i32]
     lib.laud_stem.restype = i32
     lib.laud_stem.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.laud_stem3x3.restype = i32
+    lib.laud_stem3x3.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp]
     lib.laud_channel_masker_workspace.restype = sz
     lib.laud_channel_masker_workspace.argtypes = [Fmap]
     lib.laud_channel_masker.restype = i32
@@ -277,6 +279,11 @@ def laud_stem(x, n: int, hin: int, win: int, dtype: int, w7, s, t, c_out: int, o
     wp, wb = _ws_args(ws)
     _check(load().laud_stem(_ptr(x), int(n), int(hin), int(win), int(dtype), _ptr(w7), _ptr(s), _ptr(t), int(c_out),
                             _ptr(out), wp, wb, _stream()), "laud_stem")
+
+
+def laud_stem3x3(x, n: int, hin: int, win: int, dtype: int, w3, s, t, c_out: int, out) -> None:
+    _check(load().laud_stem3x3(_ptr(x), int(n), int(hin), int(win), int(dtype), _ptr(w3), _ptr(s), _ptr(t), int(c_out),
+                               _ptr(out), _stream()), "laud_stem3x3")
 
 
 def channel_masker_workspace(fx: Fmap) -> int:

@@ -166,9 +166,92 @@ __global__ __launch_bounds__(256) void k_maxpool3x3s2(const ET* __restrict__ in,
   for (int e = 0; e < 8; ++e) elem<ET>::store(po + e, m[e]);
 }
 
+// Stem of the RegNet backbones: 3x3 stride-2 pad-1 conv from the 3-channel image, affine, ReLU.  One thread per
+// output pixel: the 27 inputs of its window are read once into registers, then the output channels are produced
+// eight at a time from the 27 x c_out float32 weights in LDS (all lanes read the same weight: a broadcast).
+// HBM-bound: the image is read once (neighbouring windows overlap in cache) and the output written once.
+template <typename ET>
+__global__ __launch_bounds__(256) void k_stem3x3(const ET* __restrict__ in, int N, int H, int W, int Ho, int Wo,
+                                                 const ET* __restrict__ w, const float* __restrict__ s,
+                                                 const float* __restrict__ t, int C, ET* __restrict__ out) {
+  extern __shared__ float s_w3[];  // [27][C] weights (tap-major, output channel fastest), then scale [C], shift [C]
+  for (int i = threadIdx.x; i < 27 * C; i += 256) {
+    const int o = i % C, k = i / C;
+    s_w3[i] = elem<ET>::load(w + (size_t)o * 27 + k);
+  }
+  float* s_sc = s_w3 + 27 * C;
+  float* s_sh = s_sc + C;
+  for (int i = threadIdx.x; i < C; i += 256) { s_sc[i] = s[i]; s_sh[i] = t[i]; }
+  __syncthreads();
+  const long long pix = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (pix >= (long long)N * Ho * Wo) return;
+  const int n = (int)(pix / (Ho * Wo)), r = (int)(pix - (long long)n * Ho * Wo);
+  const int yo = r / Wo, xo = r - yo * Wo;
+  float v[27];
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int yy = yo * 2 - 1 + ky;
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) {
+      const int xx = xo * 2 - 1 + kx;
+      const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+      const ET* p = in + (((size_t)n * H + (ok ? yy : 0)) * W + (ok ? xx : 0)) * 3;
+#pragma unroll
+      for (int c = 0; c < 3; ++c) v[(ky * 3 + kx) * 3 + c] = ok ? elem<ET>::load(p + c) : 0.f;
+    }
+  }
+  ET* po = out + (size_t)pix * C;
+  for (int g = 0; g < C; g += 8) {
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int k = 0; k < 27; ++k) {
+      const float* wk = s_w3 + k * C + g;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[k] * wk[e];
+    }
+    ET o8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) elem<ET>::store(&o8[e], fmaxf(acc[e] * s_sc[g + e] + s_sh[g + e], 0.f));
+    if constexpr (sizeof(ET) == 2) {
+      uint4 q;
+      __builtin_memcpy(&q, o8, 16);
+      *reinterpret_cast<uint4*>(po + g) = q;
+    } else {
+      uint4 q0, q1;
+      __builtin_memcpy(&q0, o8, 16);
+      __builtin_memcpy(&q1, o8 + 4, 16);
+      reinterpret_cast<uint4*>(po + g)[0] = q0;
+      reinterpret_cast<uint4*>(po + g)[1] = q1;
+    }
+  }
+}
+
 }  // namespace laud
 
 using namespace laud;
+
+extern "C" int laud_stem3x3(const void* x, int N, int Hin, int Win, int dtype, const void* w3, const float* s,
+                            const float* t, int c_out, void* out, void* stream) {
+  if (!x || !w3 || !s || !t || !out || N <= 0 || Hin <= 0 || Win <= 0 || c_out <= 0) return LAUD_ERR_INVALID_ARG;
+  if (dtype != LAUD_F32 && dtype != LAUD_BF16) return LAUD_ERR_INVALID_ARG;
+  if (c_out % 8 || c_out > 256) return LAUD_ERR_UNSUPPORTED;
+  const int Ho = (Hin - 1) / 2 + 1, Wo = (Win - 1) / 2 + 1;
+  const long long work = (long long)N * Ho * Wo;
+  if ((work + 255) / 256 > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  const unsigned blocks = (unsigned)((work + 255) / 256);
+  const size_t lds = (size_t)29 * c_out * sizeof(float);
+  if (dtype == LAUD_BF16)
+    hipLaunchKernelGGL((k_stem3x3<bf16_t>), dim3(blocks), dim3(256), lds, st, (const bf16_t*)x, N, Hin, Win, Ho, Wo,
+                       (const bf16_t*)w3, s, t, c_out, (bf16_t*)out);
+  else
+    hipLaunchKernelGGL((k_stem3x3<float>), dim3(blocks), dim3(256), lds, st, (const float*)x, N, Hin, Win, Ho, Wo,
+                       (const float*)w3, s, t, c_out, (float*)out);
+  return check_launch();
+}
 
 namespace {
 struct StemWs { size_t cols, wp, conv, bytes; };

@@ -49,6 +49,27 @@ def test_stem(case):
     close(D.to_host(out), ref, TOL[dt])
 
 
+@pytest.mark.parametrize("case", [(2, 224, 224, 32, I.BF16), (3, 45, 37, 32, I.BF16), (2, 45, 37, 48, I.F32),
+                                  (1, 2, 2, 8, I.F32), (2, 31, 64, 256, I.BF16)])
+def test_stem3x3(case):
+    """Stem of the RegNet backbones: 3x3 stride-2 conv from the image, affine, ReLU."""
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    N, Hin, Win, co, dt = case
+    g = np.random.default_rng(700 + Hin + co)
+    x = I.round_to(g.standard_normal((N, Hin, Win, 3), dtype=np.float32), dt)
+    w3 = I.round_to(g.standard_normal((co, 3, 3, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 27)), dt)
+    s = (1 + 0.1 * g.standard_normal(co)).astype(np.float32)
+    tt = (0.1 * g.standard_normal(co)).astype(np.float32)
+    ref = O.stem3x3(x, w3, s, tt)
+    xd, wd = D.to_device(x, dt), D.to_device(w3, dt)
+    out = t.full(ref.shape, 7.0, dtype=xd.dtype, device="cuda")
+    L.laud_stem3x3(xd, N, Hin, Win, dt, wd, t.from_numpy(s).cuda(), t.from_numpy(tt).cuda(), co, out)
+    t.cuda.synchronize()
+    close(D.to_host(out), ref, TOL[dt])
+
+
 @pytest.mark.parametrize("case", [
     (2, 12, 10, 16, 8, 32, 1, I.F32), (2, 12, 10, 16, 8, 32, 2, I.F32), (3, 9, 7, 40, 24, 64, 2, I.F32),
     (2, 56, 56, 64, 64, 256, 1, I.BF16), (2, 56, 56, 256, 128, 512, 2, I.BF16), (2, 14, 14, 1024, 512, 2048, 2, I.BF16)])

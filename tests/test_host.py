@@ -26,7 +26,7 @@ def lib():
 def test_header_symbols_are_exported(lib):
     with open(os.path.join(ROOT, "include", "laud.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
-    declared = sorted(set(re.findall(r"\b(laud_[a-z_]+)\s*\(", text)))
+    declared = sorted(set(re.findall(r"\b(laud_[a-z0-9_]+)\s*\(", text)))
     assert declared == sorted(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -155,6 +155,12 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq - 1, st) == B.ERR_WORKSPACE
     assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), vp(FAKE), vp(FAKE), vp(FAKE), 2, 3, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
     assert gp(vp(FAKE), fx, C.byref(pq), ge(16, 8), None, vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needq, st) == B.ERR_INVALID_ARG
+    s3 = lib.laud_stem3x3
+    assert s3(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 36, vp(FAKE), st) == B.ERR_UNSUPPORTED
+    assert s3(vp(FAKE), 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 512, vp(FAKE), st) == B.ERR_UNSUPPORTED
+    assert s3(vp(FAKE), 2, 64, 64, 7, vp(FAKE), vp(FAKE), vp(FAKE), 32, vp(FAKE), st) == B.ERR_INVALID_ARG
+    assert s3(vp(FAKE), 2, 0, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 32, vp(FAKE), st) == B.ERR_INVALID_ARG
+    assert s3(None, 2, 64, 64, 1, vp(FAKE), vp(FAKE), vp(FAKE), 32, vp(FAKE), st) == B.ERR_INVALID_ARG
     sm = lib.laud_stem
     nst = lib.laud_stem_workspace(2, 64, 64, 64, 1)
     assert nst >= 2 * 32 * 32 * (152 + 64) * 2
