@@ -234,3 +234,19 @@ def test_masks_and_params_are_seeded_and_shaped():
     assert np.array_equal(I.round_to(hb.w2, I.BF16), hb.w2)
     assert abs(float(hb.w2.std()) - np.sqrt(2.0 / (9 * 16))) < 0.02
     assert I.seed_for(2, 5, 3) == 2035
+
+
+def test_operands_beyond_the_32_bit_offset_range_are_refused(lib):
+    """The kernels address one operand with 32-bit byte offsets (upper half reserved for 'reads as zero'): a
+    feature map or scratch activation of 2 GiB or more is refused on the host, before anything is launched."""
+    vp = C.c_void_p
+    big = B.Fmap(4096, 56, 56, 256, B.BF16)          # 6.6 GB of bf16
+    p = _bn(256, 64, 256)
+    d = lib.laud_dyn_bottleneck
+    assert d(vp(FAKE), big, C.byref(p), 4, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), 1 << 40, None) == B.ERR_UNSUPPORTED
+    ok = B.Fmap(1024, 56, 56, 256, B.BF16)           # 1.6 GB: inside the range (fails later, on the workspace)
+    assert d(vp(FAKE), ok, C.byref(p), 4, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), 16, None) == B.ERR_WORKSPACE
+    f32 = B.Fmap(1024, 56, 56, 256, B.F32)           # the same shape in float32: 3.3 GB
+    assert d(vp(FAKE), f32, C.byref(p), 4, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), 1 << 40, None) == B.ERR_UNSUPPORTED
+    cs = lib.laud_channel_skip_conv
+    assert cs(vp(FAKE), big, C.byref(p), vp(FAKE), 4, vp(FAKE), vp(FAKE), 1 << 40, None) == B.ERR_UNSUPPORTED
