@@ -392,6 +392,82 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
   }
 }
 
+// Small patches (at most 4 KB): one wave takes PPW patches at once and requests all of their chunks -- PPW x LPP =
+// 16 loads of 16 bytes per lane -- before it touches any of them, so a wave keeps 16 KB in flight however small
+// the patch is, and a block's weight fill and barrier are paid once per 4 x PPW patches.  (Measured: 2 to 5 times
+// the rate of one patch per wave at 0.5 - 4 KB per patch; at 8 KB one patch per wave is as fast or faster.)
+template <typename ET, int PPW, int LPP>
+__global__ __launch_bounds__(256) void k_mask_logits_multi(const ET* __restrict__ x, int N, int H, int W, int C, int S,
+                                                           const float* __restrict__ w, float bias,
+                                                           const uint8_t* __restrict__ keep,
+                                                           uint8_t* __restrict__ mask, float* __restrict__ logits) {
+  constexpr int EPC = elem<ET>::per16;
+  extern __shared__ __align__(16) float s_w[];  // the masker weights, [C]
+  const int Hp = H / S, Wp = W / S, pps = Hp * Wp;
+  const int npatch = N * pps;
+  const int wave = threadIdx.x / kWave, lane = lane_id();
+  const int q0 = (blockIdx.x * (256 / kWave) + wave) * PPW;
+  const int cpr = C / EPC;        // chunks per pixel row
+  const int total = S * S * cpr;  // chunks per patch (at most 64 * LPP)
+  uint4 r[PPW][LPP];
+#pragma unroll
+  for (int p = 0; p < PPW; ++p) {
+    // a patch past the end re-reads the last one (valid addresses); nothing is written for it
+    const int qq = min(q0 + p, npatch - 1);
+    const int n = qq / pps, rr = qq - n * pps;
+    const int py = rr / Wp, px = rr - py * Wp;
+#pragma unroll
+    for (int u = 0; u < LPP; ++u) {
+      const int c = min(lane + u * kWave, total - 1);
+      const int j = c / cpr, cv = c - j * cpr;
+      const int dy = j / S, dx = j - dy * S;
+      const size_t pix = ((size_t)n * H + (py * S + dy)) * W + (px * S + dx);
+      r[p][u] = *reinterpret_cast<const uint4*>(x + pix * C + (size_t)cv * EPC);
+    }
+  }
+  for (int k = threadIdx.x; k < C; k += 256) s_w[k] = w[k];
+  __syncthreads();
+  float acc[PPW];
+#pragma unroll
+  for (int p = 0; p < PPW; ++p) {
+    acc[p] = 0.f;
+#pragma unroll
+    for (int u = 0; u < LPP; ++u) {
+      const int c = lane + u * kWave;
+      const int cv = min(c, total - 1) % cpr;
+      const float4* wp = reinterpret_cast<const float4*>(s_w + cv * EPC);
+      const float4 w0 = wp[0];
+      const uint4 raw = r[p][u];
+      float d;
+      if constexpr (EPC == 4) {
+        d = __uint_as_float(raw.x) * w0.x + __uint_as_float(raw.y) * w0.y + __uint_as_float(raw.z) * w0.z +
+            __uint_as_float(raw.w) * w0.w;
+      } else {
+        const float4 w1 = wp[1];
+        d = __uint_as_float(raw.x << 16) * w0.x + __uint_as_float(raw.x & 0xffff0000u) * w0.y +
+            __uint_as_float(raw.y << 16) * w0.z + __uint_as_float(raw.y & 0xffff0000u) * w0.w +
+            __uint_as_float(raw.z << 16) * w1.x + __uint_as_float(raw.z & 0xffff0000u) * w1.y +
+            __uint_as_float(raw.w << 16) * w1.z + __uint_as_float(raw.w & 0xffff0000u) * w1.w;
+      }
+      acc[p] += c < total ? d : 0.f;
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < PPW; ++p) acc[p] = wave_sum(acc[p]);
+  // lane p writes patch p
+  float mine = 0.f;
+#pragma unroll
+  for (int p = 0; p < PPW; ++p) mine = lane == p ? acc[p] : mine;
+  const int q = q0 + lane;
+  if (lane < PPW && q < npatch) {
+    const float logit = mine / (float)(S * S) + bias;
+    bool on = logit > 0.f;  // false for NaN
+    if (keep && keep[q / pps] == 0) on = false;
+    mask[q] = on ? 1 : 0;
+    if (logits) logits[q] = logit;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // stand-alone gather
 // ------------------------------------------------------------------------------------------
@@ -462,7 +538,25 @@ extern "C" int laud_mask_gen(const void* x, laud_fmap fx, int S, const float* w,
       hipLaunchKernelGGL((k_mask_logits<ET, TEAM, false>), dim3(grid), dim3(256), 0, st, (const ET*)x, fx.N,  \
                          fx.H, fx.W, fx.C, S, w, bias, keep, mask, logits);                                   \
   } while (0)
-  if (fx.dtype == LAUD_BF16) {
+  // small patches, enough of them to fill the chip with waves of PPW patches each: the multi-patch kernel
+  const int chunks = (int)(patch_bytes / 16);
+  const int lpp = chunks <= 64 ? 1 : chunks <= 128 ? 2 : 4;
+  if (chunks <= 256 && w_lds && npatch / (16 / lpp) >= 1024) {
+    const int ppw = 16 / lpp;
+    const unsigned g2 = (unsigned)((npatch + 4 * ppw - 1) / (4 * ppw));
+#define LAUD_LAUNCH_MULTI(ET, PPW, LPP)                                                                          \
+  hipLaunchKernelGGL((k_mask_logits_multi<ET, PPW, LPP>), dim3(g2), dim3(256), (size_t)fx.C * 4, st, (const ET*)x, \
+                     fx.N, fx.H, fx.W, fx.C, S, w, bias, keep, mask, logits)
+#define LAUD_PICK_MULTI(ET)                                                    \
+  do {                                                                         \
+    if (lpp == 1) LAUD_LAUNCH_MULTI(ET, 16, 1);                                \
+    else if (lpp == 2) LAUD_LAUNCH_MULTI(ET, 8, 2);                            \
+    else LAUD_LAUNCH_MULTI(ET, 4, 4);                                          \
+  } while (0)
+    if (fx.dtype == LAUD_BF16) LAUD_PICK_MULTI(bf16_t); else LAUD_PICK_MULTI(float);
+#undef LAUD_PICK_MULTI
+#undef LAUD_LAUNCH_MULTI
+  } else if (fx.dtype == LAUD_BF16) {
     if (big) LAUD_LAUNCH_MASK(bf16_t, 256); else LAUD_LAUNCH_MASK(bf16_t, 64);
   } else {
     if (big) LAUD_LAUNCH_MASK(float, 256); else LAUD_LAUNCH_MASK(float, 64);

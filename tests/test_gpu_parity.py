@@ -84,6 +84,13 @@ MASK_CASES = [
     (3, 14, 14, 256, 14, I.BF16),   # S = H: one logit per sample (layer gate), whole-block team
     (2, 14, 14, 64, 7, I.F32),
     (40, 56, 56, 16, 4, I.BF16),    # 7840 patches: multi-block compaction
+    # many small patches: the kernel that gives a wave 16 / 8 / 4 patches at once (ragged last wave each time)
+    (42, 56, 56, 16, 2, I.BF16),    # 8 chunks per patch, 32928 patches
+    (84, 56, 56, 64, 4, I.BF16),    # 128 chunks, 16464 patches
+    (42, 56, 56, 128, 4, I.BF16),   # 256 chunks, 8232 patches
+    (21, 56, 56, 64, 4, I.F32),     # 256 chunks in float32, 4116 patches
+    (42, 56, 56, 8, 2, I.F32),      # 8 chunks in float32
+    (6, 56, 56, 48, 4, I.BF16),     # 96 chunks but only 1176 patches: too few for it, one patch per wave
 ]
 
 
