@@ -471,14 +471,16 @@ __global__ __launch_bounds__(256) void k_mask_logits_multi(const ET* __restrict_
 // ------------------------------------------------------------------------------------------
 // stand-alone gather
 // ------------------------------------------------------------------------------------------
-// One wave per (patch, dy, dx) slot of the gathered buffer; 16-byte copies, zero fill outside.
+// One team of `team` lanes (a power of two, 8 .. 64: the pixel's 16-byte chunks rounded up, so that narrow maps do
+// not leave most of a wave idle) per (patch, dy, dx) slot of the gathered buffer; 16-byte copies, zero fill outside.
 __global__ __launch_bounds__(256) void k_gather(const uint4* __restrict__ x, int H, int W, int S, int halo,
                                                 int chunks_per_pixel, const int32_t* __restrict__ idx,
                                                 const int32_t* __restrict__ count, uint4* __restrict__ out,
-                                                long long cap_slots) {
+                                                long long cap_slots, int team) {
   const int E = S + 2 * halo;
   const int Hp = H / S, Wp = W / S;
-  const long long slot = (long long)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+  const long long slot = ((long long)blockIdx.x * 256 + threadIdx.x) / team;
+  const int tl = (int)threadIdx.x & (team - 1);
   if (slot >= cap_slots) return;
   const int p = (int)(slot / (E * E));
   if (p >= *count) return;
@@ -493,7 +495,7 @@ __global__ __launch_bounds__(256) void k_gather(const uint4* __restrict__ x, int
   uint4* dst = out + (size_t)slot * chunks_per_pixel;
   const uint4* src = x + (((size_t)n * H + (inside ? yy : 0)) * W + (inside ? xx : 0)) * chunks_per_pixel;
   const uint4 zero = make_uint4(0, 0, 0, 0);
-  for (int c = lane_id(); c < chunks_per_pixel; c += kWave) dst[c] = inside ? src[c] : zero;
+  for (int c = tl; c < chunks_per_pixel; c += team) dst[c] = inside ? src[c] : zero;
 }
 
 }  // namespace laud
@@ -576,12 +578,14 @@ extern "C" int laud_gather_patches(const void* x, laud_fmap fx, int S, int halo,
   if (npatch > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
   const int E = S + 2 * halo;
   const long long slots = npatch * E * E;
-  const long long blocks = (slots + 3) / 4;
-  if (blocks > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
   const int cpp = (int)((size_t)fx.C * elem_bytes(fx.dtype) / 16);
+  int team = 8;
+  while (team < kWave && team < cpp) team <<= 1;
+  const long long blocks = (slots * team + 255) / 256;
+  if (blocks > 0x7fffffffLL) return LAUD_ERR_UNSUPPORTED;
   clear_stale_error();
   StageScope scope(LAUD_STAGE_GATHER, (hipStream_t)stream);
   hipLaunchKernelGGL(k_gather, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)x, fx.H, fx.W,
-                     S, halo, cpp, idx, count, (uint4*)out, slots);
+                     S, halo, cpp, idx, count, (uint4*)out, slots, team);
   return check_launch();
 }
