@@ -67,6 +67,27 @@ __device__ __forceinline__ int scan_wave_counts(int count, int nwaves, int* wsum
   return __shfl(incl - v, wave, kWave);
 }
 
+// lower_bound over a sorted list by a whole wave: 64 probes per round instead of one, so a list of n entries
+// takes ceil(log64 n) dependent round trips.  Every lane of the wave must call it; all get the result.
+__device__ __forceinline__ int wave_lower_bound(const int32_t* v, int n, int key) {
+  const int lane = lane_id();
+  int lo = 0, hi = n;  // the answer lies in [lo, hi]
+  while (hi > lo) {
+    const int step = (hi - lo + kWave - 1) / kWave;
+    const int pos = lo + lane * step;
+    const bool below = pos < hi && v[pos] < key;  // true for a prefix of the lanes (sorted list)
+    const int c = __popcll(__ballot(below));
+    if (c == 0) {
+      hi = lo;
+    } else {
+      const int nhi = min(lo + c * step, hi);
+      lo = lo + (c - 1) * step + 1;
+      hi = nhi;
+    }
+  }
+  return lo;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -684,11 +684,11 @@ __global__ __launch_bounds__(kNeedThreads) void k_need(const int32_t* __restrict
   for (int i = tid; i < ns * pps; i += kNeedThreads) s_pm[i] = 0;
   __syncthreads();
   // The group's slice of the sorted index list: short lists are scanned whole by all threads (a
-  // handful of independent loads each); a binary search costs a dozen dependent loads in a row.
+  // handful of independent loads each); longer ones are searched 64 probes at a time by every wave.
   int lo = 0, hi = cnt;
   if (cnt > 16 * kNeedThreads) {
-    lo = lower_bound_dev(idx, cnt, n0 * pps);
-    hi = lower_bound_dev(idx, cnt, (n0 + ns) * pps);
+    lo = wave_lower_bound(idx, cnt, n0 * pps);
+    hi = wave_lower_bound(idx, cnt, (n0 + ns) * pps);
   }
   // eight entries per thread requested before any is used: one round trip per batch, not per entry
   for (int i0 = lo + tid; i0 < hi; i0 += 8 * kNeedThreads) {

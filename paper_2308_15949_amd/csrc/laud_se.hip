@@ -11,27 +11,6 @@ namespace laud {
 // two fully connected layers batched over samples, and the rows multiplied by their sample's gate in place.
 // The squeeze therefore averages over the sample's computed pixels; a sample without active patches has no rows.
 
-// lower_bound over a sorted list by a whole wave: 64 probes per round instead of one, so a list of n entries
-// takes ceil(log64 n) dependent round trips.  Every lane of the wave must call it; all get the result.
-__device__ __forceinline__ int wave_lower_bound(const int32_t* v, int n, int key) {
-  const int lane = lane_id();
-  int lo = 0, hi = n;  // the answer lies in [lo, hi]
-  while (hi > lo) {
-    const int step = (hi - lo + kWave - 1) / kWave;
-    const int pos = lo + lane * step;
-    const bool below = pos < hi && v[pos] < key;  // true for a prefix of the lanes (sorted list)
-    const int c = __popcll(__ballot(below));
-    if (c == 0) {
-      hi = lo;
-    } else {
-      const int nhi = min(lo + c * step, hi);
-      lo = lo + (c - 1) * step + 1;
-      hi = nhi;
-    }
-  }
-  return lo;
-}
-
 constexpr int kSqThreads = 1024, kSqChunks = 128;
 
 // grid (ceil(chunks per row / 128), N): z[n][c] = mean over the sample's rows of h2[row][c] for one block of

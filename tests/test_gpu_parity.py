@@ -243,6 +243,7 @@ DYN_CASES = [
     (2, 14, 14, 1024, 256, 7, I.BF16, True),  # stage 3 at the coarse granularity of the 4-4-7-1 set
     (2, 56, 56, 32, 16, 8, I.BF16, True),     # S = 8 (the 8-4-7-1 set), 7x7 patch grid
     (2, 28, 28, 32, 16, 14, I.F32, False),
+    (12, 56, 56, 16, 8, 1, I.BF16, True),     # 37632 patches, ~18.8k active: index list searched 64 probes at a time
 ]
 
 
