@@ -134,22 +134,43 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
                                                                    int32_t* __restrict__ sample_offsets,
                                                                    int per_sample) {
   __shared__ int scan[2][kCompactThreads / kWave];
-  int running = 0, pass = 0;
-  for (int base = 0; base < n; base += 4 * kCompactThreads, ++pass) {
+  // A thread owns entries 4*tid .. 4*tid+3 of each 4096-entry pass.  All of its mask bytes (at most eight
+  // passes: n <= 32768) are requested before the first pass runs, so the kernel pays one far-memory round trip
+  // instead of one per pass.
+  constexpr int kMaxPass = kSmallCompactMax / (4 * kCompactThreads);
+  unsigned m4[kMaxPass];
+  const bool aligned = (reinterpret_cast<unsigned long long>(mask) & 3ull) == 0;  // it is, for a tensor base
+#pragma unroll
+  for (int p = 0; p < kMaxPass; ++p) {
+    const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
+    unsigned v = 0;
+    if (aligned && i0 + 3 < n) {
+      v = *reinterpret_cast<const unsigned*>(mask + i0);
+    } else {
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < n) v |= (unsigned)mask[i0 + j] << (8 * j);
+    }
+    m4[p] = v;
+  }
+  int running = 0;
+#pragma unroll
+  for (int p = 0; p < kMaxPass; ++p) {
+    const int base = p * 4 * kCompactThreads;
+    if (base >= n) break;  // uniform
     const int i0 = base + 4 * (int)threadIdx.x;
     bool f[4];
     unsigned long long b[4];
     int before = 0, mine = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      f[j] = (i0 + j < n) && mask[i0 + j] != 0;
+      f[j] = ((m4[p] >> (8 * j)) & 0xffu) != 0;  // entries past n were read as 0
       b[j] = __ballot(f[j]);
       before += ballot_prefix(b[j]);  // set entries of lower lanes at position j
     }
     int wtot = 0, tot;
 #pragma unroll
     for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
-    const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[pass & 1], &tot);
+    const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[p & 1], &tot);
     int pos = running + wo + before;  // set entries before (this thread, position 0)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
