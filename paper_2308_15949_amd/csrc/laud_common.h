@@ -94,6 +94,12 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
 // ---- host-side launch checking -----------------------------------------------------------
 // hipGetLastError() reports (and clears) the last error of ANY earlier HIP call of the thread,
 // the caller's included; each entry point clears that state once, after validation and before

@@ -139,18 +139,31 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
   // instead of one per pass.
   constexpr int kMaxPass = kSmallCompactMax / (4 * kCompactThreads);
   unsigned m4[kMaxPass];
-  const bool aligned = (reinterpret_cast<unsigned long long>(mask) & 3ull) == 0;  // it is, for a tensor base
+  // Every load is unconditional (clamped index, value dropped past the end): conditional loads would be waited for
+  // one by one.  Whole words when the base is word-aligned and n a multiple of four (uniform), bytes otherwise.
+  const bool words = (reinterpret_cast<unsigned long long>(mask) & 3ull) == 0 && (n & 3) == 0 && n > 0;
+  if (words) {
 #pragma unroll
-  for (int p = 0; p < kMaxPass; ++p) {
-    const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
-    unsigned v = 0;
-    if (aligned && i0 + 3 < n) {
-      v = *reinterpret_cast<const unsigned*>(mask + i0);
-    } else {
-      for (int j = 0; j < 4; ++j)
-        if (i0 + j < n) v |= (unsigned)mask[i0 + j] << (8 * j);
+    for (int p = 0; p < kMaxPass; ++p) {
+      const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
+      const unsigned v = *reinterpret_cast<const unsigned*>(mask + min(i0, n - 4));
+      m4[p] = i0 < n ? v : 0u;
     }
-    m4[p] = v;
+  } else if (n > 0) {
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+      const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
+      unsigned v = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const unsigned byte = mask[min(i0 + j, n - 1)];
+        v |= (i0 + j < n ? byte : 0u) << (8 * j);
+      }
+      m4[p] = v;
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) m4[p] = 0u;
   }
   int running = 0;
 #pragma unroll
@@ -255,6 +268,65 @@ __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa
   }
 }
 
+// Ordered compaction of up to 64 x 4096 entries in ONE launch of several blocks: block b owns entries
+// [4096 b, 4096 b + 4096) and first counts the set entries of all blocks before it by itself (one 4-byte load
+// per thread and preceding block, eight in flight) instead of waiting for anybody: no second launch, no
+// inter-block dependency, and each block's own pass runs on a CU of its own.  Needs a word-aligned mask and n a
+// multiple of four (whole-word loads); the launcher checks.
+constexpr int kCompactOneLaunchMax = 64 * kCompactBlock;
+__global__ __launch_bounds__(kCompactThreads) void k_compact_blocks(const uint8_t* __restrict__ mask, int n,
+                                                                    int32_t* __restrict__ idx,
+                                                                    int32_t* __restrict__ count,
+                                                                    int32_t* __restrict__ sample_offsets,
+                                                                    int per_sample) {
+  __shared__ int scan[2][kCompactThreads / kWave];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const unsigned* words = reinterpret_cast<const unsigned*>(mask);
+  // own entries: 4 tid .. 4 tid + 3 of the block's range (requested first, used last)
+  const int i0 = b * kCompactBlock + 4 * tid;
+  const unsigned own = words[min(i0, n - 4) >> 2];
+  // set entries of the blocks before this one
+  int before_blocks = 0;
+  for (int p0 = 0; p0 < b; p0 += 8) {
+    unsigned v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = words[min(p0 + u, b - 1) * (kCompactBlock / 4) + tid];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      unsigned t = (v[u] | (v[u] >> 4)) & 0x0f0f0f0fu;  // per byte: non-zero -> one bit
+      t = (t | (t >> 2)) & 0x03030303u;
+      t = (t | (t >> 1)) & 0x01010101u;
+      before_blocks += p0 + u < b ? __popc(t) : 0;
+    }
+  }
+  int base;
+  (void)scan_wave_counts(wave_sum_int(before_blocks), kCompactThreads / kWave, scan[0], &base);
+  // own pass, as in k_compact_small
+  const unsigned m4 = i0 < n ? own : 0u;
+  bool f[4];
+  unsigned long long bal[4];
+  int before = 0, mine = 0, wtot = 0, tot;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f[j] = ((m4 >> (8 * j)) & 0xffu) != 0;
+    bal[j] = __ballot(f[j]);
+    before += ballot_prefix(bal[j]);
+    wtot += __popcll(bal[j]);
+  }
+  const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[1], &tot);
+  const int pos = base + wo + before;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = i0 + j;
+    if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
+    if (f[j]) { idx[pos + mine] = i; ++mine; }
+  }
+  if (b == (int)gridDim.x - 1 && tid == 0) {
+    *count = base + tot;
+    if (sample_offsets) sample_offsets[n / per_sample] = base + tot;
+  }
+}
+
 __global__ void k_write_zero_count(int32_t* count, int32_t* sample_offsets) {
   *count = 0;
   if (sample_offsets) sample_offsets[0] = 0;
@@ -265,6 +337,12 @@ int launch_compact(const uint8_t* mask, int n, int32_t* idx, int32_t* count, int
   StageScope scope(LAUD_STAGE_COMPACT, stream);
   if (n == 0) {
     hipLaunchKernelGGL(k_write_zero_count, dim3(1), dim3(1), 0, stream, count, sample_offsets);
+    return check_launch();
+  }
+  if (n > kCompactBlock && n <= kCompactOneLaunchMax && (n & 3) == 0 &&
+      (reinterpret_cast<unsigned long long>(mask) & 3ull) == 0) {
+    hipLaunchKernelGGL(k_compact_blocks, dim3((n + kCompactBlock - 1) / kCompactBlock), dim3(kCompactThreads), 0, stream,
+                       mask, n, idx, count, sample_offsets, per_sample > 0 ? per_sample : 1);
     return check_launch();
   }
   if (n <= kSmallCompactMax) {

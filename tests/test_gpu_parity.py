@@ -71,6 +71,20 @@ def test_compact_bit_exact(G, n, p):
     assert np.all(idx[c:] == -7)  # nothing written past count
 
 
+@pytest.mark.parametrize("n", [4100, 8192, 25088, 65536, 262144, 262148])
+def test_compact_any_nonzero_byte_counts_as_set(G, n):
+    """Byte values with a single bit anywhere (0x01 .. 0x80) and 0xff among zeros, at sizes on both sides of the
+    one-launch multi-block path."""
+    g = np.random.default_rng(n)
+    vals = np.array([0, 0, 0, 1, 2, 4, 8, 16, 32, 64, 128, 255], np.uint8)
+    mask = vals[g.integers(0, len(vals), n)]
+    idx, c = gpu_compact(G, mask)
+    ref = O.compact(mask)
+    assert c == len(ref)
+    assert np.array_equal(idx[:c], ref)
+    assert np.all(idx[c:] == -7)
+
+
 # ------------------------------------------------------------------------------------------
 # mask generator (laud_mask_gen)
 # ------------------------------------------------------------------------------------------
