@@ -199,12 +199,16 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_small(const uint8_t
   }
 }
 
-// Pooling, threshold and ordered compaction in ONE single-block launch for S = 2 and at most 8192
-// patches (a stage-3 batch of 128 images): the two dependent kernels cost two launch-plus-far-latency
-// chains for a few kilobytes of work.  A thread owns entries 4*tid .. 4*tid+3 of each 4096-entry pass
-// as in k_compact_small, requests all of its projection reads (two 8-byte loads per patch) before
-// using any, and compacts from registers.  Same summation order as pooled_decision.
+// Pooling, threshold and ordered compaction in ONE launch for S = 2 and at most 8192 patches (a stage-3
+// batch of 128 images): the two dependent kernels cost two launch-plus-far-latency chains for a few kilobytes
+// of work.  One patch per thread, up to eight blocks of 1024; a block needs the number of active patches
+// before its own and gets it by deciding those patches itself (at most seven more per thread: four adds and a
+// compare each), so the blocks neither wait for each other nor share anything, and no block runs more than one
+// compaction pass (a single block doing all passes is bound by instruction issue on its one CU).  Every
+// projection read of a thread (two 8-byte loads per patch) is requested before any is used.  Same summation
+// order as pooled_decision, hence the same decisions in every block.
 constexpr int kPoolFusedMax = 2 * kCompactBlock;
+constexpr int kPoolFusedBlocks = kPoolFusedMax / kCompactThreads;
 __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa, int n, uint8_t* __restrict__ mask,
                                                                      int32_t* __restrict__ idx,
                                                                      int32_t* __restrict__ count,
@@ -212,59 +216,48 @@ __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa
                                                                      int per_sample) {
   __shared__ int scan[2][kCompactThreads / kWave];
   const int Hp = pa.H / 2, Wp = pa.W / 2;
-  float2 top[2][4], bot[2][4];
-  int sample[2][4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  float2 top[kPoolFusedBlocks], bot[kPoolFusedBlocks];
+  int kept[kPoolFusedBlocks];
 #pragma unroll
-  for (int p = 0; p < 2; ++p)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = p * 4 * kCompactThreads + 4 * (int)threadIdx.x + j;
-      const int q = i < n ? i : n - 1;  // past the end: re-read the last patch, result unused
-      const int s = q / (Hp * Wp), r = q - s * (Hp * Wp);
-      const int py = r / Wp, px = r - py * Wp;
-      const float* base = pa.proj + ((size_t)s * pa.H + py * 2) * pa.W + px * 2;
-      sample[p][j] = s;
-      top[p][j] = *reinterpret_cast<const float2*>(base);
-      bot[p][j] = *reinterpret_cast<const float2*>(base + pa.W);
-    }
-  int running = 0;
-#pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int i0 = p * 4 * kCompactThreads + 4 * (int)threadIdx.x;
-    if (p * 4 * kCompactThreads >= n) break;  // uniform
-    bool f[4];
-    unsigned long long b[4];
-    int before = 0, mine = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float acc = ((top[p][j].x + top[p][j].y) + bot[p][j].x) + bot[p][j].y;
-      const float logit = acc / 4.0f + pa.bias;
-      bool on = logit > 0.f;  // false for NaN
-      if (pa.keep && pa.keep[sample[p][j]] == 0) on = false;
-      f[j] = (i0 + j < n) && on;
-      if (i0 + j < n) {
-        mask[i0 + j] = on ? 1 : 0;
-        if (pa.logits) pa.logits[i0 + j] = logit;
-      }
-      b[j] = __ballot(f[j]);
-      before += ballot_prefix(b[j]);
-    }
-    int wtot = 0, tot;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) wtot += __popcll(b[j]);
-    const int wo = scan_wave_counts(wtot, kCompactThreads / kWave, scan[p & 1], &tot);
-    const int pos = running + wo + before;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = i0 + j;
-      if (sample_offsets && i < n && (i % per_sample) == 0) sample_offsets[i / per_sample] = pos + mine;
-      if (f[j]) { idx[pos + mine] = i; ++mine; }
-    }
-    running += tot;
+  for (int u = 0; u < kPoolFusedBlocks; ++u) {
+    // slot u < b: the patch of block u at this thread's position; slots from b on: the thread's own patch
+    const int q = min(min(u, b) * kCompactThreads + tid, n - 1);  // past the end: the last patch, result unused
+    const int s = q / (Hp * Wp), r = q - s * (Hp * Wp);
+    const int py = r / Wp, px = r - py * Wp;
+    const float* base = pa.proj + ((size_t)s * pa.H + py * 2) * pa.W + px * 2;
+    top[u] = *reinterpret_cast<const float2*>(base);
+    bot[u] = *reinterpret_cast<const float2*>(base + pa.W);
+    kept[u] = pa.keep ? (int)pa.keep[s] : 1;
   }
-  if (threadIdx.x == 0) {
-    *count = running;
-    if (sample_offsets) sample_offsets[n / per_sample] = running;
+  int before_blocks = 0;
+  bool own_on = false;
+  float own_logit = 0.f;
+#pragma unroll
+  for (int u = 0; u < kPoolFusedBlocks; ++u) {
+    const float acc = ((top[u].x + top[u].y) + bot[u].x) + bot[u].y;
+    const float logit = acc / 4.0f + pa.bias;
+    const bool on = logit > 0.f && kept[u] != 0;  // false for NaN
+    before_blocks += (u < b && on) ? 1 : 0;         // blocks before this one are full: every slot is a patch
+    if (u == b) { own_on = on; own_logit = logit; }
+  }
+  int base_cnt;
+  (void)scan_wave_counts(wave_sum_int(before_blocks), kCompactThreads / kWave, scan[0], &base_cnt);
+  const int q = b * kCompactThreads + tid;
+  const bool f = q < n && own_on;
+  if (q < n) {
+    mask[q] = own_on ? 1 : 0;
+    if (pa.logits) pa.logits[q] = own_logit;
+  }
+  const unsigned long long bal = __ballot(f);
+  int tot;
+  const int wo = scan_wave_counts(__popcll(bal), kCompactThreads / kWave, scan[1], &tot);
+  const int pos = base_cnt + wo + ballot_prefix(bal);
+  if (sample_offsets && q < n && (q % per_sample) == 0) sample_offsets[q / per_sample] = pos;
+  if (f) idx[pos] = q;
+  if (b == (int)gridDim.x - 1 && tid == 0) {
+    *count = base_cnt + tot;
+    if (sample_offsets) sample_offsets[n / per_sample] = base_cnt + tot;
   }
 }
 
@@ -367,8 +360,8 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
   PoolArgs pa{proj, keep, logits, H, W, S, bias};
   if (S == 2 && npatch > 0 && npatch <= kPoolFusedMax) {
     StageScope scope(LAUD_STAGE_COMPACT, stream);
-    hipLaunchKernelGGL(k_pool_compact_s2, dim3(1), dim3(kCompactThreads), 0, stream, pa, npatch, mask, idx, count,
-                       sample_offsets, pps);
+    hipLaunchKernelGGL(k_pool_compact_s2, dim3((npatch + kCompactThreads - 1) / kCompactThreads), dim3(kCompactThreads), 0,
+                       stream, pa, npatch, mask, idx, count, sample_offsets, pps);
     return check_launch();
   }
   // One thread per patch over a wide grid: the S*S projection reads of a patch are independent, and a
