@@ -286,9 +286,14 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                                       # + the index list and the dilated-set kernels (one per-kernel constant each)
                                       "predicted_us": round((pred + 2 * PRED.MI355X.const_s) * 1e6, 1)}
                     if Ss == sg["S"] and stage != 3:
+                        # algorithmic HBM bytes of the in-place block: x over the dilated set for conv1, the residual
+                        # over the active set for conv3, and the active set written back
+                        xbytes_s = float(xs.numel() * xs.element_size())
+                        hbm = (PRED.expected_dilated_ratio(r, Ss) + 2.0 * r) * xbytes_s
                         ex[f"dyn_bottleneck_stage{stage}_b128_r050"] = {
                             "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
-                            "mfma_frac_useful": round(r * N * flops_img / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+                            "mfma_frac_useful": round(r * N * flops_img / us / (PEAK_BF16_TFLOPS * 1e6), 4),
+                            "hbm_frac_algorithmic": round(hbm / us / 1e3 / PEAK_HBM_GBS, 3)}
                     del wss
                 ex[f"latency_vs_S_stage{stage}_b128_r050"] = curve
             else:
