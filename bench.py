@@ -306,6 +306,31 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                 ex[f"channel_skip_stage{stage}_b64_keep050"] = {
                     "p50_us": round(us, 1), "images_per_s": round(N / us * 1e6, 0),
                     "mfma_frac_useful": round(useful / us / (PEAK_BF16_TFLOPS * 1e6), 4)}
+                # latency against the kept fraction of channels and the channel granularity G (the shape of the
+                # paper's latency-vs-r^c-and-G figure): every sample keeps exactly round(keep * D) of its D = m / G
+                # groups, a seeded choice per sample; the static block on the same input for the ratio
+                if stage == 3:
+                    m_ = sg["m"]
+                    grid = {}
+                    for G_ in (1, 2, 8, 64):
+                        D_ = m_ // G_
+                        wsg = D.workspace(L.workspace_size(B.OP_CHANNEL_SKIP, fxs, dbs.desc, D_))
+                        row = {}
+                        for keep_ in (0.25, 0.5, 0.75, 1.0):
+                            gg = np.random.default_rng(7320 + G_)
+                            cmk = np.zeros((N, D_), np.uint8)
+                            kk = int(round(keep_ * D_))
+                            for n_ in range(N):
+                                cmk[n_, gg.permutation(D_)[:kk]] = 1
+                            cmk_d = t.from_numpy(cmk).cuda()
+                            usg = _p50_us(t, lambda i: L.laud_channel_skip_conv(xb[i % 4], fxs, dbs.desc, cmk_d, D_,
+                                                                               xb[i % 4], wsg), iters=12, warm=2)
+                            pr = PRED.predict_block(PRED.MI355X, "channel", n=N, hw_px=sg["hw"], c_in=sg["c_in"], m=m_,
+                                                    r=kk / D_)["total_s"]
+                            row[f"keep{int(keep_ * 100):03d}"] = {"p50_us": round(usg, 1), "predicted_us": round(pr * 1e6, 1)}
+                        grid[f"G{G_}"] = row
+                        del wsg
+                    ex["channel_skip_latency_vs_keep_and_G_stage3_b64"] = grid
                 # the channel masker that would produce such a mask (global average pooling + 2-layer MLP, D = 4):
                 # HBM-bound, reads x once; cold rotating buffers are not kept here, so the rate is a cache-warm one
                 wa, ba, wb2, bb2, hid = I.channel_masker_weights(7350 + stage, sg["c_in"], 4)

@@ -99,16 +99,18 @@ __device__ __forceinline__ void mma16(f32x16& acc, const uint4& a, const uint4& 
   }
 }
 
+// Element-wise form of the kept-channel gather for group widths that do not fill a 16-byte chunk: the
+// elements at offsets eoff[] of a weight row; every load is issued (an element that must read as zero has a valid
+// offset and is dropped afterwards), so the loads of a slice stay in flight together.
 template <typename ET>
-__device__ __forceinline__ uint4 gather_elems(const ET* w, const int* kgrp, int G, int k0, int kend) {
-  // Element-wise form of the kept-channel gather for group widths that do not fill a 16-byte chunk.
+__device__ __forceinline__ uint4 gather_elems(const ET* w, const int (&eoff)[elem<ET>::per16], unsigned okbits) {
   constexpr int EPC = elem<ET>::per16;
   ET tmp[EPC];
 #pragma unroll
-  for (int e = 0; e < EPC; ++e) {
-    const int k = k0 + e;
-    tmp[e] = (k < kend) ? w[kgrp[k / G] * G + (k % G)] : (ET)0;
-  }
+  for (int e = 0; e < EPC; ++e) tmp[e] = w[eoff[e]];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e)
+    if (!((okbits >> e) & 1u)) tmp[e] = (ET)0;
   uint4 r;
   __builtin_memcpy(&r, tmp, 16);
   return r;
@@ -398,6 +400,7 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // rows).  All loads are unconditional and branch-free, so the compiler can count the loads in
   // flight instead of draining them.  Slices are visited in order; (tap, kc) advance per call.
   const int gK = a.K, gG = a.G;
+  const int gshift = (gG & (gG - 1)) == 0 ? __builtin_ctz((unsigned)gG) : -1;  // log2 of a power-of-two group width
   // Scalar state of the load side, advanced once per slice: byte offsets of the slice in the activation
   // and weight operands, the position (tap, K chunk) and the tap's bit for the rows' tap masks.  Past the
   // last tap the bit has left the masks' range and `live` is off, so null slices select nothing.
@@ -440,15 +443,30 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
       const bool ok = kok && (amask[i] & tb);
       ra[i] = __builtin_amdgcn_raw_buffer_load_b128(arsrc, ok ? voffA[i] : kOob, asoff, 0);
     }
+    // narrow groups (kept-channel gather element by element): the chunk's element offsets inside a weight
+    // row are the same for every row of this thread
+    int eoff[EPC];
+    unsigned eok = 0;
+    if constexpr (MODE == M_CS2 || MODE == M_CS3) {
+      if (!kvec) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+          const bool ok = kv && ke + e < keff;
+          const int kk = ok ? ke + e : 0;
+          const int g = gshift >= 0 ? kk >> gshift : kk / gG;
+          eoff[e] = (keff > 0 ? s_kgrp[g] : 0) * gG + (kk - g * gG);
+          eok |= ok ? (1u << e) : 0u;
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < BR; ++i) {
       if constexpr (MODE == M_CS2 || MODE == M_CS3) {
         const ET* wtap = wrow[i] + (long long)tap * gK;
         if (kvec) {
           rb[i] = *(kv ? (gptr16)(wtap + s_kgrp[ke / gG] * gG + (ke % gG)) : zpage);
-        } else {  // narrow groups: element-wise gather
-          uint4 g = make_uint4(0, 0, 0, 0);
-          if (kv) g = gather_elems<ET>(wtap, s_kgrp, gG, ke, keff);
+        } else {
+          const uint4 g = gather_elems<ET>(wtap, eoff, eok);
           rb[i] = u32x4{g.x, g.y, g.z, g.w};
         }
       } else if constexpr (MODE == M_G2) {

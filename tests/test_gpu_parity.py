@@ -371,6 +371,10 @@ CS_CASES = [
     (6, 14, 14, 1024, 256, 4, I.BF16, True),  # stage-3 bottleneck, G = 64
     (3, 56, 56, 256, 64, 4, I.BF16, True),   # stage-1 bottleneck, G = 16
     (2, 9, 5, 40, 24, 3, I.F32, True),       # ragged everything, G = 8
+    (4, 7, 7, 64, 32, 32, I.BF16, True),     # G = 1 (the paper's other granularity): element-wise
+    (3, 6, 6, 48, 24, 8, I.F32, True),       # G = 3: element-wise, not a power of two
+    (4, 14, 14, 256, 128, 128, I.BF16, False),  # G = 1 over several K slices
+    (3, 14, 14, 256, 96, 16, I.BF16, True),  # G = 6 in bf16: element-wise, not a power of two, ragged kept widths
 ]
 
 
