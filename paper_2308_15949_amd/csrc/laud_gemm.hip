@@ -102,15 +102,21 @@ __device__ __forceinline__ void mma16(f32x16& acc, const uint4& a, const uint4& 
 // Element-wise form of the kept-channel gather for group widths that do not fill a 16-byte chunk: the
 // elements at offsets eoff[] of a weight row; every load is issued (an element that must read as zero has a valid
 // offset and is dropped afterwards), so the loads of a slice stay in flight together.
-template <typename ET>
+// UE = elements moved per load (1, 2 or 4: a group is a whole number of such units, so a unit never straddles two
+// groups and is aligned to its own size); eoff[] / okbits are per element, a unit is described by its first one.
+template <typename ET, int UE>
 __device__ __forceinline__ uint4 gather_elems(const ET* w, const int (&eoff)[elem<ET>::per16], unsigned okbits) {
   constexpr int EPC = elem<ET>::per16;
-  ET tmp[EPC];
+  struct alignas(UE * sizeof(ET)) Unit { ET v[UE]; };
+  Unit tmp[EPC / UE];
 #pragma unroll
-  for (int e = 0; e < EPC; ++e) tmp[e] = w[eoff[e]];
+  for (int u = 0; u < EPC / UE; ++u) tmp[u] = *reinterpret_cast<const Unit*>(w + eoff[u * UE]);
 #pragma unroll
-  for (int e = 0; e < EPC; ++e)
-    if (!((okbits >> e) & 1u)) tmp[e] = (ET)0;
+  for (int u = 0; u < EPC / UE; ++u)
+    if (!((okbits >> (u * UE)) & 1u)) {
+#pragma unroll
+      for (int e = 0; e < UE; ++e) tmp[u].v[e] = (ET)0;
+    }
   uint4 r;
   __builtin_memcpy(&r, tmp, 16);
   return r;
@@ -401,6 +407,9 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   // flight instead of draining them.  Slices are visited in order; (tap, kc) advance per call.
   const int gK = a.K, gG = a.G;
   const int gshift = (gG & (gG - 1)) == 0 ? __builtin_ctz((unsigned)gG) : -1;  // log2 of a power-of-two group width
+  // elements per load of the element-wise kept-channel gather: the largest of 4, 2, 1 that divides the group width
+  // and stays within 8 bytes
+  const int gunit = (gG % 4 == 0 && sizeof(ET) == 2) ? 4 : (gG % 2 == 0 ? 2 : 1);
   // Scalar state of the load side, advanced once per slice: byte offsets of the slice in the activation
   // and weight operands, the position (tap, K chunk) and the tap's bit for the rows' tap masks.  Past the
   // last tap the bit has left the masks' range and `live` is off, so null slices select nothing.
@@ -466,7 +475,10 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
         if (kvec) {
           rb[i] = *(kv ? (gptr16)(wtap + s_kgrp[ke / gG] * gG + (ke % gG)) : zpage);
         } else {
-          const uint4 g = gather_elems<ET>(wtap, eoff, eok);
+          // the compact K range ends on a group boundary, so a unit is inside it or outside it as a whole
+          const uint4 g = gunit == 4 ? gather_elems<ET, (EPC >= 4 ? 4 : 1)>(wtap, eoff, eok)
+                          : gunit == 2 ? gather_elems<ET, 2>(wtap, eoff, eok)
+                                       : gather_elems<ET, 1>(wtap, eoff, eok);
           rb[i] = u32x4{g.x, g.y, g.z, g.w};
         }
       } else if constexpr (MODE == M_G2) {

@@ -375,6 +375,8 @@ CS_CASES = [
     (3, 6, 6, 48, 24, 8, I.F32, True),       # G = 3: element-wise, not a power of two
     (4, 14, 14, 256, 128, 128, I.BF16, False),  # G = 1 over several K slices
     (3, 14, 14, 256, 96, 16, I.BF16, True),  # G = 6 in bf16: element-wise, not a power of two, ragged kept widths
+    (4, 7, 7, 64, 32, 8, I.BF16, True),      # G = 4 in bf16: gathered in 8-byte units
+    (4, 14, 14, 256, 128, 64, I.BF16, True),  # G = 2 in bf16 over several K slices: 4-byte units
 ]
 
 
