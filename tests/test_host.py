@@ -250,3 +250,12 @@ def test_operands_beyond_the_32_bit_offset_range_are_refused(lib):
     assert d(vp(FAKE), f32, C.byref(p), 4, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), 1 << 40, None) == B.ERR_UNSUPPORTED
     cs = lib.laud_channel_skip_conv
     assert cs(vp(FAKE), big, C.byref(p), vp(FAKE), 4, vp(FAKE), vp(FAKE), 1 << 40, None) == B.ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: --gpus N with N > 1 exits with a message before touching any GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
