@@ -28,6 +28,11 @@
  *     default stream) and never synchronises.  Data-dependent counts stay on the device.
  *   - Return value: LAUD_OK or a negative laud_status.  Arguments are validated on the
  *     host before anything is launched; on error nothing has been launched.
+ *   - Threads: entry points may be called from several host threads at once as long as the calls
+ *     use different workspaces (and, for in-place calls, different feature maps).  The library
+ *     keeps no state between calls except (a) idempotent per-kernel launch attributes, requested on a
+ *     kernel's first launch per device or all at once by laud_init(); (b) the optional stage-timing
+ *     collector (laud_stage_timing_*), which is NOT re-entrant.  No environment variable is read.
  */
 #ifndef LAUD_H
 #define LAUD_H
@@ -83,6 +88,13 @@ const char* laud_status_string(int status);
 
 /* Library ABI version (increments when a signature changes). */
 int laud_abi_version(void);
+
+/*
+ * Optional one-time set-up for the CURRENT device: requests the launch attributes of every kernel (large
+ * dynamic LDS), so that no first call has to do it -- e.g. inside a stream capture.  Allocates nothing, launches nothing; may be
+ * called again (per device, from any thread).  Entry points work without it.
+ */
+int laud_init(void);
 
 /*
  * Workspace bytes an entry point needs for the given shapes.  `op` is a laud_op; `p` may be

@@ -22,7 +22,8 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_channel_skip_conv", "laud_masker_dyn_bottleneck", "laud_channel_masker", "laud_channel_masker_workspace", "laud_dyn_bottleneck_unfused",
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
-           "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name"]
+           "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name",
+           "laud_init"]
 STAGE_COUNT = 13
 
 
@@ -75,6 +76,8 @@ def load() -> C.CDLL:
     lib.laud_gather_patches.argtypes = [vp, Fmap, i32, i32, vp, vp, vp, vp]
     lib.laud_dyn_bottleneck.restype = i32
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
+    lib.laud_init.restype = i32
+    lib.laud_init.argtypes = []
     lib.laud_dyn_group_se_bottleneck.restype = i32
     lib.laud_dyn_group_se_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), C.POINTER(GroupSE), i32, vp, vp, vp, vp,
                                                  sz, vp]
@@ -198,6 +201,10 @@ def laud_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws)
     wp, wb = _ws_args(ws)
     _check(load().laud_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
                                       wp, wb, _stream()), "laud_dyn_bottleneck")
+
+
+def laud_init() -> None:
+    _check(load().laud_init(), "laud_init")
 
 
 def make_group_se(group_width: int, w_se1=None, b_se1=None, w_se2=None, b_se2=None) -> GroupSE:

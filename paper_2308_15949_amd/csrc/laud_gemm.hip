@@ -35,8 +35,7 @@
 #include "laud_common.h"
 
 #include <algorithm>
-#include <cstdio>
-#include <cstdlib>
+#include <atomic>
 
 namespace laud {
 
@@ -780,25 +779,31 @@ __global__ __launch_bounds__(256) void k_copy_inactive(const uint4* __restrict__
 // ------------------------------------------------------------------------------------------------
 struct Tile { int bm, bn, waves; };
 
-// Tile choice.  LAUD_TILE=BMxBNxWAVES (64x64x4, 64x128x4, 128x128x4, 64x128x8, 128x128x8) overrides it
-// for tuning runs.
+// Tile choice: a function of the shapes alone.
 static Tile pick_tile(int ncols, long long total_rows) {
-  static Tile env = {-1, 0, 0};
-  if (env.bm < 0) {
-    env = {0, 0, 0};
-    if (const char* e = std::getenv("LAUD_TILE")) {
-      int bm = 0, bn = 0, w = 4;
-      const int got = std::sscanf(e, "%dx%dx%d", &bm, &bn, &w);
-      const bool ok4 = (bm == 64 && bn == 64) || (bm == 64 && bn == 128) || (bm == 128 && bn == 128);
-      const bool ok8 = (bm == 64 && bn == 128) || (bm == 128 && bn == 128) || (bm == 64 && bn == 256) ||
-                       (bm == 128 && bn == 256);
-      if (got >= 2 && ((w == 4 && ok4) || (w == 8 && ok8))) env = {bm, bn, w};
-    }
-  }
-  if (env.bm > 0) return env;
   if (ncols < 128) return {64, 64, 4};
   // eight waves hide each other's LDS and load stalls; the large tile needs enough rows to fill the chip
   return total_rows >= 8192 ? Tile{128, 128, 8} : Tile{64, 128, 8};
+}
+
+// More than 64 KB of dynamic LDS has to be requested once per kernel and device.  The request is idempotent, so
+// threads that race on a first call only repeat it; laud_init() makes it for every kernel up front (so that no
+// first call falls inside a stream capture).
+template <int MODE, typename ET, int BM, int BN, int WGN>
+static int gemm_request_lds() {
+  static std::atomic<unsigned> done{0};  // one bit per device ordinal (ordinals >= 32 repeat the request)
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return LAUD_ERR_HIP;
+  const unsigned bit = dev >= 0 && dev < 32 ? 1u << dev : 0u;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return LAUD_OK;
+  constexpr int kStages = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
+  constexpr int kStaging = BM * (BN * 4 + 32);  // fp32 tile the epilogue transposes through
+  constexpr int kLds = kStages > kStaging ? kStages : kStaging;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN, WGN>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds + (MODE == M_DENSE1 ? 4096 * 4 : 0)) != hipSuccess)
+    return LAUD_ERR_HIP;
+  done.fetch_or(bit, std::memory_order_release);
+  return LAUD_OK;
 }
 
 template <int MODE, typename ET, int BM, int BN, int WGN>
@@ -816,13 +821,7 @@ static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream
   constexpr int kStages = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
   constexpr int kStaging = BM * (BN * 4 + 32);  // fp32 tile the epilogue transposes through
   constexpr int kLds = kStages > kStaging ? kStages : kStaging;
-  static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be requested once per kernel
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<MODE, ET, BM, BN, WGN>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds + (MODE == M_DENSE1 ? 4096 * 4 : 0)) != hipSuccess)
-      return LAUD_ERR_HIP;
-    attr_set = true;
-  }
+  if (gemm_request_lds<MODE, ET, BM, BN, WGN>() != LAUD_OK) return LAUD_ERR_HIP;
   const int lds = kLds + ((MODE == M_DENSE1 && a.wmask) ? a.K * 4 : 0);  // + masker weights
   hipLaunchKernelGGL((k_gemm<MODE, ET, BM, BN, WGN>), grid, dim3(128 * WGN), lds, st, a);
   return check_launch();
@@ -832,14 +831,36 @@ template <int MODE, typename ET>
 static int launch_gemm_e(const GemmArgs& a, long long cap_rows, int nsamples, hipStream_t st) {
   const Tile t = pick_tile(a.Ncols, cap_rows * (MODE == M_CONV1 || (MODE >= M_CS1 && MODE <= M_CS3) ? nsamples : 1));
   if (t.waves == 8) {
-    if (t.bn == 256 && t.bm == 128) return launch_gemm_t<MODE, ET, 128, 256, 4>(a, cap_rows, nsamples, st);
-    if (t.bn == 256) return launch_gemm_t<MODE, ET, 64, 256, 4>(a, cap_rows, nsamples, st);
     if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128, 4>(a, cap_rows, nsamples, st);
     return launch_gemm_t<MODE, ET, 64, 128, 4>(a, cap_rows, nsamples, st);
   }
-  if (t.bm == 128) return launch_gemm_t<MODE, ET, 128, 128, 2>(a, cap_rows, nsamples, st);
-  if (t.bn == 128) return launch_gemm_t<MODE, ET, 64, 128, 2>(a, cap_rows, nsamples, st);
   return launch_gemm_t<MODE, ET, 64, 64, 2>(a, cap_rows, nsamples, st);
+}
+
+// The LDS requests of every tile a mode can be launched with, for both element types.
+template <int MODE>
+static int gemm_request_lds_mode() {
+  int rc = LAUD_OK;
+  auto keep = [&rc](int r) { if (r != LAUD_OK) rc = r; };
+  keep(gemm_request_lds<MODE, bf16_t, 64, 64, 2>());
+  keep(gemm_request_lds<MODE, float, 64, 64, 2>());
+  if constexpr (MODE != M_G2) {
+    keep(gemm_request_lds<MODE, bf16_t, 64, 128, 4>());
+    keep(gemm_request_lds<MODE, float, 64, 128, 4>());
+    keep(gemm_request_lds<MODE, bf16_t, 128, 128, 4>());
+    keep(gemm_request_lds<MODE, float, 128, 128, 4>());
+  }
+  return rc;
+}
+template <int... MODES>
+static int gemm_request_lds_modes() {
+  int rc = LAUD_OK;
+  ((rc = (gemm_request_lds_mode<MODES>() != LAUD_OK ? LAUD_ERR_HIP : rc)), ...);
+  return rc;
+}
+int gemm_init_device() {
+  return gemm_request_lds_modes<M_CONV1, M_CONV2, M_CONV3, M_CS1, M_CS2, M_CS3, M_DENSE1, M_U1, M_U2, M_U3, M_SD1, M_SD2,
+                                M_SD3, M_G2>();
 }
 
 template <int MODE>
@@ -854,9 +875,24 @@ static int launch_gemm(int dtype, const GemmArgs& a, long long cap_rows, int nsa
 
 // The kernels address an operand through a buffer descriptor with 32-bit byte offsets and keep the upper
 // half of that range for "reads as zero": one operand (activations of a layer, its weights) has to stay
-// below 2 GiB, with a little room for the tap offsets.
-static bool operand_too_big(long long rows, long long row_elems, int dtype) {
-  return (unsigned long long)rows * (unsigned long long)row_elems * elem_bytes(dtype) >= 0x7f000000ull;
+// below 2 GiB, including the distance the 3x3's descriptor is moved back by (one row and one pixel, `tap_rowlen`
+// pixels per row) and the same distance a tap can reach forward.
+static bool operand_too_big(long long rows, long long row_elems, int dtype, long long tap_rowlen = 0) {
+  const unsigned long long eb = elem_bytes(dtype);
+  const unsigned long long shift = tap_rowlen > 0 ? (unsigned long long)(tap_rowlen + 1) * row_elems * eb : 0;
+  return (unsigned long long)rows * (unsigned long long)row_elems * eb + 2 * shift >= 0x7f000000ull;
+}
+
+// 16-byte loads and stores need 16-byte aligned bases.
+static bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+static bool block_params_misaligned(const laud_bottleneck* p) {
+  return misaligned16(p->w1) || misaligned16(p->w2) || misaligned16(p->w3);
+}
+// two ranges of `bytes` bytes that are neither identical nor disjoint
+static bool partial_overlap(const void* x, const void* out, size_t bytes_x, size_t bytes_out) {
+  const char *a = (const char*)x, *b = (const char*)out;
+  if (a == b) return false;
+  return (a < b && a + bytes_x > b) || (b < a && b + bytes_out > a);
 }
 
 static int validate_block(const void* x, const laud_fmap& fx, const laud_bottleneck* p, const void* out) {
@@ -866,14 +902,12 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   if (p->c_in <= 0 || p->c_mid <= 0 || p->c_out <= 0 || p->c_in != fx.C) return LAUD_ERR_INVALID_ARG;
   if (p->c_out != p->c_in) return LAUD_ERR_UNSUPPORTED;
   if (p->c_in % 8 || p->c_mid % 8) return LAUD_ERR_UNSUPPORTED;
+  if (misaligned16(x) || misaligned16(out) || block_params_misaligned(p)) return LAUD_ERR_UNSUPPORTED;
   if ((long long)fx.N * fx.H * fx.W > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
-  if (operand_too_big((long long)fx.N * fx.H * fx.W, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype))
+  if (operand_too_big((long long)fx.N * fx.H * fx.W, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype, fx.W))
     return LAUD_ERR_UNSUPPORTED;
-  if (x != out) {  // partial overlap is not allowed
-    const size_t bytes = (size_t)fx.N * fx.H * fx.W * fx.C * elem_bytes(fx.dtype);
-    const char *a = (const char*)x, *b = (const char*)out;
-    if ((a < b && a + bytes > b) || (b < a && b + bytes > a)) return LAUD_ERR_INVALID_ARG;
-  }
+  const size_t bytes = (size_t)fx.N * fx.H * fx.W * fx.C * elem_bytes(fx.dtype);
+  if (partial_overlap(x, out, bytes, bytes)) return LAUD_ERR_INVALID_ARG;
   return LAUD_OK;
 }
 
@@ -1216,7 +1250,10 @@ extern "C" int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bo
   const int Ho = (fx.H - 1) / stride + 1, Wo = (fx.W - 1) / stride + 1;  // 3x3 pad 1 and 1x1 pad 0 agree on this
   const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
   if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
-  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype, fx.W)) return LAUD_ERR_UNSUPPORTED;
+  if (misaligned16(x) || misaligned16(out) || misaligned16(w_sc) || block_params_misaligned(p)) return LAUD_ERR_UNSUPPORTED;
+  if (partial_overlap(x, out, (size_t)npix * fx.C * elem_bytes(fx.dtype), (size_t)nout * p->c_out * elem_bytes(fx.dtype)))
+    return LAUD_ERR_INVALID_ARG;
   if (!ws || ws_bytes < laud_static_bottleneck_workspace(fx, p, stride)) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -1282,7 +1319,10 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
   if ((size_t)Hp * Wp > 60000) return LAUD_ERR_UNSUPPORTED;  // per-sample patch mask lives in LDS
   const long long npix = (long long)fx.N * fx.H * fx.W, nout = (long long)fx.N * Ho * Wo;
   if (npix > 0x7fffffffLL / 2) return LAUD_ERR_UNSUPPORTED;
-  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype)) return LAUD_ERR_UNSUPPORTED;
+  if (operand_too_big(npix, p->c_in > p->c_mid ? p->c_in : p->c_mid, fx.dtype, fx.W)) return LAUD_ERR_UNSUPPORTED;
+  if (misaligned16(x) || misaligned16(out) || misaligned16(w_sc) || block_params_misaligned(p)) return LAUD_ERR_UNSUPPORTED;
+  if (partial_overlap(x, out, (size_t)npix * fx.C * elem_bytes(fx.dtype), (size_t)nout * p->c_out * elem_bytes(fx.dtype)))
+    return LAUD_ERR_INVALID_ARG;
   int rc;
   if (e && (rc = validate_group_se(p, e, fx)) != LAUD_OK) return rc;
   const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, stride);
@@ -1381,4 +1421,12 @@ extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bo
   a.K = p->c_mid; a.ldw = p->c_mid; a.Ncols = p->c_out; a.lda = p->c_mid; a.ldo = p->c_out;
   a.relu = p->relu_out ? 1 : 0;
   return launch_gemm<M_CS3>(fx.dtype, a, hw, fx.N, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// one-time set-up
+// ------------------------------------------------------------------------------------------------
+extern "C" int laud_init(void) {
+  clear_stale_error();
+  return gemm_init_device();
 }

@@ -30,7 +30,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == sorted(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert L.abi_version() == 2
+    assert L.abi_version() == 3
     assert L.status_string(0) == "LAUD_OK"
     for code in (-1, -2, -3, -4):
         assert L.status_string(code).startswith("LAUD_ERR_")
@@ -259,3 +259,44 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "one GPU" in (r.stderr + r.stdout)
+
+
+def test_alignment_overlap_and_operand_range_are_checked_on_the_host(lib):
+    """16-byte loads/stores need aligned bases; partial overlap of x and out is rejected on every block path;
+    the 3x3's descriptor shift counts towards the 2 GiB operand limit."""
+    vp = C.c_void_p
+    fx = B.Fmap(2, 8, 8, 64, B.F32)
+    p = _bn()
+    st = None
+    need = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, p, 2)
+    d = lib.laud_dyn_bottleneck
+    assert d(vp(FAKE + 8), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE + 8), vp(FAKE), need, st) == B.ERR_UNSUPPORTED
+    assert d(vp(FAKE), fx, C.byref(p), 2, vp(FAKE), vp(FAKE), vp(FAKE + (1 << 20) + 4), vp(FAKE), need, st) == B.ERR_UNSUPPORTED
+    pm = _bn()
+    pm.w2 = FAKE + 2
+    assert d(vp(FAKE), fx, C.byref(pm), 2, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), need, st) == B.ERR_UNSUPPORTED
+    # static / dynamic projection blocks: out [2,4,4,128] f32 = 16 KiB, x [2,8,8,64] f32 = 32 KiB
+    pw = _bn(64, 16, 128)
+    sb = lib.laud_static_bottleneck
+    needs = lib.laud_static_bottleneck_workspace(fx, C.byref(pw), 2)
+    far = vp(FAKE + (1 << 20))
+    assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, vp(FAKE + 1024), vp(FAKE), needs, st) == B.ERR_INVALID_ARG  # out inside x
+    assert sb(vp(FAKE + 1024), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, vp(FAKE), vp(FAKE), needs, st) == B.ERR_INVALID_ARG  # x starts inside out
+    assert sb(vp(FAKE), fx, C.byref(pw), vp(FAKE + 4), vp(FAKE), vp(FAKE), 2, far, vp(FAKE), needs, st) == B.ERR_UNSUPPORTED       # shortcut weights misaligned
+    dp = lib.laud_dyn_projection_bottleneck
+    needp = lib.laud_dyn_projection_workspace(fx, C.byref(pw), 2)
+    assert dp(vp(FAKE), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), vp(FAKE + 2048), vp(FAKE), needp, st) == B.ERR_INVALID_ARG
+    assert dp(vp(FAKE + 8), fx, C.byref(pw), vp(FAKE), vp(FAKE), vp(FAKE), 2, 2, vp(FAKE), vp(FAKE), far, vp(FAKE), needp, st) == B.ERR_UNSUPPORTED
+    # a very wide map: N*H*W*C*2 bytes alone fits below the limit, with twice the (W+1)-pixel tap shift it does not
+    wide = B.Fmap(1, 2, 130000, 4096, B.BF16)
+    pwide = _bn(4096, 64, 4096)
+    assert 2 * 130000 * 4096 * 2 < 0x7f000000 < 2 * 130000 * 4096 * 2 + 2 * 130001 * 4096 * 2
+    assert d(vp(FAKE), wide, C.byref(pwide), 1, vp(FAKE), vp(FAKE), vp(FAKE), vp(FAKE), 1 << 40, st) == B.ERR_UNSUPPORTED
+
+
+def test_no_environment_variable_is_read():
+    """The launch path is a function of its arguments alone."""
+    for name in os.listdir(os.path.join(ROOT, "paper_2308_15949_amd", "csrc")):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(ROOT, "paper_2308_15949_amd", "csrc", name)) as f:
+                assert "getenv" not in f.read(), name
