@@ -32,7 +32,8 @@
  *     use different workspaces (and, for in-place calls, different feature maps).  The library
  *     keeps no state between calls except (a) idempotent per-kernel launch attributes, requested on a
  *     kernel's first launch per device or all at once by laud_init(); (b) the optional stage-timing
- *     collector (laud_stage_timing_*), which is NOT re-entrant.  No environment variable is read.
+ *     collector (laud_stage_timing_*), which is NOT re-entrant; (c) the fixed scratch array of
+ *     laud_dyn_bottleneck_noalloc, shared by all calls on one GPU.  No environment variable is read.
  */
 #ifndef LAUD_H
 #define LAUD_H
@@ -49,7 +50,9 @@ typedef enum {
   LAUD_ERR_INVALID_ARG = -1, /* null pointer, non-positive dim, S not dividing H/W, D not dividing c_mid */
   LAUD_ERR_UNSUPPORTED = -2, /* dtype/shape outside what the kernels cover (e.g. channels % 8 != 0) */
   LAUD_ERR_WORKSPACE = -3,   /* workspace missing or smaller than laud_workspace_size() */
-  LAUD_ERR_HIP = -4          /* a HIP launch failed */
+  LAUD_ERR_HIP = -4,         /* a HIP launch failed */
+  LAUD_ERR_SCRATCH_LIMIT = -5 /* laud_dyn_bottleneck_noalloc: the shapes need more scratch memory than the
+                                 library's fixed LAUD_NOALLOC_SCRATCH_BYTES; use laud_dyn_bottleneck */
 } laud_status;
 
 typedef enum { LAUD_F32 = 0, LAUD_BF16 = 1 } laud_dtype;
@@ -91,7 +94,8 @@ int laud_abi_version(void);
 
 /*
  * Optional one-time set-up for the CURRENT device: requests the launch attributes of every kernel (large
- * dynamic LDS), so that no first call has to do it -- e.g. inside a stream capture.  Allocates nothing, launches nothing; may be
+ * dynamic LDS) and resolves the device address of the allocation-free entry point's scratch array, so that
+ * no first call has to do it -- e.g. inside a stream capture.  Allocates nothing, launches nothing; may be
  * called again (per device, from any thread).  Entry points work without it.
  */
 int laud_init(void);
@@ -157,6 +161,22 @@ int laud_gather_patches(const void* x, laud_fmap fx, int S, int halo,
 int laud_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
                         const int32_t* idx, const int32_t* count, void* out,
                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * laud_dyn_bottleneck for callers that cannot allocate or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the scratch activations (dilated pixel list, h1, h2) live in a fixed array of
+ * LAUD_NOALLOC_SCRATCH_BYTES in the library's device image (one copy per GPU, held until the process ends)
+ * instead of a caller workspace.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine).  Shapes whose laud_workspace_size(LAUD_OP_DYN_BOTTLENECK, ...) exceeds LAUD_NOALLOC_SCRATCH_BYTES
+ * return LAUD_ERR_SCRATCH_LIMIT (e.g. one 56 x 56 x 256 float32 image with c_mid 64 needs 1.6 MB; batch 8 of the
+ * bf16 stage-3 map 14 x 14 x 1024 with c_mid 256 needs 1.6 MB).  All calls on one GPU share the array, which keeps
+ * the last call's contents: calls that overlap in time on one GPU (different streams or threads) race and must
+ * be serialised by the caller; nothing in it needs clearing between calls.
+ */
+#define LAUD_NOALLOC_SCRATCH_BYTES (16u << 20)
+int laud_dyn_bottleneck_noalloc(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                                const int32_t* idx, const int32_t* count, void* out, void* stream);
 
 /* What a group-convolution / squeeze-and-excitation bottleneck adds to laud_bottleneck (the RegNetY
  * backbones of Sec. 4; Sec. 3.2 states that the dynamic block carries over to group convolutions). */

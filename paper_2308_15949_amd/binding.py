@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(HERE, "liblaud.so")
 
 F32, BF16 = 0, 1
 OP_MASK_GEN, OP_COMPACT, OP_GATHER, OP_DYN_BOTTLENECK, OP_CHANNEL_SKIP = range(5)
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_SCRATCH_LIMIT = 0, -1, -2, -3, -4, -5
+NOALLOC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "laud_mask_gen",
            "laud_layer_skip_compact", "laud_gather_patches", "laud_dyn_bottleneck",
@@ -23,7 +24,7 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
            "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name",
-           "laud_init"]
+           "laud_init", "laud_dyn_bottleneck_noalloc"]
 STAGE_COUNT = 13
 
 
@@ -78,6 +79,8 @@ def load() -> C.CDLL:
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
     lib.laud_init.restype = i32
     lib.laud_init.argtypes = []
+    lib.laud_dyn_bottleneck_noalloc.restype = i32
+    lib.laud_dyn_bottleneck_noalloc.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp]
     lib.laud_dyn_group_se_bottleneck.restype = i32
     lib.laud_dyn_group_se_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), C.POINTER(GroupSE), i32, vp, vp, vp, vp,
                                                  sz, vp]
@@ -205,6 +208,11 @@ def laud_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws)
 
 def laud_init() -> None:
     _check(load().laud_init(), "laud_init")
+
+
+def laud_dyn_bottleneck_noalloc(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out) -> None:
+    _check(load().laud_dyn_bottleneck_noalloc(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
+                                              _stream()), "laud_dyn_bottleneck_noalloc")
 
 
 def make_group_se(group_width: int, w_se1=None, b_se1=None, w_se2=None, b_se2=None) -> GroupSE:

@@ -51,6 +51,8 @@ extern "C" const char* laud_status_string(int status) {
     case LAUD_ERR_UNSUPPORTED: return "LAUD_ERR_UNSUPPORTED: dtype or shape outside what the kernels cover";
     case LAUD_ERR_WORKSPACE: return "LAUD_ERR_WORKSPACE: workspace missing or too small";
     case LAUD_ERR_HIP: return "LAUD_ERR_HIP: kernel launch failed";
+    case LAUD_ERR_SCRATCH_LIMIT:
+      return "LAUD_ERR_SCRATCH_LIMIT: shapes need more scratch than the allocation-free entry point's fixed array";
     default: return "LAUD: unknown status";
   }
 }

@@ -1424,9 +1424,48 @@ extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bo
 }
 
 // ------------------------------------------------------------------------------------------------
-// one-time set-up
+// one-time set-up and the allocation-free entry point
 // ------------------------------------------------------------------------------------------------
+// Scratch memory of laud_dyn_bottleneck_noalloc: a fixed array in the library's device image instead of a
+// caller workspace.  Every GPU the library runs on holds its own copy at its own address until the process ends.
+static __device__ __align__(256) unsigned char scratch[LAUD_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+// Device address of `scratch` per device ordinal.  In host code the array's name is only a handle for
+// hipGetSymbolAddress, never an address a kernel may receive.
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Resolves (once per device, with that device current) and returns the current device's scratch array.
+int scratch_of_current_device(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LAUD_ERR_HIP;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LAUD_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // threads racing here store the same address
+  }
+  *out = ptr;
+  return LAUD_OK;
+}
+}  // namespace
+
 extern "C" int laud_init(void) {
   clear_stale_error();
+  void* ptr = nullptr;
+  int rc = scratch_of_current_device(&ptr);
+  if (rc != LAUD_OK) return rc;
   return gemm_init_device();
+}
+
+extern "C" int laud_dyn_bottleneck_noalloc(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
+                                           const int32_t* idx, const int32_t* count, void* out, void* stream) {
+  if (!p || !valid_fmap(fx) || p->c_mid <= 0) return LAUD_ERR_INVALID_ARG;
+  const size_t need = dyn_ws_layout(fx, p->c_mid).bytes;
+  if (need > (size_t)LAUD_NOALLOC_SCRATCH_BYTES) return LAUD_ERR_SCRATCH_LIMIT;
+  void* ptr = nullptr;
+  const int rc = scratch_of_current_device(&ptr);
+  if (rc != LAUD_OK) return rc;
+  // Nothing in this workspace has to start at zero: every region is written before it is read within the call.
+  return run_dyn_block(x, fx, p, nullptr, S, idx, count, out, ptr, (size_t)LAUD_NOALLOC_SCRATCH_BYTES, stream);
 }
