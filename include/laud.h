@@ -358,6 +358,17 @@ int laud_stage_timing_enable(int on);
 int laud_stage_timing_read(double* total_ms, int64_t* launches);
 const char* laud_stage_name(int stage);
 
+/*
+ * Achievable-peak probes (measurement aids, not part of the paper's method): the denominators a roofline fraction
+ * can be read against besides the published peaks.  laud_probe_mfma launches `blocks` workgroups of 8 waves that
+ * each issue 4*iters MFMAs (32x32x16 bf16, or the same FLOPs as 32x32x2 float32 steps) on register operands and
+ * stores the FLOPs of the launch in *flops (host, may be NULL); sink is a device word nobody reads.
+ * laud_probe_copy copies `bytes` (a multiple of 16, both pointers 16-byte aligned) with a plain grid-stride kernel.
+ * Both only enqueue on `stream`; the caller times them with events.
+ */
+int laud_probe_mfma(int dtype, int iters, int blocks, double* flops, float* sink, void* stream);
+int laud_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

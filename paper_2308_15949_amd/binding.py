@@ -24,7 +24,7 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
            "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name",
-           "laud_init", "laud_dyn_bottleneck_noalloc"]
+           "laud_init", "laud_dyn_bottleneck_noalloc", "laud_probe_mfma", "laud_probe_copy"]
 STAGE_COUNT = 13
 
 
@@ -77,6 +77,10 @@ def load() -> C.CDLL:
     lib.laud_gather_patches.argtypes = [vp, Fmap, i32, i32, vp, vp, vp, vp]
     lib.laud_dyn_bottleneck.restype = i32
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
+    lib.laud_probe_mfma.restype = i32
+    lib.laud_probe_mfma.argtypes = [i32, i32, i32, C.POINTER(C.c_double), vp, vp]
+    lib.laud_probe_copy.restype = i32
+    lib.laud_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.laud_init.restype = i32
     lib.laud_init.argtypes = []
     lib.laud_dyn_bottleneck_noalloc.restype = i32
@@ -204,6 +208,17 @@ def laud_dyn_bottleneck(x, fx: Fmap, p: Bottleneck, S: int, idx, count, out, ws)
     wp, wb = _ws_args(ws)
     _check(load().laud_dyn_bottleneck(_ptr(x), fx, C.byref(p), int(S), _ptr(idx), _ptr(count), _ptr(out),
                                       wp, wb, _stream()), "laud_dyn_bottleneck")
+
+
+def laud_probe_mfma(dtype: int, iters: int, blocks: int, sink) -> float:
+    """Enqueues the bare MFMA loop; returns the FLOPs of the launch."""
+    fl = C.c_double(0.0)
+    _check(load().laud_probe_mfma(int(dtype), int(iters), int(blocks), C.byref(fl), _ptr(sink), _stream()), "laud_probe_mfma")
+    return float(fl.value)
+
+
+def laud_probe_copy(src, dst, nbytes: int) -> None:
+    _check(load().laud_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream()), "laud_probe_copy")
 
 
 def laud_init() -> None:

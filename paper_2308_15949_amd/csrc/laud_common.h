@@ -140,6 +140,29 @@ constexpr int kSeMaxC = 4096, kSeMaxHidden = 1024;  // widest layer / SE hidden 
 int launch_se(int dtype, int N, int pps, int SS, int C, const laud_group_se* e, void* h2, const int32_t* idx,
               const int32_t* count, float* scratch, long long cap_rows, hipStream_t stream);
 
+// conv2 -> conv3 -> residual add in one kernel (laud_tail.hip), for the shapes tail_supported() names.
+struct TailArgs {
+  const void* h1;        // [pixels of the input grid][MID] bf16, conv1's output at pixel positions
+  const void* w2;        // [MID][3][3][MID]
+  const void* w3;        // [cout][MID]
+  const float* s2; const float* t2;  // [MID]
+  const float* s3; const float* t3;  // [cout]
+  const void* res;       // residual [output pixels][cout] (x, or the shortcut already in `out`)
+  void* out;             // [output pixels][cout]; may alias res
+  const int32_t* count;  // device: number of active patches
+  const int32_t* list;   // device: ascending active patch ids
+  int H, W;              // input grid of h1
+  int S;                 // patch size on the output grid
+  int stride, Ho, Wo;    // spatial stride of the 3x3 and the output grid (stride 1: Ho = H, Wo = W)
+  int cout;
+  int relu;
+};
+
+bool tail_supported(int dtype, int c_mid, int c_out);
+int tail_init_device();
+// cap_rows: upper bound of the number of active pixels (grid size); the count itself stays on the device
+int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t stream);
+
 // Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
 extern bool g_stage_timing_on;
 void stage_mark(int stage, hipStream_t stream, bool begin);

@@ -997,6 +997,23 @@ static int launch_conv2(int dtype, GemmArgs a, const laud_group_se* e, long long
                             : launch_gemm_t<M_G2, float, 64, 64, 2>(a, cap_rows, 1, st);
 }
 
+// conv2 -> conv3 -> residual add as one kernel where laud_tail.hip covers the shape (h2 stays in LDS).
+// Returns 1 when that kernel was launched (*rc = its status), 0 when the caller has to run the two GEMMs.
+static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e, const void* h1, const void* res,
+                    void* out, const int32_t* idx, const int32_t* count, int H, int W, int S, int stride, int Ho, int Wo,
+                    long long cap_rows, hipStream_t st, int* rc) {
+#ifdef LAUD_TAIL_OFF
+  return 0;
+#endif
+  if (e || !tail_supported(dtype, p->c_mid, p->c_out)) return 0;
+  TailArgs t{};
+  t.h1 = h1; t.w2 = p->w2; t.w3 = p->w3; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
+  t.res = res; t.out = out; t.count = count; t.list = idx; t.H = H; t.W = W; t.S = S; t.stride = stride;
+  t.Ho = Ho; t.Wo = Wo; t.cout = p->c_out; t.relu = p->relu_out ? 1 : 0;
+  *rc = launch_tail(t, cap_rows, st);
+  return 1;
+}
+
 // The spatially adaptive block on an index list; `e` adds the group convolution / SE variant (or is null).
 static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, const laud_group_se* e, int S,
                          const int32_t* idx, const int32_t* count, void* out, void* ws, size_t ws_bytes,
@@ -1046,6 +1063,7 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+  if (try_tail(fx.dtype, p, e, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, st, &rc)) return rc;
   // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
@@ -1111,6 +1129,7 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
     if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
   }
   a.wmask = nullptr; a.proj = nullptr;
+  if (try_tail(fx.dtype, p, nullptr, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, st, &rc)) return rc;
   // conv2 and conv3 exactly as in laud_dyn_bottleneck
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
@@ -1360,6 +1379,7 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
   a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+  if (try_tail(fx.dtype, p, e, h1, out, out, idx, count, fx.H, fx.W, S, stride, Ho, Wo, nout, st, &rc)) return rc;
   // conv2: strided 3x3 at the active output pixels -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
@@ -1455,7 +1475,9 @@ extern "C" int laud_init(void) {
   void* ptr = nullptr;
   int rc = scratch_of_current_device(&ptr);
   if (rc != LAUD_OK) return rc;
-  return gemm_init_device();
+  rc = gemm_init_device();
+  if (rc != LAUD_OK) return rc;
+  return tail_init_device();
 }
 
 extern "C" int laud_dyn_bottleneck_noalloc(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
