@@ -143,8 +143,7 @@ int launch_se(int dtype, int N, int pps, int SS, int C, const laud_group_se* e, 
 // conv2 -> conv3 -> residual add in one kernel (laud_tail.hip), for the shapes tail_supported() names.
 struct TailArgs {
   const void* h1;        // [pixels of the input grid][MID] bf16, conv1's output at pixel positions
-  const void* w2;        // [MID][3][3][MID]
-  const void* w3;        // [cout][MID]
+  const void* wpacked;   // w2 and w3 in MFMA fragment order (launch_tail_pack), tail_packed_bytes() bytes
   const float* s2; const float* t2;  // [MID]
   const float* s3; const float* t3;  // [cout]
   const void* res;       // residual [output pixels][cout] (x, or the shortcut already in `out`)
@@ -160,6 +159,9 @@ struct TailArgs {
 
 bool tail_supported(int dtype, int c_mid, int c_out);
 int tail_init_device();
+size_t tail_packed_bytes(int c_mid, int c_out);
+// re-orders w2 [c_mid][3][3][c_mid] and w3 [c_out][c_mid] into the order the fused kernel streams them
+int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hipStream_t stream);
 // cap_rows: upper bound of the number of active pixels (grid size); the count itself stays on the device
 int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t stream);
 

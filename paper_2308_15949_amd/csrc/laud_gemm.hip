@@ -911,7 +911,7 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   return LAUD_OK;
 }
 
-struct DynWs { size_t need_counts, pix, h1, h2, blocks, bytes; };
+struct DynWs { size_t need_counts, pix, h1, h2, blocks, wpack, bytes; };
 static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
   DynWs w;
@@ -921,6 +921,8 @@ static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(npix * c_mid * eb, 256);
   w.blocks = o;      o += compact_ws_bytes((long long)npix);  // block counts of a large compaction
+  // weights in MFMA fragment order for the fused conv2 -> conv3 kernel (identity block: c_out = C)
+  w.wpack = o;       o += tail_supported(fx.dtype, c_mid, fx.C) ? tail_packed_bytes(c_mid, fx.C) : 0;
   w.bytes = o;
   return w;
 }
@@ -1001,13 +1003,17 @@ static int launch_conv2(int dtype, GemmArgs a, const laud_group_se* e, long long
 // Returns 1 when that kernel was launched (*rc = its status), 0 when the caller has to run the two GEMMs.
 static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e, const void* h1, const void* res,
                     void* out, const int32_t* idx, const int32_t* count, int H, int W, int S, int stride, int Ho, int Wo,
-                    long long cap_rows, hipStream_t st, int* rc) {
+                    long long cap_rows, void* wpack, hipStream_t st, int* rc) {
 #ifdef LAUD_TAIL_OFF
   return 0;
 #endif
   if (e || !tail_supported(dtype, p->c_mid, p->c_out)) return 0;
+  {
+    StageScope scope(LAUD_STAGE_NEED, st);
+    if ((*rc = launch_tail_pack(p->w2, p->w3, p->c_out, wpack, st)) != LAUD_OK) return 1;
+  }
   TailArgs t{};
-  t.h1 = h1; t.w2 = p->w2; t.w3 = p->w3; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
+  t.h1 = h1; t.wpacked = wpack; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
   t.res = res; t.out = out; t.count = count; t.list = idx; t.H = H; t.W = W; t.S = S; t.stride = stride;
   t.Ho = Ho; t.Wo = Wo; t.cout = p->c_out; t.relu = p->relu_out ? 1 : 0;
   *rc = launch_tail(t, cap_rows, st);
@@ -1063,7 +1069,7 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
-  if (try_tail(fx.dtype, p, e, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, st, &rc)) return rc;
+  if (try_tail(fx.dtype, p, e, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, wsb + L.wpack, st, &rc)) return rc;
   // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
@@ -1129,7 +1135,7 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
     if (check_launch() != LAUD_OK) return LAUD_ERR_HIP;
   }
   a.wmask = nullptr; a.proj = nullptr;
-  if (try_tail(fx.dtype, p, nullptr, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, st, &rc)) return rc;
+  if (try_tail(fx.dtype, p, nullptr, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, wsb + L.wpack, st, &rc)) return rc;
   // conv2 and conv3 exactly as in laud_dyn_bottleneck
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;
@@ -1300,8 +1306,8 @@ extern "C" int laud_static_bottleneck(const void* x, laud_fmap fx, const laud_bo
 }
 
 namespace {
-struct DynProjWs { size_t need_counts, pix, h1, h2, bytes; };
-DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int stride) {
+struct DynProjWs { size_t need_counts, pix, h1, h2, wpack, bytes; };
+DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int c_out, int stride) {
   const size_t eb = elem_bytes(fx.dtype), npix = (size_t)fx.N * fx.H * fx.W;
   const size_t nout = (size_t)fx.N * ((fx.H - 1) / stride + 1) * ((fx.W - 1) / stride + 1);
   DynProjWs w;
@@ -1310,6 +1316,7 @@ DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int stride) {
   w.pix = o;         o += align_up(npix * 4, 256);
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(nout * c_mid * eb, 256);
+  w.wpack = o;       o += tail_supported(fx.dtype, c_mid, c_out) ? tail_packed_bytes(c_mid, c_out) : 0;
   w.bytes = o;
   return w;
 }
@@ -1317,7 +1324,7 @@ DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int stride) {
 
 extern "C" size_t laud_dyn_projection_workspace(laud_fmap fx, const laud_bottleneck* p, int stride) {
   if (!valid_fmap(fx) || !p || p->c_mid <= 0 || (stride != 1 && stride != 2)) return 0;
-  return dyn_proj_ws_layout(fx, p->c_mid, stride).bytes;
+  return dyn_proj_ws_layout(fx, p->c_mid, p->c_out, stride).bytes;
 }
 
 // Dynamic first block of a stage; `e` adds the group convolution / SE variant (or is null).
@@ -1344,7 +1351,7 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
     return LAUD_ERR_INVALID_ARG;
   int rc;
   if (e && (rc = validate_group_se(p, e, fx)) != LAUD_OK) return rc;
-  const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, stride);
+  const DynProjWs L = dyn_proj_ws_layout(fx, p->c_mid, p->c_out, stride);
   if (!ws || ws_bytes < L.bytes) return LAUD_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
@@ -1379,7 +1386,7 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
   a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
-  if (try_tail(fx.dtype, p, e, h1, out, out, idx, count, fx.H, fx.W, S, stride, Ho, Wo, nout, st, &rc)) return rc;
+  if (try_tail(fx.dtype, p, e, h1, out, out, idx, count, fx.H, fx.W, S, stride, Ho, Wo, nout, wsb + L.wpack, st, &rc)) return rc;
   // conv2: strided 3x3 at the active output pixels -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
   a.count = count; a.list = idx; a.K = p->c_mid; a.ldw = 9 * p->c_mid; a.Ncols = p->c_mid;

@@ -38,20 +38,22 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 namespace tail {
 constexpr int kMid = 256;
-constexpr int kBM = 64;                       // pixels per workgroup
+constexpr int kPB = 2;                        // 32-pixel blocks per workgroup (and per wave)
+constexpr int kBM = 32 * kPB;                 // pixels per workgroup
 constexpr int kWaves = 8, kThreads = 512;
-constexpr int kAStage = kBM * 128;            // 8 KB: 64 rows x one 128-byte K slice
-constexpr int kBStage = kMid * 128;           // 32 KB: 256 weight rows x one K slice
-constexpr int kARing = 4, kBRing = 3;
-constexpr int kBOff = 0;                      // weight ring
-constexpr int kAOff = kBRing * kBStage;       // activation ring, later the h2 tile (64 x 512 bytes)
-constexpr int kTabOff = kAOff + kARing * kAStage;
+constexpr int kAStage = kBM * 128;            // one 128-byte K slice of every pixel row
+constexpr int kARing = 4;
+constexpr int kAOff = 0;                      // activation ring
+constexpr int kH2Off = kARing * kAStage;      // h2 tile: kBM pixels x 512 bytes
+constexpr int kTabOff = kH2Off + kBM * kMid * 2;
 constexpr int kKch = kMid / 64;               // K slices per tap (3x3) and per column tile (1x1)
 constexpr int kSl2 = 9 * kKch;                // slices of the 3x3
+constexpr int kWRing = 3;                     // weight slices held / in flight in registers
+constexpr int kSliceChunks = kWaves * 4 * 64; // 16-byte chunks of one packed weight slice (32 KB)
 constexpr unsigned kOob = 0x80000000u;        // offset outside every descriptor: reads as zero
-// float tables in LDS behind the rings: s2, t2 [256], then s3, t3 [cout], then 64 output rows (int)
-// ... then 1 KB that the L2 warm-up loads land in (never read)
-__host__ __device__ constexpr int lds_bytes(int cout) { return kTabOff + (2 * kMid + 2 * cout) * 4 + kBM * 4 + 1024; }
+// float tables in LDS behind the tiles: s2, t2 [256], then s3, t3 [cout], then kBM output rows (int)
+__host__ __device__ constexpr int lds_bytes(int cout) { return kTabOff + (2 * kMid + 2 * cout) * 4 + kBM * 4; }
+__host__ __device__ constexpr size_t packed_bytes(int cout) { return (size_t)(kSl2 + cout / 256 * kKch) * kSliceChunks * 16; }
 }  // namespace tail
 
 // LDS-direct load of 16 bytes per lane: lane l's chunk lands at LDS byte address lds_base + 16*l.
@@ -61,25 +63,14 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff
                : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
                : "memory");
 }
-// 16-byte load into registers the compiler does not track: the caller waits with vm_wait before use.
-__device__ __forceinline__ u32x4 load16_untracked(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff) {
-  u32x4 v;
-  asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(voff), "s"(rsrc), "s"(soff) : "memory");
-  return v;
-}
 template <int N>
 __device__ __forceinline__ void vm_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// the same wait, tied to registers written by load16_untracked so that their uses stay behind it
-template <int N>
-__device__ __forceinline__ void vm_wait_regs(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
-  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
-}
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-__device__ __forceinline__ f32x16 mma_bf16(const uint4& first, const uint4& second, f32x16 acc) {
+__device__ __forceinline__ f32x16 mma_bf16(const u32x4& first, const uint4& second, f32x16 acc) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second),
                                                  acc, 0, 0, 0);
 }
@@ -102,11 +93,34 @@ __device__ __forceinline__ void to_consecutive_channels(float (&v)[16]) {
   }
 }
 
+// Weights in the order the MFMAs consume them: slice b of the weight stream (b < 36: tap b/4, K chunk b%4 of the
+// 3x3; then column tile (b-36)/4, K chunk (b-36)%4 of the last 1x1), wave w, K step kg, lane l hold the 16 bytes
+// W[channel 32w + l%32 (+256*tile)][k = 64*chunk + 16*kg + 8*(l/32) .. +7]: a wave instruction reads 1 KB in a row.
+__global__ __launch_bounds__(256) void k_pack_tail_weights(const uint4* __restrict__ w2, const uint4* __restrict__ w3,
+                                                           uint4* __restrict__ out, int nslices) {
+  using namespace tail;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= nslices * kSliceChunks) return;
+  const int l = idx & 63, kg = (idx >> 6) & 3, w = (idx >> 8) & 7, b = idx >> 11;
+  const int k = kg * 16 + (l >> 5) * 8;  // within the 64-element slice
+  if (b < kSl2) {
+    const int tap = b / kKch, kc = b % kKch, ch = 32 * w + (l & 31);
+    out[idx] = w2[((size_t)(ch * 9 + tap) * kMid + kc * 64 + k) / 8];
+  } else {
+    const int c = b - kSl2, ct = c / kKch, ks = c % kKch, ch = ct * 256 + 32 * w + (l & 31);
+    out[idx] = w3[((size_t)ch * kMid + ks * 64 + k) / 8];
+  }
+}
+
 #ifdef LAUD_TAIL_DBG
 __device__ long long g_tail_dbg[1024 * 64];
 #define TAIL_STAMP(i) do { if (tid == 0 && blockIdx.x < 1024) g_tail_dbg[blockIdx.x * 64 + (i)] = (long long)__builtin_readcyclecounter(); } while (0)
+__device__ long long g_tail_fine[8 * 64];
+// fine stamps: every wave of workgroup 0, slot i (0..63)
+#define TAIL_FINE(i) do { if (blockIdx.x == 0 && lane == 0) g_tail_fine[wave * 64 + (i)] = (long long)__builtin_readcyclecounter(); } while (0)
 #else
 #define TAIL_STAMP(i) do { } while (0)
+#define TAIL_FINE(i) do { } while (0)
 #endif
 
 template <int NCT>  // column tiles of 256 output channels (cout = 256 * NCT)
@@ -114,6 +128,8 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   using namespace tail;
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int COUT = 256 * NCT;
+  constexpr int kNB = kSl2 + NCT * kKch;  // slices in the weight stream
+  constexpr int kAI = kPB / 2;            // LDS-direct instructions per wave and activation slice (8 rows each)
   float* const s_s2 = reinterpret_cast<float*>(smem + kTabOff);
   float* const s_t2 = s_s2 + kMid;
   float* const s_s3 = s_t2 + kMid;
@@ -136,70 +152,31 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   if (slot >= tpx || rt >= ntiles) return;
   const int row0 = rt * kBM;
 
-  const __amdgpu_buffer_rsrc_t w2rs =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w2), 0, (int)kOob, 0x00020000);
-  const __amdgpu_buffer_rsrc_t w3rs =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.w3), 0, (int)kOob, 0x00020000);
-
-  // ---- weight slices: wave w loads (and later multiplies) rows 32w .. 32w+31, four instructions of 8 rows -------
-  // row R = 32w + 8i + lane/8 sits at LDS position lane%8 of its row and must hold chunk (lane%8) ^ f(R),
-  // f(R) = (R&7) ^ ((R>>3)&1) = (lane/8) ^ (i&1)
-  unsigned voffB2[4], voffB3[4];
+  // ---- weight stream: three slices in registers (one in use, two in flight) ------------------------------------
+  typedef const __attribute__((address_space(1))) u32x4* gptr16;
+  const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
+  u32x4 wr[kWRing][4];
+  auto load_W = [&](int buf, int b) __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const unsigned R = 32u * wave + 8u * i + l8;
-    const unsigned c = (unsigned)l7 ^ ((unsigned)l8 ^ (i & 1u));
-    voffB2[i] = R * (9u * kMid * 2u) + c * 16u;
-    voffB3[i] = R * (kMid * 2u) + c * 16u;
-  }
-  const unsigned ldsB = kBOff + wave * 4096;  // this wave's 32 rows inside a weight stage
-  // b = stream index of a weight slice: 0 .. kSl2-1 the 3x3 (tap-major), then the column tiles of the 1x1
-  auto issue_B = [&](int b) __attribute__((always_inline)) {
-    const unsigned base = ldsB + (unsigned)(b % kBRing) * kBStage;
-    if (b < kSl2) {
-      const unsigned soff = (unsigned)((b / kKch) * kMid + (b % kKch) * 64) * 2u;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) dma16(w2rs, voffB2[i], soff, base + i * 1024);
-    } else {
-      const int c = b - kSl2;
-      const unsigned soff = (unsigned)((c / kKch) * 256 * kMid + (c % kKch) * 64) * 2u;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) dma16(w3rs, voffB3[i], soff, base + i * 1024);
-    }
+    for (int kg = 0; kg < 4; ++kg) wr[buf][kg] = wsrc[(size_t)b * kSliceChunks + kg * 64];
   };
-  issue_B(0);
-  issue_B(1);
+#pragma unroll
+  for (int b = 0; b < kWRing; ++b) load_W(b, b);
 
-  // ---- L2 warm-up: every workgroup of an XCD walks w2 and w3 in the same order at the same time, so without help
-  // each slice would be fetched into that XCD's L2 at the moment all of them need it, and all of them would wait
-  // for memory.  Instead the XCD's workgroups touch one 16-byte piece of every 128-byte line up front, in stream
-  // order, sharing the lines among them; the loads land in a spare KB of LDS nobody reads.
-  {
-    constexpr int kLines2 = kSl2 * kMid;           // w2: per slice one line per row
-    constexpr int kLines = kLines2 + COUT * kMid * 2 / 128;
-    const unsigned dummy = (unsigned)(kTabOff + (2 * kMid + 2 * COUT) * 4 + kBM * 4);
-    int base = __builtin_amdgcn_readfirstlane(slot * kThreads + wave * 64);
-    for (int it = 0; it < 8 && base < kLines; ++it, base += tpx * kThreads) {
-      const int L = base + lane;
-      if (base < kLines2) {
-        const unsigned sl = (unsigned)L / kMid, row = (unsigned)L % kMid;
-        dma16(w2rs, row * (9u * kMid * 2u) + sl * 128u, 0u, dummy);
-      } else {
-        dma16(w3rs, (unsigned)(L - kLines2) * 128u, 0u, dummy);
-      }
-    }
-  }
-
-  // ---- per-channel affine tables and output rows -------------------------------------------------------------
+  // ---- per-channel affine tables --------------------------------------------------------------------------------
   for (int i = tid; i < kMid; i += kThreads) { s_s2[i] = a.s2[i]; s_t2[i] = a.t2[i]; }
   for (int i = tid; i < COUT; i += kThreads) { s_s3[i] = a.s3[i]; s_t3[i] = a.t3[i]; }
 
-  // ---- activation rows: lane loads chunk position lane%8 of row 8w + lane/8 ---------------------------------
+  // ---- activation rows: instruction i of wave w loads rows 64i + 8w .. +7, lane l the chunk position l%8 of row
+  // 64i + 8w + l/8; row r keeps chunk c at position c ^ f(r), f(r) = (r&7) ^ ((r>>3)&1) (conflict-free fragment
+  // reads; the swizzle is applied on the global side) -----------------------------------------------------------
   const int sy = a.stride;
   const int Hp = a.Ho / a.S, Wp = a.Wo / a.S;
-  unsigned voffA = 0, amask = 0;
-  {
-    const int r = 8 * wave + l8;
+  unsigned voffA[kAI], amask[kAI];
+#pragma unroll
+  for (int i = 0; i < kAI; ++i) {
+    voffA[i] = 0; amask[i] = 0;
+    const int r = 64 * i + 8 * wave + l8;
     const int rho = row0 + r;
     if (rho < M) {
       const int p = rho / SS, j = rho - p * SS;
@@ -210,12 +187,14 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
       const int y = yo * sy, x = xo * sy;  // centre of the 3x3 on the input grid
       const unsigned pix = (unsigned)(n * a.H * a.W + y * a.W + x);
       const unsigned c = (unsigned)l7 ^ ((unsigned)(l8 & 7) ^ (wave & 1u));
-      voffA = pix * (kMid * 2u) + c * 16u;
+      voffA[i] = pix * (kMid * 2u) + c * 16u;
+      unsigned mk = 0;
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
         const int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
-        if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W) amask |= 1u << t;
+        if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W) mk |= 1u << t;
       }
+      amask[i] = mk;
       if (l7 == 0) s_orow[r] = n * (a.Ho * a.Wo) + yo * a.Wo + xo;
     } else if (l7 == 0) {
       s_orow[r] = -1;
@@ -230,8 +209,11 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     const int tap = s / kKch, kc = s - tap * kKch;
     const int ky = tap / 3, kx = tap - ky * 3;
     const unsigned soff = (unsigned)((ky * a.W + kx) * kMid + kc * 64) * 2u;
-    const unsigned v = ((amask >> tap) & 1u) ? voffA : kOob;
-    dma16(h1rs, v, soff, ldsA + (unsigned)(s & (kARing - 1)) * kAStage);
+#pragma unroll
+    for (int i = 0; i < kAI; ++i) {
+      const unsigned v = (tap < 9 && ((amask[i] >> tap) & 1u)) ? voffA[i] : kOob;  // (slices past the 3x3: zeros)
+      dma16(h1rs, v, soff, ldsA + (unsigned)(s & (kARing - 1)) * kAStage + i * 8192);
+    }
   };
   issue_A(0);
   issue_A(1);
@@ -245,71 +227,63 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     for (int kg = 0; kg < 4; ++kg) swz[kg] = (unsigned)l31 * 128u + (((2u * kg + lhi) ^ f) << 4);
   }
 
-  f32x16 acc[2];
+  f32x16 acc[kPB];
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+  for (int t = 0; t < kPB; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
-  uint4 fw[2], fa[2][2];  // double-buffered fragments: weights, activations of pixel blocks 0 / 1
+  uint4 fa[2][kPB];  // activation fragments of the pixel blocks, read one K step ahead of their MFMAs
   auto read_frags2 = [&](int buf, int s, int kg) __attribute__((always_inline)) {
-    const unsigned char* pb = smem + kBOff + (unsigned)(s % kBRing) * kBStage + wave * 4096 + swz[kg];
     const unsigned char* pa = smem + kAOff + (unsigned)(s & (kARing - 1)) * kAStage + swz[kg];
-    fw[buf] = *reinterpret_cast<const uint4*>(pb);
-    fa[buf][0] = *reinterpret_cast<const uint4*>(pa);
-    fa[buf][1] = *reinterpret_cast<const uint4*>(pa + 4096);
+#pragma unroll
+    for (int t = 0; t < kPB; ++t) fa[buf][t] = *reinterpret_cast<const uint4*>(pa + t * 4096);
   };
 
   // ---- the 3x3 -----------------------------------------------------------------------------------------------
-  // issued so far, in order: B0, B1 (4 loads each), A0, A1, A2 (1 each)
-  vm_wait<1>();  // B0, B1, A0, A1 of this wave have landed
+  vm_wait<0>();  // everything issued so far (weights 0-2, activations 0-2 of this wave) has landed
   lds_wait();    // the tables written above
-  wg_barrier();  // ... and everybody else's; also publishes the tables
+  wg_barrier();  // ... and everybody else's
   TAIL_STAMP(1);
   read_frags2(0, 0, 0);
 
-  // One slice.  VM_SYNC: loads allowed in flight when the next slice's activations are needed (middle of the
-  // slice); VM_B: when the next slice's weights are needed (end of the slice); ISSUE_A / LAST as named.
-  auto slice2 = [&](int s, auto vm_sync, auto vm_b, auto issue_a, auto last) __attribute__((always_inline)) {
-    TAIL_STAMP(2 + s);
+  // Three slices = twelve K steps with static register indices (weight buffer g/4, fragment buffer g%2).
+  // One barrier per slice, in its middle: behind it everyone's activations of the next slice have landed and
+  // everyone is done with the slice before this one, whose stage is refilled (three slices ahead).
+  // Vector-memory operations of a wave in program order, per slice s: A(s+3) x kAI [middle of s], W(s+3) x4 [end
+  // of s].  Needed at the barrier of slice s: A(s+1), issued two slices earlier -- W(s+1), A(s+2), W(s+2) are
+  // younger: 8 + kAI loads.  Activation loads past the last slice are issued all the same (they read as zeros
+  // into stages nobody reads any more) so that the count holds to the end.
+  auto group2 = [&](int s0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int kg = 0; kg < 4; ++kg) {
-      const int cur = kg & 1, nxt = cur ^ 1;
-      if (kg < 3) {
-        read_frags2(nxt, s, kg + 1);
-      } else if (!decltype(last)::value) {
-        vm_wait<decltype(vm_b)::value>();  // own weights of slice s+1 (activations were covered by the barrier)
-        read_frags2(nxt, s + 1, 0);
-      }
+    for (int g = 0; g < 12; ++g) {
+      const int s = s0 + g / 4, kg = g % 4;
+      if (kg == 0) TAIL_STAMP(2 + s);
+      if (kg < 3) read_frags2((g + 1) & 1, s, kg + 1);
+      else if (s + 1 < kSl2) read_frags2((g + 1) & 1, s + 1, 0);
       __builtin_amdgcn_sched_barrier(0);  // the next step's fragment reads stay ahead of this step's MFMAs
-      acc[0] = mma_bf16(fw[cur], fa[cur][0], acc[0]);
-      acc[1] = mma_bf16(fw[cur], fa[cur][1], acc[1]);
+#pragma unroll
+      for (int t = 0; t < kPB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
       __builtin_amdgcn_sched_barrier(0);
       if (kg == 1) {
-        if (!decltype(last)::value) {
-          vm_wait<decltype(vm_sync)::value>();  // own part of the activations of slice s+1
-          wg_barrier();                          // everyone's; and everyone is done with slice s-1
-        }
-        issue_B(s + 2);
-        if (decltype(issue_a)::value) issue_A(s + 3);
+        vm_wait<8 + kAI>();  // own part of the activations of slice s+1
+        wg_barrier();        // everyone's; and everyone is done with slice s-1
+        issue_A(s + 3);
+      }
+      if (kg == 3) {
+        load_W(g / 4, s + kWRing);  // (the stream continues into the last 1x1)
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
-  using std::integral_constant;
-  typedef integral_constant<bool, true> T_;
-  typedef integral_constant<bool, false> F_;
-  for (int s = 0; s < kSl2 - 3; ++s) slice2(s, integral_constant<int, 5>{}, integral_constant<int, 6>{}, T_{}, F_{});
-  slice2(kSl2 - 3, integral_constant<int, 5>{}, integral_constant<int, 5>{}, F_{}, F_{});
-  slice2(kSl2 - 2, integral_constant<int, 4>{}, integral_constant<int, 4>{}, F_{}, F_{});
-  slice2(kSl2 - 1, integral_constant<int, 0>{}, integral_constant<int, 0>{}, F_{}, T_{});
+  for (int s = 0; s < kSl2; s += 3) group2(s);
 
-  // ---- h2 = relu(s2 * acc + t2) -> LDS over the activation ring ----------------------------------------------
+  // ---- h2 = relu(s2 * acc + t2) -> LDS -------------------------------------------------------------------------
   TAIL_STAMP(38);
-  wg_barrier();  // every wave has finished reading the activation ring
   {
     const int cb = wave * 32;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < kPB; ++t) {
       float v[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -326,91 +300,70 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
       // pixel row r, 512 bytes per row; 16-byte chunk c sits at position c ^ (r & 15)
       const unsigned r = 32u * t + l31;
       const unsigned ch = wave * 4u + lhi * 2u;
-      unsigned char* row = smem + kAOff + r * 512u;
+      unsigned char* row = smem + kH2Off + r * 512u;
       *reinterpret_cast<uint4*>(row + ((ch ^ (r & 15u)) << 4)) = c0;
       *reinterpret_cast<uint4*>(row + (((ch + 1u) ^ (r & 15u)) << 4)) = c1;
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;  // the last 1x1 starts from zero
+      __builtin_amdgcn_sched_barrier(0);              // one pixel block at a time (register pressure)
     }
   }
   lds_wait();
   wg_barrier();  // h2 complete
   TAIL_STAMP(39);
 
-  // ---- the last 1x1, column tile by column tile ------------------------------------------------------------------
-  const __amdgpu_buffer_rsrc_t resrs =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.res), 0, (int)kOob, 0x00020000);
-  const int orow0 = s_orow[l31], orow1 = s_orow[32 + l31];
-  const unsigned chan_b = (unsigned)(wave * 32 + lhi * 16) * 2u;  // byte offset of this lane's 16 channels in a tile
-  const unsigned voffR0 = orow0 >= 0 ? (unsigned)orow0 * (COUT * 2u) + chan_b : kOob;
-  const unsigned voffR1 = orow1 >= 0 ? (unsigned)orow1 * (COUT * 2u) + chan_b : kOob;
-  unsigned hswz[2];  // h2 fragment row bases: pixel block t, row lane%32
+  // ---- the last 1x1, column tile by column tile: no activation loads, no barriers ------------------------------
+  int orow[kPB];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) hswz[t] = kAOff + (32u * t + l31) * 512u;
+  for (int t = 0; t < kPB; ++t) orow[t] = s_orow[32 * t + l31];
+  const unsigned hrow = kH2Off + (unsigned)l31 * 512u;  // h2 fragment rows: pixel block t at + t * 32 * 512
   const unsigned hx = (unsigned)(l31 & 15);
-  auto read_frags3 = [&](int buf, int b, int ks, int kg) __attribute__((always_inline)) {
-    const unsigned char* pb = smem + kBOff + (unsigned)(b % kBRing) * kBStage + wave * 4096 + swz[kg];
-    fw[buf] = *reinterpret_cast<const uint4*>(pb);
+  auto read_frags3 = [&](int buf, int ks, int kg) __attribute__((always_inline)) {
     const unsigned c = (unsigned)(ks * 8 + 2 * kg) + lhi;
-    fa[buf][0] = *reinterpret_cast<const uint4*>(smem + hswz[0] + ((c ^ hx) << 4));
-    fa[buf][1] = *reinterpret_cast<const uint4*>(smem + hswz[1] + ((c ^ hx) << 4));
+#pragma unroll
+    for (int t = 0; t < kPB; ++t)
+      fa[buf][t] = *reinterpret_cast<const uint4*>(smem + hrow + t * (32 * 512) + ((c ^ hx) << 4));
   };
-  constexpr int kNB = kSl2 + NCT * kKch;  // slices in the weight stream
-  // in flight here: B(kSl2) (waited for below), B(kSl2+1)
-  vm_wait<4>();
-  read_frags3(0, kSl2, 0, 0);
+  const float floor_ = a.relu ? 0.f : -__builtin_inff();  // the activation after the add as one max (NaN passes through)
+  const __bf16* const resp = reinterpret_cast<const __bf16*>(a.res);
+  __bf16* const outp = reinterpret_cast<__bf16*>(a.out);
+  read_frags3(0, 0, 0);
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
-    u32x4 r00, r01, r10, r11;  // residual: pixel block 0 / 1, channels 0-7 / 8-15 of the lane's sixteen
+    const int cb = ct * 256 + wave * 32;
+    uint4 res[kPB][2];  // residual: per pixel block, channels 0-7 / 8-15 of the lane's sixteen
+#pragma unroll
+    for (int t = 0; t < kPB; ++t) res[t][0] = res[t][1] = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int ks = 0; ks < kKch; ++ks) {
       const int b = kSl2 + ct * kKch + ks;
+      const int BUF = b % kWRing;
       TAIL_STAMP(40 + ct * kKch + ks);
 #pragma unroll
       for (int kg = 0; kg < 4; ++kg) {
         const int cur = kg & 1, nxt = cur ^ 1;
-        if (kg < 3) {
-          read_frags3(nxt, b, ks, kg + 1);
-        } else if (b + 1 < kNB) {
-          // weights of slice b+1; younger loads: B(b+2) if it exists, and the residual if issued in this slice
-          constexpr int kRes = 4;
-          const bool has2 = b + 2 < kNB;
-          if (ks == 0) { if (has2) vm_wait<4 + kRes>(); else vm_wait<kRes>(); }
-          else { if (has2) vm_wait<4>(); else vm_wait<0>(); }
-          read_frags3(nxt, b + 1, (ks + 1) % kKch, 0);
-        }
+        if (kg < 3) read_frags3(nxt, ks, kg + 1);
+        else if (b + 1 < kNB) read_frags3(nxt, (ks + 1) % kKch, 0);
         __builtin_amdgcn_sched_barrier(0);
-        acc[0] = mma_bf16(fw[cur], fa[cur][0], acc[0]);
-        acc[1] = mma_bf16(fw[cur], fa[cur][1], acc[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kg == 1) {
-          if (ks == 0) {
-            const unsigned so = (unsigned)ct * 512u;
-            r00 = load16_untracked(resrs, voffR0, so);
-            r01 = load16_untracked(resrs, voffR0 + 16u, so);
-            r10 = load16_untracked(resrs, voffR1, so);
-            r11 = load16_untracked(resrs, voffR1 + 16u, so);
-          }
-          if (b + 2 < kNB) issue_B(b + 2);
-        }
-      }
-    }
-    // epilogue of the column tile: younger loads than the residual = the weight slices issued since (4 each)
-    {
-      const int left = kNB - (kSl2 + ct * kKch) - 2;                     // weight slices not yet issued when the tile began
-      const int after = left < 0 ? 0 : (left < kKch ? left : kKch);     // ... of which this tile issued
-      switch (after) {  // (folds to one case once the tile loop is unrolled)
-        case 4: vm_wait_regs<16>(r00, r01, r10, r11); break;
-        case 3: vm_wait_regs<12>(r00, r01, r10, r11); break;
-        case 2: vm_wait_regs<8>(r00, r01, r10, r11); break;
-        case 1: vm_wait_regs<4>(r00, r01, r10, r11); break;
-        default: vm_wait_regs<0>(r00, r01, r10, r11); break;
-      }
-    }
-    const int cb = ct * 256 + wave * 32;
-    __bf16* const outp = reinterpret_cast<__bf16*>(a.out);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < kPB; ++t) acc[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc[t]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kg == 1 && ks == 0) {
+#pragma unroll
+          for (int t = 0; t < kPB; ++t)
+            if (orow[t] >= 0) {
+              const uint4* rp = reinterpret_cast<const uint4*>(resp + (size_t)orow[t] * COUT + cb + lhi * 16);
+              res[t][0] = rp[0];
+              res[t][1] = rp[1];
+            }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if (b + kWRing < kNB) load_W(BUF, b + kWRing);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int t = 0; t < kPB; ++t) {
       float v[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -422,26 +375,27 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
         v[4 * g + 3] = acc[t][4 * g + 3] * sc.w + sh.w;
       }
       to_consecutive_channels(v);
-      const u32x4 ra = t == 0 ? r00 : r10, rb = t == 0 ? r01 : r11;
-      // v order: [0-3]=ch0-3, [8-11]=ch4-7 (chunk a); [4-7]=ch8-11, [12-15]=ch12-15 (chunk b)
+      const unsigned rav[4] = {res[t][0].x, res[t][0].y, res[t][0].z, res[t][0].w};
+      const unsigned rbv[4] = {res[t][1].x, res[t][1].y, res[t][1].z, res[t][1].w};
+      // v order: [0-3]=ch0-3, [8-11]=ch4-7 (first chunk); [4-7]=ch8-11, [12-15]=ch12-15 (second chunk)
       const int o0[4] = {0, 2, 8, 10}, o1[4] = {4, 6, 12, 14};
       unsigned pa[4], pb[4];
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        float x0 = v[o0[d]] + __uint_as_float(ra[d] << 16), x1 = v[o0[d] + 1] + __uint_as_float(ra[d] & 0xffff0000u);
-        float y0 = v[o1[d]] + __uint_as_float(rb[d] << 16), y1 = v[o1[d] + 1] + __uint_as_float(rb[d] & 0xffff0000u);
-        if (a.relu) { x0 = fmaxf(x0, 0.f); x1 = fmaxf(x1, 0.f); y0 = fmaxf(y0, 0.f); y1 = fmaxf(y1, 0.f); }
+        float x0 = v[o0[d]] + __uint_as_float(rav[d] << 16), x1 = v[o0[d] + 1] + __uint_as_float(rav[d] & 0xffff0000u);
+        float y0 = v[o1[d]] + __uint_as_float(rbv[d] << 16), y1 = v[o1[d] + 1] + __uint_as_float(rbv[d] & 0xffff0000u);
+        x0 = fmaxf(x0, floor_); x1 = fmaxf(x1, floor_); y0 = fmaxf(y0, floor_); y1 = fmaxf(y1, floor_);
         pa[d] = pack_bf16(x0, x1);
         pb[d] = pack_bf16(y0, y1);
       }
-      const int orow = t == 0 ? orow0 : orow1;
-      if (orow >= 0) {
-        uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)orow * COUT + cb + lhi * 16);
+      if (orow[t] >= 0) {
+        uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)orow[t] * COUT + cb + lhi * 16);
         dst[0] = make_uint4(pa[0], pa[1], pa[2], pa[3]);
         dst[1] = make_uint4(pb[0], pb[1], pb[2], pb[3]);
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+      __builtin_amdgcn_sched_barrier(0);  // one pixel block at a time (register pressure)
     }
   }
   TAIL_STAMP(56);
@@ -449,6 +403,9 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
 
 #ifdef LAUD_TAIL_DBG
 }  // namespace laud
+extern "C" int laud_tail_fine_read(long long* host) {
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(laud::g_tail_fine), 8 * 64 * 8) == hipSuccess ? 0 : -1;
+}
 extern "C" int laud_tail_dbg_read(long long* host, int nblocks) {
   return hipMemcpyFromSymbol(host, HIP_SYMBOL(laud::g_tail_dbg), (size_t)nblocks * 64 * 8) == hipSuccess ? 0 : -1;
 }
@@ -459,10 +416,19 @@ namespace laud {
 bool tail_supported(int dtype, int c_mid, int c_out) {
   return dtype == LAUD_BF16 && c_mid == tail::kMid && (c_out == 1024);
 }
+size_t tail_packed_bytes(int c_mid, int c_out) { (void)c_mid; return align_up(tail::packed_bytes(c_out), 256); }
 
 int tail_init_device() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              tail::lds_bytes(1024)) == hipSuccess ? LAUD_OK : LAUD_ERR_HIP;
+}
+
+int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hipStream_t st) {
+  const int nslices = tail::kSl2 + c_out / 256 * tail::kKch;
+  const int chunks = nslices * tail::kSliceChunks;
+  hipLaunchKernelGGL(k_pack_tail_weights, dim3((chunks + 255) / 256), dim3(256), 0, st, (const uint4*)w2, (const uint4*)w3,
+                     (uint4*)packed, nslices);
+  return check_launch();
 }
 
 int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t st) {
