@@ -150,6 +150,7 @@ struct TailArgs {
   void* out;             // [output pixels][cout]; may alias res
   const int32_t* count;  // device: number of active patches
   const int32_t* list;   // device: ascending active patch ids
+  int cap_patches;       // capacity of `list` (number of patches of the grid), > 0
   int H, W;              // input grid of h1
   int S;                 // patch size on the output grid
   int stride, Ho, Wo;    // spatial stride of the 3x3 and the output grid (stride 1: Ho = H, Wo = W)

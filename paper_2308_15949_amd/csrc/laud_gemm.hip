@@ -1016,6 +1016,7 @@ static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e,
   t.h1 = h1; t.wpacked = wpack; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
   t.res = res; t.out = out; t.count = count; t.list = idx; t.H = H; t.W = W; t.S = S; t.stride = stride;
   t.Ho = Ho; t.Wo = Wo; t.cout = p->c_out; t.relu = p->relu_out ? 1 : 0;
+  t.cap_patches = (int)(cap_rows / ((long long)S * S));
   *rc = launch_tail(t, cap_rows, st);
   return 1;
 }

@@ -140,18 +140,17 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l31 = lane & 31, lhi = lane >> 5, l8 = lane >> 3, l7 = lane & 7;
 
-  // ---- which tile: consecutive workgroup ids go round-robin over the 8 XCDs; each XCD takes a contiguous run
-  // of row tiles (neighbouring tiles share halo rows of h1 in that XCD's L2) --------------------------------
+  // ---- which tile: workgroup b takes rows 64b ..; the count is only needed to tell which rows exist, so the index
+  // list entries of this tile are requested together with it (the list's capacity covers every workgroup of the
+  // grid; entries past the count are read but never used) --------------------------------------------------------
   TAIL_STAMP(0);
   const int SS = a.S * a.S;
+  const int row0 = blockIdx.x * kBM;
+  int qsp[kPB / 2];
+#pragma unroll
+  for (int i = 0; i < kPB / 2; ++i) qsp[i] = a.list[min((row0 + 64 * i + 8 * wave + l8) / SS, a.cap_patches - 1)];
   const int M = *a.count * SS;
-  const int ntiles = (M + kBM - 1) / kBM;
-  const int tpx = (ntiles + 7) >> 3;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int rt = xcd * tpx + slot;
-  if (slot >= tpx || rt >= ntiles) return;
-  const int row0 = rt * kBM;
-
+  if (row0 >= M) return;
   // ---- weight stream: three slices in registers (one in use, two in flight) ------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
@@ -180,7 +179,7 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     const int rho = row0 + r;
     if (rho < M) {
       const int p = rho / SS, j = rho - p * SS;
-      const int q = a.list[p];
+      const int q = qsp[i];
       const int n = q / (Hp * Wp), r2 = q - n * (Hp * Wp);
       const int py = r2 / Wp, px = r2 - py * Wp;
       const int yo = py * a.S + j / a.S, xo = px * a.S + j % a.S;
@@ -313,6 +312,9 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   TAIL_STAMP(39);
 
   // ---- the last 1x1, column tile by column tile: no activation loads, no barriers ------------------------------
+  // Two accumulator sets alternate between column tiles: while tile ct is multiplied into one, the other (tile
+  // ct-1) goes through its epilogue -- affine, residual add, activation, rounding, store -- in half-block pieces
+  // placed behind the MFMAs of tile ct's first K steps, so the vector ALU works in the shadow of the matrix pipe.
   int orow[kPB];
 #pragma unroll
   for (int t = 0; t < kPB; ++t) orow[t] = s_orow[32 * t + l31];
@@ -327,76 +329,94 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const float floor_ = a.relu ? 0.f : -__builtin_inff();  // the activation after the add as one max (NaN passes through)
   const __bf16* const resp = reinterpret_cast<const __bf16*>(a.res);
   __bf16* const outp = reinterpret_cast<__bf16*>(a.out);
+  f32x16 acc2[kPB];  // the second accumulator set (odd column tiles)
+#pragma unroll
+  for (int t = 0; t < kPB; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc2[t][e] = 0.f;
+  uint4 res[kPB][2];  // residual of the tile whose epilogue is pending: per pixel block, channels 0-7 / 8-15
+#pragma unroll
+  for (int t = 0; t < kPB; ++t) res[t][0] = res[t][1] = make_uint4(0, 0, 0, 0);
+
+  // Half a pixel block of the epilogue of column tile ct: accumulator groups h and h+2 of a lane (channels
+  // 8h + 4*(lane/32) .. +3 and 16 + 8h + 4*(lane/32) .. +3) become, after four lane swaps, eight consecutive channels.
+  auto epilogue_half = [&](int ct, int t, int h, f32x16& A) __attribute__((always_inline)) {
+    const int cb = ct * 256 + wave * 32;
+    const float4 sc0 = *reinterpret_cast<const float4*>(s_s3 + cb + 8 * h + 4 * lhi);
+    const float4 sh0 = *reinterpret_cast<const float4*>(s_t3 + cb + 8 * h + 4 * lhi);
+    const float4 sc1 = *reinterpret_cast<const float4*>(s_s3 + cb + 8 * (h + 2) + 4 * lhi);
+    const float4 sh1 = *reinterpret_cast<const float4*>(s_t3 + cb + 8 * (h + 2) + 4 * lhi);
+    float v0[4] = {A[4 * h + 0] * sc0.x + sh0.x, A[4 * h + 1] * sc0.y + sh0.y, A[4 * h + 2] * sc0.z + sh0.z,
+                   A[4 * h + 3] * sc0.w + sh0.w};
+    float v1[4] = {A[4 * h + 8] * sc1.x + sh1.x, A[4 * h + 9] * sc1.y + sh1.y, A[4 * h + 10] * sc1.z + sh1.z,
+                   A[4 * h + 11] * sc1.w + sh1.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v0[i]), __float_as_uint(v1[i]), false, false);
+      v0[i] = __uint_as_float(r[0]);
+      v1[i] = __uint_as_float(r[1]);
+      A[4 * h + i] = 0.f;  // the set is free for the tile after next
+      A[4 * h + 8 + i] = 0.f;
+    }
+    const unsigned rv[4] = {res[t][h].x, res[t][h].y, res[t][h].z, res[t][h].w};
+    const float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    unsigned pk[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const float lo = fmaxf(x[2 * d] + __uint_as_float(rv[d] << 16), floor_);
+      const float hi = fmaxf(x[2 * d + 1] + __uint_as_float(rv[d] & 0xffff0000u), floor_);
+      pk[d] = pack_bf16(lo, hi);
+    }
+    if (orow[t] >= 0)
+      *reinterpret_cast<uint4*>(outp + (size_t)orow[t] * COUT + cb + lhi * 16 + h * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+  };
+  auto load_residual = [&](int ct) __attribute__((always_inline)) {
+    const int cb = ct * 256 + wave * 32;
+#pragma unroll
+    for (int t = 0; t < kPB; ++t)
+      if (orow[t] >= 0) {
+        const uint4* rp = reinterpret_cast<const uint4*>(resp + (size_t)orow[t] * COUT + cb + lhi * 16);
+        res[t][0] = rp[0];
+        res[t][1] = rp[1];
+      }
+  };
+
   read_frags3(0, 0, 0);
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
-    const int cb = ct * 256 + wave * 32;
-    uint4 res[kPB][2];  // residual: per pixel block, channels 0-7 / 8-15 of the lane's sixteen
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) res[t][0] = res[t][1] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int ks = 0; ks < kKch; ++ks) {
+    for (int st = 0; st < 4 * kKch; ++st) {
+      const int ks = st / 4, kg = st % 4;
       const int b = kSl2 + ct * kKch + ks;
       const int BUF = b % kWRing;
-      TAIL_STAMP(40 + ct * kKch + ks);
+      if (kg == 0) TAIL_STAMP(40 + ct * kKch + ks);
+      const int cur = st & 1, nxt = cur ^ 1;
+      if (kg < 3) read_frags3(nxt, ks, kg + 1);
+      else if (b + 1 < kNB) read_frags3(nxt, (ks + 1) % kKch, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {
-        const int cur = kg & 1, nxt = cur ^ 1;
-        if (kg < 3) read_frags3(nxt, ks, kg + 1);
-        else if (b + 1 < kNB) read_frags3(nxt, (ks + 1) % kKch, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int t = 0; t < kPB; ++t) acc[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc[t]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kg == 1 && ks == 0) {
-#pragma unroll
-          for (int t = 0; t < kPB; ++t)
-            if (orow[t] >= 0) {
-              const uint4* rp = reinterpret_cast<const uint4*>(resp + (size_t)orow[t] * COUT + cb + lhi * 16);
-              res[t][0] = rp[0];
-              res[t][1] = rp[1];
-            }
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      for (int t = 0; t < kPB; ++t) {
+        if (ct & 1) acc2[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc2[t]);
+        else acc[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc[t]);
       }
-      if (b + kWRing < kNB) load_W(BUF, b + kWRing);
+      // a piece of the previous tile's epilogue behind these MFMAs (odd steps 1, 3, ... : one half block each)
+      if (ct > 0 && (st & 1) && st / 2 < 2 * kPB) {
+        const int pi = st / 2, t = pi / 2, h = pi % 2;
+        if (ct & 1) epilogue_half(ct - 1, t, h, acc[t]); else epilogue_half(ct - 1, t, h, acc2[t]);
+      }
+      // this tile's residual, requested once the previous tile's has been used up
+      if (st == 4 * kPB) load_residual(ct);
+      // the weight register just used is refilled for three slices later
+      if (b + kWRing < kNB) wr[BUF][kg] = wsrc[(size_t)(b + kWRing) * kSliceChunks + kg * 64];
       __builtin_amdgcn_sched_barrier(0);
     }
+  }
+  // the last tile's epilogue
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) {
-      float v[16];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 sc = *reinterpret_cast<const float4*>(s_s3 + cb + 8 * g + 4 * lhi);
-        const float4 sh = *reinterpret_cast<const float4*>(s_t3 + cb + 8 * g + 4 * lhi);
-        v[4 * g + 0] = acc[t][4 * g + 0] * sc.x + sh.x;
-        v[4 * g + 1] = acc[t][4 * g + 1] * sc.y + sh.y;
-        v[4 * g + 2] = acc[t][4 * g + 2] * sc.z + sh.z;
-        v[4 * g + 3] = acc[t][4 * g + 3] * sc.w + sh.w;
-      }
-      to_consecutive_channels(v);
-      const unsigned rav[4] = {res[t][0].x, res[t][0].y, res[t][0].z, res[t][0].w};
-      const unsigned rbv[4] = {res[t][1].x, res[t][1].y, res[t][1].z, res[t][1].w};
-      // v order: [0-3]=ch0-3, [8-11]=ch4-7 (first chunk); [4-7]=ch8-11, [12-15]=ch12-15 (second chunk)
-      const int o0[4] = {0, 2, 8, 10}, o1[4] = {4, 6, 12, 14};
-      unsigned pa[4], pb[4];
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        float x0 = v[o0[d]] + __uint_as_float(rav[d] << 16), x1 = v[o0[d] + 1] + __uint_as_float(rav[d] & 0xffff0000u);
-        float y0 = v[o1[d]] + __uint_as_float(rbv[d] << 16), y1 = v[o1[d] + 1] + __uint_as_float(rbv[d] & 0xffff0000u);
-        x0 = fmaxf(x0, floor_); x1 = fmaxf(x1, floor_); y0 = fmaxf(y0, floor_); y1 = fmaxf(y1, floor_);
-        pa[d] = pack_bf16(x0, x1);
-        pb[d] = pack_bf16(y0, y1);
-      }
-      if (orow[t] >= 0) {
-        uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)orow[t] * COUT + cb + lhi * 16);
-        dst[0] = make_uint4(pa[0], pa[1], pa[2], pa[3]);
-        dst[1] = make_uint4(pb[0], pb[1], pb[2], pb[3]);
-      }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-      __builtin_amdgcn_sched_barrier(0);  // one pixel block at a time (register pressure)
-    }
+  for (int pi = 0; pi < 2 * kPB; ++pi) {
+    const int t = pi / 2, h = pi % 2;
+    if ((NCT - 1) & 1) epilogue_half(NCT - 1, t, h, acc2[t]); else epilogue_half(NCT - 1, t, h, acc[t]);
+    __builtin_amdgcn_sched_barrier(0);
   }
   TAIL_STAMP(56);
 }
@@ -441,7 +461,7 @@ int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t st) {
     done.fetch_or(bit, std::memory_order_release);
   }
   const long long tiles = (cap_rows + tail::kBM - 1) / tail::kBM;
-  const unsigned grid = (unsigned)(((tiles + 7) / 8) * 8);
+  const unsigned grid = (unsigned)tiles;
   StageScope scope(LAUD_STAGE_CONV2, st);
   hipLaunchKernelGGL((k_tail<4>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(1024), st, a);
   return check_launch();
