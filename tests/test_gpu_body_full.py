@@ -1,0 +1,163 @@
+"""The whole dynamic ResNet-101 body at full size on the GPU (batch 128 from 224 x 224 images: stem, per stage a
+static projection block and 2 / 3 / 22 / 2 dynamic identity blocks, granularity 4-4-2-1) against the CPU oracle
+on a subsample of the batch.
+
+The oracle runs its own chain on eight images (float64 arithmetic; what one block hands to the next is rounded to
+the storage type, as the GPU stores it).  The GPU works on the full batch, in the launch configuration the
+benchmark times.  The batch holds the eight images three times over:
+
+  slots 0-7   teacher-forced: before every block these slots are overwritten with the oracle's input of that block
+              (exactly representable in bf16), so every one of the 33 blocks is compared per element, at the fixed
+              per-block tolerance, on exactly the oracle's input; masks must agree exactly (every threshold sits
+              in a gap of the oracle's logits), inactive pixels must come back bit for bit;
+  slots 8-15  free-running copies of the same images: never overwritten, the GPU's own chain; their masks are
+              compared with the oracle's to REPORT the agreement rate and the drift (printed, with a loose sanity
+              bound only -- a mask is a discontinuous function of rounded features);
+  the rest    other seeded images, so that the batch has the statistics of a real one.
+
+Layer skipping (the second case): batch 256, a seeded Bernoulli(0.6) keep gate per sample and block; in stages 1,
+2 and 4 the gate is the whole decision (compaction of the kept samples, S = H), in stage 3 it is AND-ed with the
+spatial masker (S = 2, ratio 0.5)."""
+import numpy as np
+import pytest
+
+from oracle import laud_oracle as O
+from paper_2308_15949_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+DT = I.BF16
+TOL = 2e-2
+NS = 8  # sampled images
+
+
+def close(got, ref, what):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    err = np.abs(got - ref)
+    bad = err > TOL * (np.abs(ref) + rms)
+    assert not bad.any(), f"{what}: {int(bad.sum())}/{ref.size} out of tolerance, max err {err.max():.3e}, rms {rms:.3e}"
+    return float(err.max() / (rms + 1e-30))
+
+
+def oparams(hb):
+    return O.BottleneckParams(hb.w1, hb.w2, hb.w3, hb.s1, hb.t1, hb.s2, hb.t2, hb.s3, hb.t3, hb.relu_out)
+
+
+def shortcut_params(seed, c_in, c_out):
+    g = np.random.default_rng(seed)
+    w = I.round_to(g.standard_normal((c_out, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), DT)
+    return w, (0.5 * (1 + 0.1 * g.standard_normal(c_out))).astype(np.float32), (0.1 * g.standard_normal(c_out)).astype(np.float32)
+
+
+@pytest.mark.parametrize("case", [("config3", 128, None, (1, 2, 3, 4)), ("config5", 256, 0.6, (3,))])
+def test_resnet101_body_full_size_sampled(case):
+    import torch as t
+    import paper_2308_15949_amd as L
+    from paper_2308_15949_amd import device as D
+    B = L.binding
+    name, N, keep_p, spatial_stages = case
+    cfg = 3 if keep_p is None else 5
+    g = np.random.default_rng(I.seed_for(cfg, 0))
+    img = I.round_to(g.standard_normal((N, 224, 224, 3), dtype=np.float32), DT)
+    img[NS:2 * NS] = img[:NS]   # the free-running copies
+    w7 = I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), DT)
+    s7, t7 = (1 + 0.1 * g.standard_normal(64)).astype(np.float32), (0.1 * g.standard_normal(64)).astype(np.float32)
+    dev = lambda v: t.from_numpy(np.ascontiguousarray(v)).cuda()
+
+    # ---- stem -----------------------------------------------------------------------------------------------
+    xd = t.empty((N, 56, 56, 64), dtype=t.bfloat16, device="cuda")
+    L.laud_stem(D.to_device(img, DT), N, 224, 224, DT, D.to_device(w7, DT), dev(s7), dev(t7), 64, xd,
+                D.workspace(L.stem_workspace(N, 224, 224, 64, DT)))
+    t.cuda.synchronize()
+    y_ref = O.stem(img[:NS], w7, s7, t7)
+    worst = {"stem": close(D.to_host(xd[:NS]), y_ref, "stem")}
+    x_ref = I.round_to(y_ref.astype(np.float32), DT)   # what the next block receives: the stored values
+    report = []
+    c_in, hw, blk_no = 64, 56, 0
+    wc = D.workspace(4096)
+    for stage, nblk in ((1, 3), (2, 4), (3, 23), (4, 3)):
+        sg = I.STAGES[stage]
+        m, stride, co = sg["m"], (1 if stage == 1 else 2), 4 * sg["m"]
+        spatial = stage in spatial_stages
+        # ---- static first block of the stage (projection shortcut, stride on the 3x3) -------------------------
+        blk_no += 1
+        hb = I.bottleneck_params(I.seed_for(cfg, 0, blk_no), c_in, m, co, DT, relu_out=True, s3_gain=0.5)
+        wsc, ssc, tsc = shortcut_params(I.seed_for(cfg, 8, blk_no), c_in, co)
+        xd[:NS] = D.to_device(x_ref, DT)                     # teacher-forced slots: the oracle's input
+        fx = L.fmap_of(xd)
+        db = D.DeviceBottleneck(hb)
+        hw = (hw - 1) // stride + 1
+        out = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+        print(f"{name} block {blk_no}: stage {stage} static projection block", flush=True)
+        L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, DT), dev(ssc), dev(tsc), stride, out,
+                                 D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride)))
+        t.cuda.synchronize()
+        y_ref = O.projection_bottleneck(x_ref, oparams(hb), wsc, ssc, tsc, stride)
+        worst[f"b{blk_no}"] = close(D.to_host(out[:NS]), y_ref, f"block {blk_no} (static, stage {stage})")
+        x_ref = I.round_to(y_ref.astype(np.float32), DT)
+        xd, c_in = out, co
+        del db
+        # ---- dynamic identity blocks -----------------------------------------------------------------------
+        S = sg["S"] if spatial else hw
+        fx = L.fmap_of(xd)
+        hp = hw // S
+        npatch = N * hp * hp
+        mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.zeros(1, dtype=t.int32, device="cuda")
+        ws = None
+        for _ in range(1, nblk):
+            blk_no += 1
+            hb = I.bottleneck_params(I.seed_for(cfg, 0, blk_no), co, m, co, DT, relu_out=True, s3_gain=0.25)
+            p = oparams(hb)
+            db = D.DeviceBottleneck(hb)
+            if ws is None:
+                ws = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fx, db.desc, S))
+            keep = None
+            if keep_p is not None:
+                keep = I.bernoulli_mask(I.seed_for(cfg, 7, blk_no), (N,), keep_p)
+                keep[NS:2 * NS] = keep[:NS]
+            xd[:NS] = D.to_device(x_ref, DT)
+            gpu_in = D.to_host(xd[:2 * NS])
+            print(f"{name} block {blk_no}: stage {stage} dynamic block, S = {S}", flush=True)
+            if spatial:
+                w = I.masker_weights(I.seed_for(cfg, 5, blk_no), co)
+                ref0 = O.mask_logits(x_ref, S, w, 0.0)
+                bias, half_gap = I.bias_for_ratio(ref0, 0.5)
+                assert half_gap > 1e-4 * float(np.sqrt(np.mean(ref0 * ref0))), "threshold not in a gap"
+                ref_mask = O.threshold(ref0 + bias)
+                if keep is not None:
+                    ref_mask = ref_mask * keep[:NS, None, None]
+                L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, dev(w), bias, dev(keep) if keep is not None else None,
+                                             mask, idx, cnt, None, None, xd, ws)
+                t.cuda.synchronize()
+                gm = mask.cpu().numpy().reshape(N, hp, hp)
+            else:   # layer skipping alone: the gate is the mask, one "patch" per sample
+                ref_mask = keep[:NS].reshape(NS, 1, 1)
+                L.laud_layer_skip_compact(dev(keep), N, idx, cnt, wc)
+                L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
+                t.cuda.synchronize()
+                gm = keep.reshape(N, 1, 1)
+                c = int(cnt.item())
+                assert np.array_equal(idx.cpu().numpy()[:c], O.compact(keep))
+            y_ref = O.dyn_bottleneck(x_ref, p, S, ref_mask)
+            got = D.to_host(xd[:2 * NS])
+            # teacher-forced slots: exact masks, per-element parity, inactive pixels untouched
+            assert np.array_equal(gm[:NS], ref_mask), f"block {blk_no}: mask differs on the teacher-forced images"
+            up = O.upsample_mask(ref_mask, S).astype(bool)
+            assert np.array_equal(got[:NS][~up], gpu_in[:NS][~up]), f"block {blk_no}: inactive pixels changed"
+            worst[f"b{blk_no}"] = close(got[:NS], y_ref, f"block {blk_no} (dynamic, stage {stage})")
+            # free-running slots: agreement of the GPU chain's own masks with the oracle's, and its drift
+            agree = float((gm[NS:2 * NS] == ref_mask).mean())
+            rms = float(np.sqrt(np.mean(y_ref * y_ref)))
+            drift = float(np.sqrt(np.mean((got[NS:] - y_ref) ** 2)) / rms)
+            report.append((blk_no, stage, float(gm.mean()), float(ref_mask.mean()), agree, drift))
+            x_ref = I.round_to(y_ref.astype(np.float32), DT)
+            del db
+    print(f"{name}: per-block worst |err| / rms on the teacher-forced images: max {max(worst.values()):.4f}")
+    print(f"{name}: block stage ratio(batch) ratio(oracle, 8 images) free-running mask agreement, rms drift")
+    for r in report:
+        print(f"  {r[0]:2d} {r[1]} {r[2]:.3f} {r[3]:.3f} {r[4]:.4f} {r[5]:.4f}")
+    assert len(worst) == 1 + 33
+    # sanity of the free-running chain (reported above, not a parity gate): the masks stay mostly those of the oracle
+    assert np.mean([r[4] for r in report]) > 0.9

@@ -406,7 +406,8 @@ def test_channel_skip(G, case, inplace):
 # ------------------------------------------------------------------------------------------
 # full-size workload of the benchmark (config 2), sampled images
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("r,fused", [(0.25, False), (1.0, False), (0.5, True), (0.25, True)])
+@pytest.mark.parametrize("r,fused", [(0.25, False), (0.75, False), (1.0, False), (0.5, True), (0.25, True), (0.75, True),
+                                     (1.0, True), (0.5, False), (0.0, True)])
 def test_config2_full_size_sampled(G, r, fused):
     """128 x 14 x 14 x 1024 bf16, mid 256, S = 2, mask from the masker at ratio r -- the launch
     configuration the benchmark times (fused = its default entry point, the masker inside the first 1x1).
@@ -427,7 +428,7 @@ def test_config2_full_size_sampled(G, r, fused):
     lg = t.zeros(npatch, dtype=t.float32, device="cuda")
     wsm = D.workspace(L.workspace_size(L.binding.OP_MASK_GEN, fx, None, S))
     wd = t.from_numpy(w).cuda()
-    sample = [0, 1, 63, 127]
+    sample = [0, 1, 17, 42, 63, 64, 100, 127]
     # bias from the oracle's logits of the whole batch (the pooled 1x1 is cheap on the CPU), in the middle of a gap
     ref0 = O.mask_logits(x, S, w, 0.0)
     bias, half_gap = I.bias_for_ratio(ref0, r)
