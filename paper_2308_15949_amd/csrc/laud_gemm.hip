@@ -33,6 +33,7 @@
 //
 // Accumulation is float32 (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32).
 #include "laud_common.h"
+#include "laud_tail_pack.h"
 
 #include <algorithm>
 #include <atomic>
@@ -78,6 +79,9 @@ struct GemmArgs {
   int m_rows;            // DENSE1, SD1..3: number of rows (all output pixels), known on the host
   int stride, Ho, Wo;    // SD1, SD2: spatial stride and output size (H, W are the input size)
   int gw;                // G2: channels per group of the 3x3
+  // Workgroups past the tiles (CONV1 / DENSE1 launches only) copy the block's w2 / w3 into the fused tail kernel's
+  // streaming order while the first 1x1 runs; pk_out == null: none.
+  const void* pk_w2; const void* pk_w3; void* pk_out; int pk_chunks; int pk_first_block;
   const float* wmask;    // DENSE1: masker weights [K] or null
   float* proj;           // DENSE1: per-pixel masker projection sum_c w[c]*x[pixel][c], [m_rows]
 };
@@ -170,6 +174,14 @@ __global__ __launch_bounds__(128 * WGN) void k_gemm(const GemmArgs a) {
   __shared__ int s_nkept;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if constexpr (MODE == M_CONV1 || MODE == M_DENSE1) {
+    if (a.pk_out != nullptr && (int)blockIdx.x >= a.pk_first_block) {
+      const int nextra = (int)gridDim.x - a.pk_first_block;
+      for (int idx = ((int)blockIdx.x - a.pk_first_block) * NT + tid; idx < a.pk_chunks; idx += nextra * NT)
+        tail_pack_chunk(idx, (const uint4*)a.pk_w2, (const uint4*)a.pk_w3, (uint4*)a.pk_out);
+      return;
+    }
+  }
   const int wm = wave / WGN, wn = wave % WGN;
   const int HW = a.H * a.W, SS = a.S * a.S;
   // Dynamic blocks with a spatial stride (a.stride > 1) keep their mask on the output grid Ho x Wo;
@@ -818,6 +830,14 @@ static int launch_gemm_t(GemmArgs a, long long cap_rows, int nsamples, hipStream
   dim3 grid;
   if (!CS) grid = dim3((unsigned)(((a.row_tiles + 7) / 8) * 8 * a.col_tiles));
   else grid = dim3((unsigned)(a.row_tiles * a.col_tiles), (unsigned)nsamples);
+  if constexpr (MODE == M_CONV1 || MODE == M_DENSE1) {
+    if (a.pk_out != nullptr) {  // spare workgroups for the weight re-ordering: one chunk per thread
+      a.pk_first_block = (int)grid.x;
+      grid.x += (unsigned)((a.pk_chunks + 128 * WGN - 1) / (128 * WGN));
+    }
+  } else {
+    a.pk_out = nullptr;
+  }
   constexpr int kStages = 2 * (BM + BN) * 144;  // two pipeline stages of 144-byte rows
   constexpr int kStaging = BM * (BN * 4 + 32);  // fp32 tile the epilogue transposes through
   constexpr int kLds = kStages > kStaging ? kStages : kStaging;
@@ -999,19 +1019,27 @@ static int launch_conv2(int dtype, GemmArgs a, const laud_group_se* e, long long
                             : launch_gemm_t<M_G2, float, 64, 64, 2>(a, cap_rows, 1, st);
 }
 
+// Whether conv2 -> conv3 -> residual add run as the one kernel of laud_tail.hip (h2 stays in LDS).
+static bool tail_wanted(int dtype, const laud_bottleneck* p, const laud_group_se* e) {
+#ifdef LAUD_TAIL_OFF
+  return false;
+#endif
+  return !e && tail_supported(dtype, p->c_mid, p->c_out);
+}
+// ... and then the first 1x1's launch carries the re-ordering of w2 / w3 for it in spare workgroups.
+static void attach_tail_pack(GemmArgs& a, int dtype, const laud_bottleneck* p, const laud_group_se* e, void* wpack) {
+  a.pk_out = nullptr;
+  if (!tail_wanted(dtype, p, e)) return;
+  a.pk_w2 = p->w2; a.pk_w3 = p->w3; a.pk_out = wpack;
+  a.pk_chunks = tail::packed_slices(p->c_out) * tail::kSliceChunks;
+}
+
 // conv2 -> conv3 -> residual add as one kernel where laud_tail.hip covers the shape (h2 stays in LDS).
 // Returns 1 when that kernel was launched (*rc = its status), 0 when the caller has to run the two GEMMs.
 static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e, const void* h1, const void* res,
                     void* out, const int32_t* idx, const int32_t* count, int H, int W, int S, int stride, int Ho, int Wo,
                     long long cap_rows, void* wpack, hipStream_t st, int* rc) {
-#ifdef LAUD_TAIL_OFF
-  return 0;
-#endif
-  if (e || !tail_supported(dtype, p->c_mid, p->c_out)) return 0;
-  {
-    StageScope scope(LAUD_STAGE_NEED, st);
-    if ((*rc = launch_tail_pack(p->w2, p->w3, p->c_out, wpack, st)) != LAUD_OK) return 1;
-  }
+  if (!tail_wanted(dtype, p, e)) return 0;
   TailArgs t{};
   t.h1 = h1; t.wpacked = wpack; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
   t.res = res; t.out = out; t.count = count; t.list = idx; t.H = H; t.W = W; t.S = S; t.stride = stride;
@@ -1069,7 +1097,9 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
+  attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+  a.pk_out = nullptr;
   if (try_tail(fx.dtype, p, e, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, wsb + L.wpack, st, &rc)) return rc;
   // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
@@ -1124,7 +1154,9 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
   a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = nullptr; a.list = nullptr; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1; a.m_rows = (int)npix; a.wmask = w; a.proj = proj;
+  attach_tail_pack(a, fx.dtype, p, nullptr, wsb + L.wpack);
   if ((rc = launch_gemm<M_DENSE1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+  a.pk_out = nullptr;
   // pooled logits -> threshold -> ascending index list (device-side count)
   if ((rc = launch_pool_compact(proj, fx.N, fx.H, fx.W, S, bias, keep, mask, logits, idx, count, sample_offsets,
                                 (int32_t*)(wsb + L.blocks), st)) != LAUD_OK)
@@ -1386,7 +1418,9 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
   // conv1 over that set -> h1 at input pixel positions
   a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
+  attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
   if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+  a.pk_out = nullptr;
   if (try_tail(fx.dtype, p, e, h1, out, out, idx, count, fx.H, fx.W, S, stride, Ho, Wo, nout, wsb + L.wpack, st, &rc)) return rc;
   // conv2: strided 3x3 at the active output pixels -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;

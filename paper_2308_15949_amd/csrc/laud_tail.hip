@@ -24,6 +24,7 @@
 // not know them.  Every wait for them is an explicit s_waitcnt vmcnt(n), n = number of LOADS this wave issued
 // after the ones needed (loads return in order; stores in flight only make such a wait longer, never shorter).
 #include "laud_common.h"
+#include "laud_tail_pack.h"
 
 #include <atomic>
 #include <type_traits>
@@ -37,23 +38,17 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 namespace tail {
-constexpr int kMid = 256;
 constexpr int kPB = 2;                        // 32-pixel blocks per workgroup (and per wave)
 constexpr int kBM = 32 * kPB;                 // pixels per workgroup
-constexpr int kWaves = 8, kThreads = 512;
 constexpr int kAStage = kBM * 128;            // one 128-byte K slice of every pixel row
 constexpr int kARing = 4;
 constexpr int kAOff = 0;                      // activation ring
 constexpr int kH2Off = kARing * kAStage;      // h2 tile: kBM pixels x 512 bytes
 constexpr int kTabOff = kH2Off + kBM * kMid * 2;
-constexpr int kKch = kMid / 64;               // K slices per tap (3x3) and per column tile (1x1)
-constexpr int kSl2 = 9 * kKch;                // slices of the 3x3
 constexpr int kWRing = 3;                     // weight slices held / in flight in registers
-constexpr int kSliceChunks = kWaves * 4 * 64; // 16-byte chunks of one packed weight slice (32 KB)
 constexpr unsigned kOob = 0x80000000u;        // offset outside every descriptor: reads as zero
 // float tables in LDS behind the tiles: s2, t2 [256], then s3, t3 [cout], then kBM output rows (int)
 __host__ __device__ constexpr int lds_bytes(int cout) { return kTabOff + (2 * kMid + 2 * cout) * 4 + kBM * 4; }
-__host__ __device__ constexpr size_t packed_bytes(int cout) { return (size_t)(kSl2 + cout / 256 * kKch) * kSliceChunks * 16; }
 }  // namespace tail
 
 // LDS-direct load of 16 bytes per lane: lane l's chunk lands at LDS byte address lds_base + 16*l.
@@ -93,23 +88,10 @@ __device__ __forceinline__ void to_consecutive_channels(float (&v)[16]) {
   }
 }
 
-// Weights in the order the MFMAs consume them: slice b of the weight stream (b < 36: tap b/4, K chunk b%4 of the
-// 3x3; then column tile (b-36)/4, K chunk (b-36)%4 of the last 1x1), wave w, K step kg, lane l hold the 16 bytes
-// W[channel 32w + l%32 (+256*tile)][k = 64*chunk + 16*kg + 8*(l/32) .. +7]: a wave instruction reads 1 KB in a row.
 __global__ __launch_bounds__(256) void k_pack_tail_weights(const uint4* __restrict__ w2, const uint4* __restrict__ w3,
                                                            uint4* __restrict__ out, int nslices) {
-  using namespace tail;
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= nslices * kSliceChunks) return;
-  const int l = idx & 63, kg = (idx >> 6) & 3, w = (idx >> 8) & 7, b = idx >> 11;
-  const int k = kg * 16 + (l >> 5) * 8;  // within the 64-element slice
-  if (b < kSl2) {
-    const int tap = b / kKch, kc = b % kKch, ch = 32 * w + (l & 31);
-    out[idx] = w2[((size_t)(ch * 9 + tap) * kMid + kc * 64 + k) / 8];
-  } else {
-    const int c = b - kSl2, ct = c / kKch, ks = c % kKch, ch = ct * 256 + 32 * w + (l & 31);
-    out[idx] = w3[((size_t)ch * kMid + ks * 64 + k) / 8];
-  }
+  if (idx < nslices * tail::kSliceChunks) tail_pack_chunk(idx, w2, w3, out);
 }
 
 #ifdef LAUD_TAIL_DBG
@@ -444,7 +426,7 @@ int tail_init_device() {
 }
 
 int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hipStream_t st) {
-  const int nslices = tail::kSl2 + c_out / 256 * tail::kKch;
+  const int nslices = tail::packed_slices(c_out);
   const int chunks = nslices * tail::kSliceChunks;
   hipLaunchKernelGGL(k_pack_tail_weights, dim3((chunks + 255) / 256), dim3(256), 0, st, (const uint4*)w2, (const uint4*)w3,
                      (uint4*)packed, nslices);
