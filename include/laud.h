@@ -84,6 +84,10 @@ typedef struct {
   const float* s3;
   const float* t3;
   int32_t relu_out; /* non-zero: ReLU after the residual add, on computed pixels only */
+  const void* packed; /* NULL, or the block's weights re-ordered once by laud_pack_weights() (device memory of
+                         laud_packed_weights_size() bytes).  With it no call spends time re-ordering weights; without
+                         it the entry points do the same re-ordering themselves on every call, into their workspace.
+                         It must be re-made whenever w1 / w2 / w3 change. */
 } laud_bottleneck;
 
 /* Human-readable name of a status code (static storage). */
@@ -99,6 +103,16 @@ int laud_abi_version(void);
  * called again (per device, from any thread).  Entry points work without it.
  */
 int laud_init(void);
+
+/*
+ * Weights in the order the MFMA kernels stream them (a data layout, no arithmetic: every 16-byte piece of w1, w2, w3
+ * is copied to the place where the lane that multiplies it will read it, so that a wave loads 1 KB in a row straight
+ * into registers).  Made once per block -- e.g. when a model is loaded -- and handed over in laud_bottleneck.packed.
+ * laud_packed_weights_size returns 0 for shapes / dtypes whose kernels read the plain layout (then packed stays
+ * NULL).  p->packed itself is ignored by both calls.
+ */
+size_t laud_packed_weights_size(const laud_bottleneck* p, int dtype);
+int laud_pack_weights(const laud_bottleneck* p, int dtype, void* packed, void* stream);
 
 /*
  * Workspace bytes an entry point needs for the given shapes.  `op` is a laud_op; `p` may be

@@ -24,7 +24,8 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
            "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name",
-           "laud_init", "laud_dyn_bottleneck_noalloc", "laud_probe_mfma", "laud_probe_copy"]
+           "laud_init", "laud_dyn_bottleneck_noalloc", "laud_probe_mfma", "laud_probe_copy",
+           "laud_packed_weights_size", "laud_pack_weights"]
 STAGE_COUNT = 13
 
 
@@ -36,7 +37,7 @@ class Bottleneck(C.Structure):
     _fields_ = [("c_in", C.c_int32), ("c_mid", C.c_int32), ("c_out", C.c_int32),
                 ("w1", C.c_void_p), ("w2", C.c_void_p), ("w3", C.c_void_p),
                 ("s1", C.c_void_p), ("t1", C.c_void_p), ("s2", C.c_void_p), ("t2", C.c_void_p),
-                ("s3", C.c_void_p), ("t3", C.c_void_p), ("relu_out", C.c_int32)]
+                ("s3", C.c_void_p), ("t3", C.c_void_p), ("relu_out", C.c_int32), ("packed", C.c_void_p)]
 
 
 class GroupSE(C.Structure):
@@ -81,6 +82,10 @@ def load() -> C.CDLL:
     lib.laud_probe_mfma.argtypes = [i32, i32, i32, C.POINTER(C.c_double), vp, vp]
     lib.laud_probe_copy.restype = i32
     lib.laud_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.laud_packed_weights_size.restype = sz
+    lib.laud_packed_weights_size.argtypes = [C.POINTER(Bottleneck), i32]
+    lib.laud_pack_weights.restype = i32
+    lib.laud_pack_weights.argtypes = [C.POINTER(Bottleneck), i32, vp, vp]
     lib.laud_init.restype = i32
     lib.laud_init.argtypes = []
     lib.laud_dyn_bottleneck_noalloc.restype = i32
@@ -173,6 +178,16 @@ def make_bottleneck(w1, w2, w3, s1, t1, s2, t2, s3, t3, relu_out: bool) -> Bottl
                       w1.data_ptr(), w2.data_ptr(), w3.data_ptr(),
                       s1.data_ptr(), t1.data_ptr(), s2.data_ptr(), t2.data_ptr(),
                       s3.data_ptr(), t3.data_ptr(), 1 if relu_out else 0)
+
+
+def packed_weights_size(p: Bottleneck, dtype: int) -> int:
+    return int(load().laud_packed_weights_size(C.byref(p), int(dtype)))
+
+
+def laud_pack_weights(p: Bottleneck, dtype: int, packed) -> None:
+    """Re-orders the block's weights into `packed` (device memory of packed_weights_size bytes); the caller then sets
+    p.packed = packed.data_ptr() and keeps the tensor alive."""
+    _check(load().laud_pack_weights(C.byref(p), int(dtype), _ptr(packed), _stream()), "laud_pack_weights")
 
 
 def workspace_size(op: int, fx: Fmap, p: Bottleneck | None, s_or_d: int) -> int:

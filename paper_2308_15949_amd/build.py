@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "liblaud.so")
 SOURCES = ["laud_api.hip", "laud_mask.hip", "laud_chanmask.hip", "laud_static.hip", "laud_se.hip", "laud_gemm.hip",
-           "laud_probe.hip", "laud_tail.hip"]
+           "laud_probe.hip", "laud_tail.hip", "laud_head.hip"]
 # packed-fp32 code generation is switched off for device code (the host pass warns that it
 # does not know the feature; that is harmless).
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

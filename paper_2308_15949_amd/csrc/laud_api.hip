@@ -57,7 +57,7 @@ extern "C" const char* laud_status_string(int status) {
   }
 }
 
-extern "C" int laud_abi_version(void) { return 3; }
+extern "C" int laud_abi_version(void) { return 4; }
 
 extern "C" int laud_stage_timing_enable(int on) {
   laud::recycle();

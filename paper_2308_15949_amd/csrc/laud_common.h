@@ -166,6 +166,22 @@ int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hi
 // cap_rows: upper bound of the number of active pixels (grid size); the count itself stays on the device
 int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t stream);
 
+// conv1 on every pixel (+ masker projection) with register-resident weights (laud_head.hip), for head_supported() shapes.
+struct HeadArgs {
+  const void* x;         // [m_rows][K] bf16
+  const void* wpacked;   // w1 in MFMA fragment order (launch_head_pack), head_packed_bytes() bytes
+  const float* s1; const float* t1;  // [256]
+  void* h1;              // [m_rows][256] bf16
+  int m_rows, K;
+  const float* wmask;    // masker weights [K] or null
+  float* proj;           // [m_rows] per-pixel projection (with wmask)
+};
+bool head_supported(int dtype, int c_in, int c_mid);
+int head_init_device();
+size_t head_packed_bytes(int c_in);
+int launch_head_pack(const void* w1, int c_in, void* packed, hipStream_t stream);
+int launch_head(const HeadArgs& a, hipStream_t stream);
+
 // Stage timing (see laud_stage_timing_enable): RAII bracket around the launches of one stage.
 extern bool g_stage_timing_on;
 void stage_mark(int stage, hipStream_t stream, bool begin);

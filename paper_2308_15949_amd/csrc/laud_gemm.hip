@@ -942,7 +942,8 @@ static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   w.h2 = o;          o += align_up(npix * c_mid * eb, 256);
   w.blocks = o;      o += compact_ws_bytes((long long)npix);  // block counts of a large compaction
   // weights in MFMA fragment order for the fused conv2 -> conv3 kernel (identity block: c_out = C)
-  w.wpack = o;       o += tail_supported(fx.dtype, c_mid, fx.C) ? tail_packed_bytes(c_mid, fx.C) : 0;
+  w.wpack = o;       o += (head_supported(fx.dtype, fx.C, c_mid) ? head_packed_bytes(fx.C) : 0) +
+                          (tail_supported(fx.dtype, c_mid, fx.C) ? tail_packed_bytes(c_mid, fx.C) : 0);
   w.bytes = o;
   return w;
 }
@@ -1019,18 +1020,42 @@ static int launch_conv2(int dtype, GemmArgs a, const laud_group_se* e, long long
                             : launch_gemm_t<M_G2, float, 64, 64, 2>(a, cap_rows, 1, st);
 }
 
-// Whether conv2 -> conv3 -> residual add run as the one kernel of laud_tail.hip (h2 stays in LDS).
+// Whether conv2 -> conv3 -> residual add run as the one kernel of laud_tail.hip (h2 stays in LDS), and whether
+// the dense first 1x1 (+ masker projection) runs as the kernel of laud_head.hip.
 static bool tail_wanted(int dtype, const laud_bottleneck* p, const laud_group_se* e) {
 #ifdef LAUD_TAIL_OFF
   return false;
 #endif
   return !e && tail_supported(dtype, p->c_mid, p->c_out);
 }
+static bool head_wanted(int dtype, const laud_bottleneck* p) {
+#ifdef LAUD_TAIL_OFF
+  return false;
+#endif
+  return head_supported(dtype, p->c_in, p->c_mid);
+}
+// Where the two parts lie in a block's packed weights (laud_pack_weights, or the workspace copy of a call).
+struct PackedLayout { size_t head, tail, bytes; };
+static PackedLayout packed_layout(int dtype, const laud_bottleneck* p) {
+  PackedLayout L{0, 0, 0};
+  if (head_wanted(dtype, p)) L.bytes += head_packed_bytes(p->c_in);
+  L.tail = L.bytes;
+  if (tail_wanted(dtype, p, nullptr)) L.bytes += tail_packed_bytes(p->c_mid, p->c_out);
+  return L;
+}
+static int pack_weights_into(int dtype, const laud_bottleneck* p, void* packed, bool head, bool tail, hipStream_t st) {
+  const PackedLayout L = packed_layout(dtype, p);
+  int rc = LAUD_OK;
+  if (head && head_wanted(dtype, p)) rc = launch_head_pack(p->w1, p->c_in, (char*)packed + L.head, st);
+  if (rc == LAUD_OK && tail && tail_wanted(dtype, p, nullptr))
+    rc = launch_tail_pack(p->w2, p->w3, p->c_out, (char*)packed + L.tail, st);
+  return rc;
+}
 // ... and then the first 1x1's launch carries the re-ordering of w2 / w3 for it in spare workgroups.
 static void attach_tail_pack(GemmArgs& a, int dtype, const laud_bottleneck* p, const laud_group_se* e, void* wpack) {
   a.pk_out = nullptr;
-  if (!tail_wanted(dtype, p, e)) return;
-  a.pk_w2 = p->w2; a.pk_w3 = p->w3; a.pk_out = wpack;
+  if (!tail_wanted(dtype, p, e) || p->packed) return;
+  a.pk_w2 = p->w2; a.pk_w3 = p->w3; a.pk_out = (char*)wpack + packed_layout(dtype, p).tail;
   a.pk_chunks = tail::packed_slices(p->c_out) * tail::kSliceChunks;
 }
 
@@ -1041,7 +1066,7 @@ static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e,
                     long long cap_rows, void* wpack, hipStream_t st, int* rc) {
   if (!tail_wanted(dtype, p, e)) return 0;
   TailArgs t{};
-  t.h1 = h1; t.wpacked = wpack; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
+  t.h1 = h1; t.wpacked = (const char*)(p->packed ? p->packed : wpack) + packed_layout(dtype, p).tail; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
   t.res = res; t.out = out; t.count = count; t.list = idx; t.H = H; t.W = W; t.S = S; t.stride = stride;
   t.Ho = Ho; t.Wo = Wo; t.cout = p->c_out; t.relu = p->relu_out ? 1 : 0;
   t.cap_patches = (int)(cap_rows / ((long long)S * S));
@@ -1154,9 +1179,18 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
   a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = nullptr; a.list = nullptr; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1; a.m_rows = (int)npix; a.wmask = w; a.proj = proj;
-  attach_tail_pack(a, fx.dtype, p, nullptr, wsb + L.wpack);
-  if ((rc = launch_gemm<M_DENSE1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
-  a.pk_out = nullptr;
+  if (head_wanted(fx.dtype, p)) {
+    // register-weight kernel; without caller-packed weights both parts are re-ordered here, ahead of it
+    if (!p->packed && (rc = pack_weights_into(fx.dtype, p, wsb + L.wpack, true, true, st)) != LAUD_OK) return rc;
+    HeadArgs h{};
+    h.x = x; h.wpacked = (const char*)(p->packed ? p->packed : wsb + L.wpack) + packed_layout(fx.dtype, p).head;
+    h.s1 = p->s1; h.t1 = p->t1; h.h1 = h1; h.m_rows = (int)npix; h.K = p->c_in; h.wmask = w; h.proj = proj;
+    if ((rc = launch_head(h, st)) != LAUD_OK) return rc;
+  } else {
+    attach_tail_pack(a, fx.dtype, p, nullptr, wsb + L.wpack);
+    if ((rc = launch_gemm<M_DENSE1>(fx.dtype, a, npix, 1, st)) != LAUD_OK) return rc;
+    a.pk_out = nullptr;
+  }
   // pooled logits -> threshold -> ascending index list (device-side count)
   if ((rc = launch_pool_compact(proj, fx.N, fx.H, fx.W, S, bias, keep, mask, logits, idx, count, sample_offsets,
                                 (int32_t*)(wsb + L.blocks), st)) != LAUD_OK)
@@ -1349,7 +1383,8 @@ DynProjWs dyn_proj_ws_layout(const laud_fmap& fx, int c_mid, int c_out, int stri
   w.pix = o;         o += align_up(npix * 4, 256);
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(nout * c_mid * eb, 256);
-  w.wpack = o;       o += tail_supported(fx.dtype, c_mid, c_out) ? tail_packed_bytes(c_mid, c_out) : 0;
+  w.wpack = o;       o += (head_supported(fx.dtype, fx.C, c_mid) ? head_packed_bytes(fx.C) : 0) +
+                          (tail_supported(fx.dtype, c_mid, c_out) ? tail_packed_bytes(c_mid, c_out) : 0);
   w.bytes = o;
   return w;
 }
@@ -1519,7 +1554,8 @@ extern "C" int laud_init(void) {
   if (rc != LAUD_OK) return rc;
   rc = gemm_init_device();
   if (rc != LAUD_OK) return rc;
-  return tail_init_device();
+  if ((rc = tail_init_device()) != LAUD_OK) return rc;
+  return head_init_device();
 }
 
 extern "C" int laud_dyn_bottleneck_noalloc(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
@@ -1532,4 +1568,18 @@ extern "C" int laud_dyn_bottleneck_noalloc(const void* x, laud_fmap fx, const la
   if (rc != LAUD_OK) return rc;
   // Nothing in this workspace has to start at zero: every region is written before it is read within the call.
   return run_dyn_block(x, fx, p, nullptr, S, idx, count, out, ptr, (size_t)LAUD_NOALLOC_SCRATCH_BYTES, stream);
+}
+
+extern "C" size_t laud_packed_weights_size(const laud_bottleneck* p, int dtype) {
+  if (!p || p->c_in <= 0 || p->c_mid <= 0 || p->c_out <= 0) return 0;
+  return packed_layout(dtype, p).bytes;
+}
+
+extern "C" int laud_pack_weights(const laud_bottleneck* p, int dtype, void* packed, void* stream) {
+  if (!p || !packed || !p->w1 || !p->w2 || !p->w3 || p->c_in <= 0 || p->c_mid <= 0 || p->c_out <= 0)
+    return LAUD_ERR_INVALID_ARG;
+  if (packed_layout(dtype, p).bytes == 0) return LAUD_ERR_UNSUPPORTED;
+  if (misaligned16(packed) || block_params_misaligned(p)) return LAUD_ERR_UNSUPPORTED;
+  clear_stale_error();
+  return pack_weights_into(dtype, p, packed, true, true, (hipStream_t)stream);
 }

@@ -25,17 +25,12 @@
 // after the ones needed (loads return in order; stores in flight only make such a wait longer, never shorter).
 #include "laud_common.h"
 #include "laud_tail_pack.h"
+#include "laud_tile_util.h"
 
 #include <atomic>
 #include <type_traits>
 
 namespace laud {
-
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 namespace tail {
 constexpr int kPB = 2;                        // 32-pixel blocks per workgroup (and per wave)
@@ -50,43 +45,6 @@ constexpr unsigned kOob = 0x80000000u;        // offset outside every descriptor
 // float tables in LDS behind the tiles: s2, t2 [256], then s3, t3 [cout], then kBM output rows (int)
 __host__ __device__ constexpr int lds_bytes(int cout) { return kTabOff + (2 * kMid + 2 * cout) * 4 + kBM * 4; }
 }  // namespace tail
-
-// LDS-direct load of 16 bytes per lane: lane l's chunk lands at LDS byte address lds_base + 16*l.
-__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
-               : "memory");
-}
-template <int N>
-__device__ __forceinline__ void vm_wait() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
-__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-__device__ __forceinline__ f32x16 mma_bf16(const u32x4& first, const uint4& second, f32x16 acc) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second),
-                                                 acc, 0, 0, 0);
-}
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
-}
-
-// Accumulator e of a lane belongs to channel 8*(e/4) + 4*(lane/32) + e%4 of the wave's 32.  After these eight
-// swaps v[] holds, in the order 0-3, 8-11, 4-7, 12-15, the sixteen consecutive channels 16*(lane/32) .. +15.
-__device__ __forceinline__ void to_consecutive_channels(float (&v)[16]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[8 + i]), false, false);
-    v[i] = __uint_as_float(r[0]);
-    v[8 + i] = __uint_as_float(r[1]);
-    auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[4 + i]), __float_as_uint(v[12 + i]), false, false);
-    v[4 + i] = __uint_as_float(q[0]);
-    v[12 + i] = __uint_as_float(q[1]);
-  }
-}
 
 __global__ __launch_bounds__(256) void k_pack_tail_weights(const uint4* __restrict__ w2, const uint4* __restrict__ w3,
                                                            uint4* __restrict__ out, int nslices) {

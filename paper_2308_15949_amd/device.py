@@ -26,7 +26,7 @@ def to_host(t) -> np.ndarray:
 class DeviceBottleneck:
     """Holds the device tensors of one bottleneck and the C descriptor that points at them."""
 
-    def __init__(self, hb: HostBottleneck, device: str = "cuda:0"):
+    def __init__(self, hb: HostBottleneck, device: str = "cuda:0", prepack: bool = True):
         import torch
         self.hb = hb
         self.w1 = to_device(hb.w1, hb.dtype, device)
@@ -36,6 +36,15 @@ class DeviceBottleneck:
         self.s1, self.t1, self.s2, self.t2, self.s3, self.t3 = map(f, (hb.s1, hb.t1, hb.s2, hb.t2, hb.s3, hb.t3))
         self.desc = B.make_bottleneck(self.w1, self.w2, self.w3, self.s1, self.t1, self.s2, self.t2,
                                       self.s3, self.t3, hb.relu_out)
+        # weights in the kernels' streaming order, made once (as when a model is loaded); prepack=False leaves the
+        # re-ordering to every call
+        self.packed = None
+        plain = tuple(hb.w2.shape) == (hb.c_mid, 3, 3, hb.c_mid)   # (a group convolution's w2 has another shape)
+        nb = B.packed_weights_size(self.desc, hb.dtype) if prepack and plain else 0
+        if nb:
+            self.packed = torch.empty(nb, dtype=torch.uint8, device=device)
+            B.laud_pack_weights(self.desc, hb.dtype, self.packed)
+            self.desc.packed = self.packed.data_ptr()
 
 
 class DeviceGroupSE:

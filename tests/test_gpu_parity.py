@@ -700,3 +700,52 @@ def test_fused_block_replays_from_a_hip_graph(G):
         assert int(cnt.item()) == ref_cnt, f"replay {rep}"
         assert t.equal(idx[:ref_cnt], ref_idx[:ref_cnt]), f"replay {rep}"
         assert t.equal(out.view(t.int16), ref_out.view(t.int16)), f"replay {rep}"
+
+
+# ------------------------------------------------------------------------------------------
+# weights re-ordered once (laud_pack_weights) against the re-ordering done inside every call
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("entry", ["masker", "two_call"])
+@pytest.mark.parametrize("N", [3, 21])
+def test_packed_weights_and_per_call_reordering_agree(G, entry, N):
+    """Stage-3 shape (the one the register-weight kernels cover): the block's result must not depend on who
+    re-ordered the weights -- bit for bit -- and must match the oracle; 21 images = 4116 pixels: several 128-pixel
+    tiles with a ragged last one."""
+    t, L, D = G.torch, G.L, G.D
+    H, C, m, S, dt = 14, 1024, 256, 2, I.BF16
+    x = I.feature_map(5100 + N, N, H, H, C, dt)
+    hb = I.bottleneck_params(5101, C, m, C, dt, relu_out=True)
+    hb.t1 = (np.abs(hb.t1) + 0.25).astype(np.float32)
+    w = I.masker_weights(5102, C)
+    ref0 = O.mask_logits(x, S, w, 0.0)
+    bias, _ = I.bias_for_ratio(ref0, 0.5)
+    ref_mask = O.threshold(ref0 + bias)
+    ref = O.dyn_bottleneck(x, oracle_params(hb), S, ref_mask)
+    outs = []
+    for prepack in (True, False):
+        db = D.DeviceBottleneck(hb, prepack=prepack)
+        assert (db.desc.packed is not None) == prepack
+        xd = D.to_device(x, dt)
+        fx = L.fmap_of(xd)
+        npatch = ref_mask.size
+        mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.zeros(1, dtype=t.int32, device="cuda")
+        ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+        ws.fill_(0xFF)
+        out = t.full_like(xd, 5.0)
+        if entry == "masker":
+            L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None, None,
+                                         out, ws)
+        else:
+            L.laud_mask_gen(xd, fx, S, t.from_numpy(w).cuda(), bias, None, mask, idx, cnt, None, None,
+                            D.workspace(L.workspace_size(L.binding.OP_MASK_GEN, fx, None, S)))
+            L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, out, ws)
+        t.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().reshape(ref_mask.shape), ref_mask)
+        got = D.to_host(out)
+        up = O.upsample_mask(ref_mask, S).astype(bool)
+        assert np.array_equal(got[~up], x[~up])
+        assert_close(got[up], ref[up], TOL[dt], f"{entry} prepack={prepack}")
+        outs.append(got)
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))

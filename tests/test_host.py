@@ -30,7 +30,7 @@ def test_header_symbols_are_exported(lib):
     assert declared == sorted(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert L.abi_version() == 3
+    assert L.abi_version() == 4
     assert L.status_string(0) == "LAUD_OK"
     for code in (-1, -2, -3, -4):
         assert L.status_string(code).startswith("LAUD_ERR_")
@@ -38,8 +38,8 @@ def test_header_symbols_are_exported(lib):
 
 def test_struct_layout_matches_header():
     assert C.sizeof(B.Fmap) == 20
-    # 3 ints (+4 pad), 9 pointers, 1 int (+4 pad)
-    assert C.sizeof(B.Bottleneck) == 16 + 72 + 8
+    # 3 ints (+4 pad), 9 pointers, 1 int (+4 pad), 1 pointer
+    assert C.sizeof(B.Bottleneck) == 16 + 72 + 8 + 8
     assert C.sizeof(B.GroupSE) == 8 + 32
 
 
@@ -55,7 +55,10 @@ def test_workspace_sizes(lib):
     p = _bn(1024, 256, 1024)
     npix = 128 * 14 * 14
     dyn = L.workspace_size(B.OP_DYN_BOTTLENECK, fx, p, 2)
-    assert dyn >= 2 * npix * 256 * 2 + npix * 4 and dyn < 2 * npix * 256 * 2 + npix * 4 + 8192  # + small counters
+    packed = L.packed_weights_size(p, B.BF16)   # room for the per-call copy of the re-ordered weights
+    assert packed == 256 * 1024 * 2 + (256 * 9 * 256 + 1024 * 256) * 2
+    assert dyn >= 2 * npix * 256 * 2 + npix * 4 + packed and dyn < 2 * npix * 256 * 2 + npix * 4 + packed + 8192  # + small counters
+    assert L.packed_weights_size(p, B.F32) == 0 and L.packed_weights_size(_bn(256, 64, 256), B.BF16) == 0
     assert L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4) == 2 * npix * 256 * 2
     assert L.workspace_size(B.OP_MASK_GEN, fx, None, 2) == 256
     assert L.workspace_size(B.OP_COMPACT, fx, None, 300001) >= 4 * 74
