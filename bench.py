@@ -24,10 +24,22 @@ from paper_2308_15949_amd import predictor as PRED  # noqa: E402  (host arithmet
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the conv2 kernel at the default workload (batch 128, ratio 0.5), from the
-# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/bench_config2_r050_pmc.txt
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors from a plain copy of known size).
-CONV2_TRAFFIC_BYTES_R050_B128 = 28.2e6
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "bench_config2_r050_pmc.txt")
+
+
+def traffic_from_profile(kernel: str):
+    """HBM bytes per launch of `kernel` at the default workload (batch 128, ratio 0.5) from the committed summary of the
+    FETCH_SIZE / WRITE_SIZE counter runs: the line `traffic_bytes <kernel> = <bytes>` (counter KiB scaled by what the
+    same counters read for a plain copy of known size; the summary states the factors).  None if there is none."""
+    try:
+        with open(PMC_SUMMARY) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and parts[0] == "traffic_bytes" and parts[1] == kernel and parts[2] == "=":
+                    return float(parts[3])
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -238,6 +250,39 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
     for b in bufs:
         b.copy_(x_master)
     xbytes = x_master.numel() * x_master.element_size()
+    # achievable peaks on this machine (the second denominator beside the published peaks): a bare MFMA loop on
+    # register operands and a plain copy kernel over a buffer far larger than the caches
+    sink = t.zeros(16, dtype=t.float32, device="cuda")
+    fl = [0.0]
+
+    def mfma_probe(i):
+        fl[0] = L.laud_probe_mfma(L.BF16, 4000, 2048, sink)
+    us = _p50_us(t, mfma_probe, iters=8, warm=2)
+    big_a = t.empty(1 << 30, dtype=t.uint8, device="cuda")
+    big_b = t.empty(1 << 30, dtype=t.uint8, device="cuda")
+    big_a.fill_(1)
+    usc = _p50_us(t, lambda i: L.laud_probe_copy(big_a, big_b, 1 << 30), iters=8, warm=2)
+    ex["achievable_peaks"] = {"mfma_bf16_TFLOP_per_s": round(fl[0] / us / 1e6, 0),
+                              "mfma_bf16_frac_of_published": round(fl[0] / us / 1e6 / PEAK_BF16_TFLOPS, 3),
+                              "copy_1GiB_GB_per_s_read_plus_write": round(2.0 * (1 << 30) / usc / 1e3, 0),
+                              "copy_frac_of_published_hbm": round(2.0 * (1 << 30) / usc / 1e3 / PEAK_HBM_GBS, 3)}
+    usr = _p50_us(t, lambda i: L.laud_probe_read(big_a, 1 << 30, sink), iters=8, warm=2)
+    ex["achievable_peaks"]["read_1GiB_GB_per_s"] = round((1 << 30) / usr / 1e3, 0)
+    # ... and a read of one cache-cold x buffer (the masker's whole traffic), launch included as for the kernels below
+    usx = _p50_us(t, lambda i: L.laud_probe_read(bufs[i % nb], x_master.numel() * x_master.element_size(), sink))
+    ex["achievable_peaks"]["read_one_x_buffer_us"] = round(usx, 1)
+    ex["achievable_peaks"]["read_one_x_buffer_GB_per_s"] = round(x_master.numel() * x_master.element_size() / usx / 1e3, 0)
+    del big_a, big_b
+    # the step with the weights re-ordered inside every call (laud_bottleneck.packed == NULL) instead of once
+    hb2 = I.bottleneck_params(I.seed_for(2, 0), fx.C, I.STAGES[3]["m"], fx.C, I.BF16, relu_out=False)
+    db_np = D.DeviceBottleneck(hb2, prepack=False)
+    ws_np = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fx, db_np.desc, S))
+    us = _p50_us(t, lambda i: L.laud_masker_dyn_bottleneck(bufs[i % nb], fx, db_np.desc, S, wd, bias, None, mask, idx, cnt,
+                                                          None, None, bufs[i % nb], ws_np))
+    ex["step_with_per_call_weight_reordering_config2_r050"] = {"p50_us": round(us, 1)}
+    del db_np, ws_np
+    for b in bufs:
+        b.copy_(x_master)
     # masker alone (HBM-bound: reads x once)
     us = _p50_us(t, lambda i: L.laud_mask_gen(bufs[i % nb], fx, S, wd, bias, None, mask, idx, cnt, None, None, wsm))
     ex["mask_gen_config2"] = {"p50_us": round(us, 1), "GB_per_s": round(xbytes / us / 1e3, 0),
@@ -720,14 +765,35 @@ def main():
     stages = L.laud_stage_timing_read()
     L.laud_stage_timing_enable(False)
     stage_us = {k: 1e3 * v[0] / a.steps for k, v in stages.items()}
-    conv2_us = stage_us["conv2"]
-    conv2_flops = P * S * S * 2.0 * 9.0 * m * m
-    achieved = conv2_flops / (conv2_us * 1e-6) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_gemm<CONV2,bf16> (3x3 implicit GEMM on active patches)",
+    # Per-kernel algorithmic FLOPs of the step (useful work only: active pixels; conv1 of the fused-masker entry point
+    # runs on every pixel by construction).  With the register-weight kernels conv2 and conv3 are ONE launch (stage
+    # label conv2).  The dominant kernel is the one with the longest average launch.
+    fused_tail = "conv3" not in stage_us
+    conv1_rows = N * H * H if a.variant == "fused" else None
+    kern = {}
+    if conv1_rows is not None and "conv1" in stage_us:
+        kern["conv1 (first 1x1 on every pixel + masker projection)"] = (stage_us["conv1"], conv1_rows * 2.0 * C * m)
+    if fused_tail:
+        kern["k_tail (3x3 -> last 1x1 -> residual add on active patches, one launch)"] = (
+            stage_us["conv2"], P * S * S * 2.0 * 13.0 * m * m)
+    else:
+        kern["conv2 (3x3 on active patches)"] = (stage_us["conv2"], P * S * S * 2.0 * 9.0 * m * m)
+        kern["conv3 (last 1x1 + residual add)"] = (stage_us["conv3"], P * S * S * 2.0 * 4.0 * m * m)
+    per_kernel = {k: {"avg_us": round(us, 2), "flops_per_launch": fl, "TFLOP_per_s": round(fl / us / 1e6, 1),
+                      "frac_of_peak": round(fl / us / 1e6 / PEAK_BF16_TFLOPS, 4)} for k, (us, fl) in kern.items()}
+    dom = max(kern, key=lambda k: kern[k][0])
+    dom_us, dom_flops = kern[dom]
+    achieved = dom_flops / (dom_us * 1e-6) / 1e12
+    at_default = abs(a.ratio - 0.5) < 1e-9 and N == 128 and a.variant == "fused"
+    roofline = {"bound": "mfma", "kernel": dom,
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": CONV2_TRAFFIC_BYTES_R050_B128 if (abs(a.ratio - 0.5) < 1e-9 and N == 128) else None,
-                "flops_per_launch": conv2_flops, "avg_us": round(conv2_us, 2)}
+                "traffic": traffic_from_profile("k_tail" if fused_tail else "conv2") if at_default else None,
+                "flops_per_launch": dom_flops, "avg_us": round(dom_us, 2),
+                # the whole step: useful FLOPs (17 m^2 MACs per active pixel) over p50 latency and the bf16 peak
+                "step_useful_flops": useful_flops(P), "step_p50_us": round(p50 * 1e3, 1),
+                "step_frac_useful": round(useful_flops(P) / (p50 * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+                "per_kernel": per_kernel}
 
     # ---- the other variant, for context (p50 only) ----------------------------------------------------
     other = "two-call" if a.variant == "fused" else "fused"
@@ -738,36 +804,41 @@ def main():
     other_p50 = lato[len(lato) // 2]
     variant[0] = a.variant
 
-    # ---- latency vs activation ratio -------------------------------------------------------------
-    sweep = []
-    if a.sweep_steps > 0:
+    # ---- latency vs activation ratio, for both entry points -----------------------------------------------
+    def run_sweep(var):
+        variant[0] = var
+        pts = []
         k = min(a.sweep_steps, a.steps)
         wu = min(a.warmup, 5)
         for r in (0.0, 0.25, 0.5, 0.75, 1.0):
             restore(k + wu)
             _, Pr, latr = timed(bias_of[r], k, wu, per_step_events=True)
             p = latr[len(latr) // 2]
-            sweep.append({"ratio_target": r, "active_patches": Pr, "ratio": round(Pr / npatch, 4),
-                          "p50_us": round(p * 1e3, 1), "p10_us": round(latr[len(latr) // 10] * 1e3, 1),
-                          "p90_us": round(latr[(9 * len(latr)) // 10] * 1e3, 1),
-                          "images_per_s": round(N / (p * 1e-3), 0),
-                          "mfma_frac_useful": round(useful_flops(Pr) / (p * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
-                          # latency predictor re-parameterised for MI355X (Sec. 3.3, App. A): host arithmetic only
-                          "predicted_us": round(PRED.predict_block(
-                              PRED.MI355X, "spatial", n=N, hw_px=H, c_in=C, m=m, S=S, r=Pr / npatch,
-                              fused_masker=(a.variant == "fused"))["total_s"] * 1e6, 1)})
-        rs = np.array([s["ratio"] for s in sweep])
-        ls = np.array([s["p50_us"] for s in sweep])
+            pts.append({"ratio_target": r, "active_patches": Pr, "ratio": round(Pr / npatch, 4),
+                        "p50_us": round(p * 1e3, 1), "p10_us": round(latr[len(latr) // 10] * 1e3, 1),
+                        "p90_us": round(latr[(9 * len(latr)) // 10] * 1e3, 1),
+                        "images_per_s": round(N / (p * 1e-3), 0),
+                        "mfma_frac_useful": round(useful_flops(Pr) / (p * 1e-3) / (PEAK_BF16_TFLOPS * 1e12), 4),
+                        # latency predictor re-parameterised for MI355X (Sec. 3.3, App. A): host arithmetic only
+                        "predicted_us": round(PRED.predict_block(
+                            PRED.MI355X, "spatial", n=N, hw_px=H, c_in=C, m=m, S=S, r=Pr / npatch,
+                            fused_masker=(var == "fused"))["total_s"] * 1e6, 1)})
+        variant[0] = a.variant
+        rs = np.array([s_["ratio"] for s_ in pts])
+        ls = np.array([s_["p50_us"] for s_ in pts])
         A = np.stack([np.ones_like(rs), rs], 1)
         coef, *_ = np.linalg.lstsq(A, ls, rcond=None)
         res = ls - A @ coef
         r2 = 1.0 - float(res @ res) / float(((ls - ls.mean()) ** 2).sum() or 1.0)
-        fit = {"intercept_us": round(float(coef[0]), 1), "slope_us_per_unit_ratio": round(float(coef[1]), 1),
-               "r2": round(r2, 4),
-               "predictor_mean_abs_rel_err": round(float(np.mean([abs(s_["predicted_us"] - s_["p50_us"]) / s_["p50_us"]
-                                                                   for s_ in sweep])), 3)}
-    else:
-        fit = None
+        return pts, {"intercept_us": round(float(coef[0]), 1), "slope_us_per_unit_ratio": round(float(coef[1]), 1),
+                     "r2": round(r2, 4),
+                     "predictor_mean_abs_rel_err": round(float(np.mean([abs(s_["predicted_us"] - s_["p50_us"]) / s_["p50_us"]
+                                                                         for s_ in pts])), 3)}
+
+    sweep, fit, sweep_other, fit_other = [], None, [], None
+    if a.sweep_steps > 0:
+        sweep, fit = run_sweep(a.variant)
+        sweep_other, fit_other = run_sweep(other)
 
     # ---- short measurements of the other entry points and stage shapes (context, 20 launches each) ----
     extras = None
@@ -818,7 +889,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "BASELINE config 2: stage-3 dynamic bottleneck, x 128x14x14x1024 NHWC bf16, "
                                "mid 256, S=2 (7x7 patch grid), mask from the pooled 1x1 masker, bias calibrated "
-                               "to the target ratio; in place; one pristine cache-cold copy of x per step; entry point: "
+                               "to the target ratio; in place; one pristine cache-cold copy of x per step; weights "
+                               "resident in the layout the kernels stream (laud_pack_weights once, as at model "
+                               "load; per-call re-ordering is timed in extras); entry point: "
                                + ("laud_masker_dyn_bottleneck" if a.variant == "fused"
                                   else "laud_mask_gen + laud_dyn_bottleneck"),
                    "global_batch": N, "activation_ratio": round(P / npatch, 4), "active_patches": P},
@@ -830,6 +903,7 @@ def main():
         "cpu_baseline": cpu,
         "sweep": sweep,
         "latency_fit": fit,
+        "sweep_other_variant": {"variant": other, "points": sweep_other, "latency_fit": fit_other},
         "extras": extras,
     }
     print(json.dumps(out))

@@ -377,11 +377,13 @@ const char* laud_stage_name(int stage);
  * can be read against besides the published peaks.  laud_probe_mfma launches `blocks` workgroups of 8 waves that
  * each issue 4*iters MFMAs (32x32x16 bf16, or the same FLOPs as 32x32x2 float32 steps) on register operands and
  * stores the FLOPs of the launch in *flops (host, may be NULL); sink is a device word nobody reads.
- * laud_probe_copy copies `bytes` (a multiple of 16, both pointers 16-byte aligned) with a plain grid-stride kernel.
- * Both only enqueue on `stream`; the caller times them with events.
+ * laud_probe_copy copies `bytes` (a multiple of 16, both pointers 16-byte aligned) with a plain grid-stride kernel;
+ * laud_probe_read only reads them (sink: at least 16 device words nobody reads).
+ * All only enqueue on `stream`; the caller times them with events.
  */
 int laud_probe_mfma(int dtype, int iters, int blocks, double* flops, float* sink, void* stream);
 int laud_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int laud_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 
 #ifdef __cplusplus
 }

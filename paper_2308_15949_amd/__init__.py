@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     laud_dyn_bottleneck_unfused, dyn_bottleneck_unfused_workspace, laud_static_bottleneck,
     static_bottleneck_workspace, laud_stem, laud_stem3x3, stem_workspace, laud_dyn_projection_bottleneck,
     dyn_projection_workspace, GroupSE, laud_dyn_group_se_bottleneck, laud_dyn_group_se_projection_bottleneck, make_group_se,
-    laud_stage_timing_enable, laud_stage_timing_read, load, laud_init, laud_dyn_bottleneck_noalloc, laud_probe_mfma, laud_probe_copy, laud_pack_weights, packed_weights_size,
+    laud_stage_timing_enable, laud_stage_timing_read, load, laud_init, laud_dyn_bottleneck_noalloc, laud_probe_mfma, laud_probe_copy, laud_probe_read, laud_pack_weights, packed_weights_size,
     make_bottleneck, status_string, workspace_size,
 )

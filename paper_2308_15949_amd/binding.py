@@ -24,7 +24,7 @@ EXPORTS = ["laud_status_string", "laud_abi_version", "laud_workspace_size", "lau
            "laud_dyn_bottleneck_unfused_workspace", "laud_static_bottleneck", "laud_static_bottleneck_workspace",
            "laud_stem", "laud_stem3x3", "laud_stem_workspace", "laud_dyn_projection_bottleneck", "laud_dyn_projection_workspace",
            "laud_dyn_group_se_bottleneck", "laud_dyn_group_se_projection_bottleneck", "laud_stage_timing_enable", "laud_stage_timing_read", "laud_stage_name",
-           "laud_init", "laud_dyn_bottleneck_noalloc", "laud_probe_mfma", "laud_probe_copy",
+           "laud_init", "laud_dyn_bottleneck_noalloc", "laud_probe_mfma", "laud_probe_copy", "laud_probe_read",
            "laud_packed_weights_size", "laud_pack_weights"]
 STAGE_COUNT = 13
 
@@ -80,6 +80,8 @@ def load() -> C.CDLL:
     lib.laud_dyn_bottleneck.argtypes = [vp, Fmap, C.POINTER(Bottleneck), i32, vp, vp, vp, vp, sz, vp]
     lib.laud_probe_mfma.restype = i32
     lib.laud_probe_mfma.argtypes = [i32, i32, i32, C.POINTER(C.c_double), vp, vp]
+    lib.laud_probe_read.restype = i32
+    lib.laud_probe_read.argtypes = [vp, sz, vp, vp]
     lib.laud_probe_copy.restype = i32
     lib.laud_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.laud_packed_weights_size.restype = sz
@@ -234,6 +236,10 @@ def laud_probe_mfma(dtype: int, iters: int, blocks: int, sink) -> float:
 
 def laud_probe_copy(src, dst, nbytes: int) -> None:
     _check(load().laud_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream()), "laud_probe_copy")
+
+
+def laud_probe_read(src, nbytes: int, sink) -> None:
+    _check(load().laud_probe_read(_ptr(src), int(nbytes), _ptr(sink), _stream()), "laud_probe_read")
 
 
 def laud_init() -> None:

@@ -93,9 +93,8 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
     for (int i = 0; i < kAI; ++i)
       dma16(xrs, s < NSL ? voffA[i] : kOob, soff, ldsA + (unsigned)(s & (kARing - 1)) * kAStage + i * 8192);
   };
-  issue_A(0);
-  issue_A(1);
-  issue_A(2);
+#pragma unroll
+  for (int s = 0; s < kARing - 1; ++s) issue_A(s);
 
   unsigned swz[4];
   {
@@ -124,9 +123,10 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   read_frags(0, 0, 0);
 
   // Four slices = sixteen K steps with static register indices.  Vector-memory operations of a wave in program
-  // order, per slice s: A(s+3) x kAI [middle of s], W(s+4) x4 [end of s].  Needed at the barrier of slice s: A(s+1),
-  // issued two slices earlier -- W(s+2), A(s+2), W(s+3) are younger: 8 + kAI loads.  Loads past the last slice are
-  // issued all the same so that the count holds to the end.
+  // order, per slice s: A(s+R-1) x kAI [middle of s], W(s+4) x4 [end of s], R = kARing.  Needed at the barrier of
+  // slice s: A(s+1), issued R-2 slices earlier -- R-2 weight slices and R-3 activation slices are younger.  Loads
+  // past the last slice are issued all the same so that the count holds to the end.  (A deeper ring, R = 8, measured
+  // slower: 27.8 against 25.4 us at 128 x 14 x 14 x 1024.)
   for (int s0 = 0; s0 < NSL; s0 += 4) {
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
@@ -155,9 +155,9 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
       if (kg == 1) {
-        vm_wait<8 + kAI>();
+        vm_wait<4 * (kARing - 2) + (kARing - 3) * kAI>();
         wg_barrier();
-        issue_A(s + 3);
+        issue_A(s + kARing - 1);
       }
       if (kg == 3) {
         load_W(g / 4, s + kWRing);
