@@ -175,6 +175,10 @@ struct HeadArgs {
   int m_rows, K;
   const float* wmask;    // masker weights [K] or null
   float* proj;           // [m_rows] per-pixel projection (with wmask)
+  // sparse form (the gather fused into the first 1x1): rows are pixel ids taken from per-group lists; list == null: dense
+  const int32_t* list;   // [ngroups][group_rows] ascending pixel ids of the dilated active set
+  const int32_t* counts; // [ngroups] device: valid entries per group
+  int group_rows, tiles_per_group;
 };
 bool head_supported(int dtype, int c_in, int c_mid);
 int head_init_device();

@@ -1059,6 +1059,20 @@ static void attach_tail_pack(GemmArgs& a, int dtype, const laud_bottleneck* p, c
   a.pk_chunks = tail::packed_slices(p->c_out) * tail::kSliceChunks;
 }
 
+// The first 1x1 over the dilated active set (rows = pixel ids from the per-group lists) with the register-weight
+// kernel; without caller-packed weights both packed parts are made here, ahead of it.
+static int launch_sparse_head(int dtype, const laud_bottleneck* p, const void* x, void* h1, const int32_t* pix,
+                              const int32_t* need_counts, int group_rows, int ngroups, void* wpack, hipStream_t st) {
+  int rc;
+  if (!p->packed && (rc = pack_weights_into(dtype, p, wpack, true, true, st)) != LAUD_OK) return rc;
+  HeadArgs h{};
+  h.x = x; h.wpacked = (const char*)(p->packed ? p->packed : wpack) + packed_layout(dtype, p).head;
+  h.s1 = p->s1; h.t1 = p->t1; h.h1 = h1; h.m_rows = ngroups; h.K = p->c_in;
+  h.list = pix; h.counts = need_counts; h.group_rows = group_rows;
+  h.tiles_per_group = (group_rows + 127) / 128;
+  return launch_head(h, st);
+}
+
 // conv2 -> conv3 -> residual add as one kernel where laud_tail.hip covers the shape (h2 stays in LDS).
 // Returns 1 when that kernel was launched (*rc = its status), 0 when the caller has to run the two GEMMs.
 static int try_tail(int dtype, const laud_bottleneck* p, const laud_group_se* e, const void* h1, const void* res,
@@ -1122,9 +1136,13 @@ static int run_dyn_block(const void* x, laud_fmap fx, const laud_bottleneck* p, 
   a.A = x; a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.K = p->c_in; a.ldw = p->c_in; a.Ncols = p->c_mid;
   a.lda = p->c_in; a.ldo = p->c_mid; a.relu = 1;
-  attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
-  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
-  a.pk_out = nullptr;
+  if (!e && head_wanted(fx.dtype, p)) {
+    if ((rc = launch_sparse_head(fx.dtype, p, x, h1, pix, need_counts, gs * hw, ngroups, wsb + L.wpack, st)) != LAUD_OK) return rc;
+  } else {
+    attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
+    if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+    a.pk_out = nullptr;
+  }
   if (try_tail(fx.dtype, p, e, h1, x, out, idx, count, fx.H, fx.W, S, 1, fx.H, fx.W, npix, wsb + L.wpack, st, &rc)) return rc;
   // conv2: 3x3 over active patches, A rows fetched from h1 by index -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;
@@ -1453,9 +1471,13 @@ static int run_dyn_projection(const void* x, laud_fmap fx, const laud_bottleneck
   // conv1 over that set -> h1 at input pixel positions
   a.Wt = p->w1; a.scale = p->s1; a.shift = p->t1; a.Out = h1; a.Res = nullptr;
   a.count = need_counts; a.list = pix; a.group_rows = gs * hw; a.Ncols = p->c_mid; a.ldo = p->c_mid; a.relu = 1;
-  attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
-  if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
-  a.pk_out = nullptr;
+  if (!e && head_wanted(fx.dtype, p)) {
+    if ((rc = launch_sparse_head(fx.dtype, p, x, h1, pix, need_counts, gs * hw, ngroups, wsb + L.wpack, st)) != LAUD_OK) return rc;
+  } else {
+    attach_tail_pack(a, fx.dtype, p, e, wsb + L.wpack);
+    if ((rc = launch_gemm<M_CONV1>(fx.dtype, a, (long long)gs * hw, ngroups, st)) != LAUD_OK) return rc;
+    a.pk_out = nullptr;
+  }
   if (try_tail(fx.dtype, p, e, h1, out, out, idx, count, fx.H, fx.W, S, stride, Ho, Wo, nout, wsb + L.wpack, st, &rc)) return rc;
   // conv2: strided 3x3 at the active output pixels -> dense h2
   a.A = h1; a.Wt = p->w2; a.scale = p->s2; a.shift = p->t2; a.Out = h2;

@@ -30,7 +30,8 @@ constexpr int kAI = kPB / 2;                  // LDS-direct instructions per wav
 constexpr int kTabOff = kARing * kAStage;     // s1, t1 [256] floats, masker weights [K] floats, partial sums [8][kBM]
 constexpr unsigned kOob = 0x80000000u;
 constexpr int kMaxK = 4096;
-__host__ __device__ constexpr int lds_bytes(int K) { return kTabOff + 2 * kMid * 4 + K * 4 + kWaves * kBM * 4; }
+// ... then the output rows of the tile (int)
+__host__ __device__ constexpr int lds_bytes(int K) { return kTabOff + 2 * kMid * 4 + K * 4 + kWaves * kBM * 4 + kBM * 4; }
 }  // namespace head
 
 // w1 [256][K] in MFMA fragment order: slice b (K chunk of 64), wave w, K step kg, lane l hold the 16 bytes
@@ -53,12 +54,26 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   float* const s_t1 = s_s1 + kMid;
   float* const s_wm = s_t1 + kMid;
   float* const s_part = s_wm + a.K;
+  int* const s_orow = reinterpret_cast<int*>(s_part + kWaves * kBM);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l31 = lane & 31, lhi = lane >> 5, l8 = lane >> 3, l7 = lane & 7;
   const int K = a.K, NSL = K / 64;
-  const int row0 = blockIdx.x * kBM;
+  // dense: workgroup b takes rows 128b ..; sparse: the pixel lists are kept per group of samples, workgroup b takes
+  // tile b % tiles_per_group of group b / tiles_per_group (list entries requested together with the group's count)
+  int row0 = blockIdx.x * kBM, M = a.m_rows;
+  const int32_t* listp = nullptr;
+  int pixsp[kAI];
+  if (a.list != nullptr) {
+    const int g = blockIdx.x / a.tiles_per_group;
+    row0 = (blockIdx.x - g * a.tiles_per_group) * kBM;
+    listp = a.list + (size_t)g * a.group_rows;
+#pragma unroll
+    for (int i = 0; i < kAI; ++i) pixsp[i] = listp[min(row0 + 64 * i + 8 * wave + l8, a.group_rows - 1)];
+    M = a.counts[g];
+    if (row0 >= M) return;
+  }
 
   // ---- weight stream: four slices in registers -------------------------------------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
@@ -81,9 +96,12 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   unsigned voffA[kAI];
 #pragma unroll
   for (int i = 0; i < kAI; ++i) {
-    const int rho = row0 + 64 * i + 8 * wave + l8;
+    const int r = 64 * i + 8 * wave + l8;
+    const int rho = row0 + r;
     const unsigned c = (unsigned)l7 ^ ((unsigned)(l8 & 7) ^ (wave & 1u));
-    voffA[i] = rho < a.m_rows ? (unsigned)rho * (unsigned)(K * 2) + c * 16u : kOob;
+    const int pixel = rho < M ? (listp ? pixsp[i] : rho) : -1;
+    voffA[i] = pixel >= 0 ? (unsigned)pixel * (unsigned)(K * 2) + c * 16u : kOob;
+    if (l7 == 0) s_orow[r] = pixel;
   }
   const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(a.x), 0, (int)kOob, 0x00020000);
   const unsigned ldsA = wave * 1024;
@@ -185,9 +203,9 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
       to_consecutive_channels(v);
       const uint4 c0 = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[8], v[9]), pack_bf16(v[10], v[11]));
       const uint4 c1 = make_uint4(pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]), pack_bf16(v[12], v[13]), pack_bf16(v[14], v[15]));
-      const int rho = row0 + 32 * t + l31;
-      if (rho < a.m_rows) {
-        uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)rho * kMid + cb + lhi * 16);
+      const int pixel = s_orow[32 * t + l31];
+      if (pixel >= 0) {
+        uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)pixel * kMid + cb + lhi * 16);
         dst[0] = c0;
         dst[1] = c1;
       }
@@ -203,11 +221,11 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
     }
     lds_wait();
     wg_barrier();
-    if (tid < kBM && row0 + tid < a.m_rows) {
+    if (tid < kBM && s_orow[tid] >= 0) {
       float p = 0.f;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) p += s_part[w * kBM + tid];
-      a.proj[row0 + tid] = p;
+      a.proj[s_orow[tid]] = p;
     }
   }
 }
@@ -243,7 +261,8 @@ int launch_head(const HeadArgs& a, hipStream_t st) {
     if (head_init_device() != LAUD_OK) return LAUD_ERR_HIP;
     done.fetch_or(bit, std::memory_order_release);
   }
-  const unsigned grid = (unsigned)((a.m_rows + head::kBM - 1) / head::kBM);
+  // dense: m_rows rows; sparse: m_rows = number of groups, each with tiles_per_group tiles
+  const unsigned grid = a.list ? (unsigned)(a.m_rows * a.tiles_per_group) : (unsigned)((a.m_rows + head::kBM - 1) / head::kBM);
   StageScope scope(LAUD_STAGE_CONV1, st);
   if (a.wmask)
     hipLaunchKernelGGL((k_head<true>), dim3(grid), dim3(head::kThreads), head::lds_bytes(a.K), st, a);
