@@ -52,7 +52,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-extras", action="store_true", help="skip the short per-entry-point measurements")
-    ap.add_argument("--extras-only", choices=["regnety"], default=None,
+    ap.add_argument("--extras-only", choices=["regnety", "stages"], default=None,
                     help="run only this group of the short measurements (for profiling one group)")
     ap.add_argument("--variant", choices=["fused", "two-call"], default="fused",
                     help="fused: laud_masker_dyn_bottleneck (masker fused into a static conv1); "
@@ -243,7 +243,7 @@ def measure_regnety(t, L, B, D, I):
     return ex
 
 
-def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm):
+def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm, only=None):
     """p50 of single entry points on rotating buffers; bytes and FLOPs are the algorithmic ones."""
     ex = {}
     nb = len(bufs)
@@ -389,6 +389,8 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                                                           "GB_per_s": round(xbytes_s / usm / 1e3, 0),
                                                           "hbm_frac": round(xbytes_s / usm / 1e3 / PEAK_HBM_GBS, 3)}
             del xb, xs
+    if only == "stages":   # (profiling runs: the masker, the gather and the per-stage blocks only)
+        return ex
     # spatially coherent masks (contiguous active regions, like learned masks) against independent patches at
     # the same ratio: the dilated set conv1 covers shrinks, so the sparse-conv1 path gains (config 2 geometry)
     sg = I.STAGES[3]
@@ -848,7 +850,7 @@ def main():
         if a.extras_only == "regnety":
             extras = measure_regnety(t, L, B, D, I)
         else:
-            extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm)
+            extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm, only=a.extras_only)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload --------
     cpu = None

@@ -303,3 +303,16 @@ def test_no_environment_variable_is_read():
         if name.endswith((".hip", ".h")):
             with open(os.path.join(ROOT, "paper_2308_15949_amd", "csrc", name)) as f:
                 assert "getenv" not in f.read(), name
+
+
+def test_bench_reads_traffic_from_the_committed_counter_summary():
+    """roofline.traffic comes from profiles/: the summary of the FETCH_SIZE / WRITE_SIZE runs carries one
+    machine-readable line per kernel, and bench.py finds the dominant kernel's."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    v = mod.traffic_from_profile("k_tail")
+    assert v is not None and 4e7 < v < 2e8   # tens of MB per launch at batch 128, ratio 0.5
+    assert mod.traffic_from_profile("k_head") is not None
+    assert mod.traffic_from_profile("no_such_kernel") is None
