@@ -156,6 +156,8 @@ struct TailArgs {
   int stride, Ho, Wo;    // spatial stride of the 3x3 and the output grid (stride 1: Ho = H, Wo = W)
   int cout;
   int relu;
+  int pb;                // tile height in blocks of 32 pixels (1..3); 0 = chosen on the device from the count
+  int wg_target;         // workgroups that fill the device once (its compute units; set by launch_tail)
 };
 
 bool tail_supported(int dtype, int c_mid, int c_out);

@@ -2,21 +2,22 @@
 // output tile h2 never leaves the CU (Sec. 3.4 operator fusion; App. B items 2-3: gather inside the 3x3, scatter-add
 // in the last 1x1).  bf16 operands, float32 accumulation; c_mid = 256, c_out a multiple of 256.
 //
-// One workgroup = 64 active pixels (rows of the compact list: active patch x pixel in patch) x all 256 mid channels,
-// 8 waves (two per SIMD).  Wave w owns mid channels 32w .. 32w+31 of the 3x3 and, per 256-wide column tile of the
-// last 1x1, output channels 32w .. 32w+31 of that tile, for all 64 pixels: the weight rows a wave multiplies are the
-// rows it loads itself, so weights need no barrier; only the activation slices (loaded cooperatively) do.
+// One workgroup = 32, 64 or 96 active pixels (rows of the compact list: active patch x pixel in patch; the height is
+// chosen on the device from the count, see k_tail) x all 256 mid channels, 8 waves (two per SIMD).  Wave w owns mid
+// channels 32w .. 32w+31 of the 3x3 and, per 256-wide column tile of the last 1x1, output channels 32w .. 32w+31 of
+// that tile, for all pixels of the tile: the weight rows a wave multiplies are the rows it loads itself, so weights
+// need no barrier; only the activation slices (loaded cooperatively) do.
 //
 //   * Operands reach LDS with LDS-direct 16-byte buffer loads (no VGPR staging, no ds_write): a wave instruction
 //     drops 64 x 16 bytes = 8 rows of a 128-byte K slice.  Bank conflicts are avoided by an XOR swizzle of the 16-byte
 //     chunk position applied on the global side: chunk c of row r lies at position c ^ (r&7) ^ ((r>>3)&1).
-//   * Rings: 4 activation stages (8 KB each), 3 weight stages (32 KB each).  One barrier per slice, placed in the
+//   * Rings: 4 activation stages (4 KB per 32 pixels each), 3 weight stages (32 KB each, in registers).  One barrier per slice, placed in the
 //     middle of the slice's MFMAs; fragments of the next K step (also across slices) are read before the current
 //     step's MFMAs are issued.
 //   * The MFMAs compute the transposed tile (weights as the first operand): a lane then holds, for one pixel,
 //     4 x 4 consecutive channels; one v_permlane32_swap per register pair turns that into 16 consecutive channels
 //     per lane, so h2 goes to LDS, and the result to memory, in 16-byte pieces without an LDS transpose.
-//   * h2 (64 x 256 bf16) overlays the activation ring once the 3x3 is done; the last 1x1 streams w3 through the
+//   * h2 (pixels x 256 bf16) sits behind the activation ring in LDS; the last 1x1 streams w3 through the
 //     same weight ring (no barrier at all in that phase), reads the residual 32 bytes per lane and pixel, adds,
 //     applies the activation, rounds and stores.
 //
@@ -33,17 +34,17 @@
 namespace laud {
 
 namespace tail {
-constexpr int kPB = 2;                        // 32-pixel blocks per workgroup (and per wave)
-constexpr int kBM = 32 * kPB;                 // pixels per workgroup
-constexpr int kAStage = kBM * 128;            // one 128-byte K slice of every pixel row
+// A workgroup takes PB blocks of 32 pixels (PB = 1 .. 3, chosen per launch on the device from the number of active
+// pixels, see k_tail); the LDS layout depends on it.
+constexpr int kMaxPB = 3;
 constexpr int kARing = 4;
-constexpr int kAOff = 0;                      // activation ring
-constexpr int kH2Off = kARing * kAStage;      // h2 tile: kBM pixels x 512 bytes
-constexpr int kTabOff = kH2Off + kBM * kMid * 2;
 constexpr int kWRing = 3;                     // weight slices held / in flight in registers
 constexpr unsigned kOob = 0x80000000u;        // offset outside every descriptor: reads as zero
-// float tables in LDS behind the tiles: s2, t2 [256], then s3, t3 [cout], then kBM output rows (int)
-__host__ __device__ constexpr int lds_bytes(int cout) { return kTabOff + (2 * kMid + 2 * cout) * 4 + kBM * 4; }
+__host__ __device__ constexpr int a_stage(int pb) { return 32 * pb * 128; }        // one 128-byte K slice of every pixel row
+__host__ __device__ constexpr int h2_off(int pb) { return kARing * a_stage(pb); }  // h2 tile: 32*pb pixels x 512 bytes
+__host__ __device__ constexpr int tab_off(int pb) { return h2_off(pb) + 32 * pb * kMid * 2; }
+// float tables in LDS behind the tiles: s2, t2 [256], then s3, t3 [cout], then the tile's output rows (int)
+__host__ __device__ constexpr int lds_bytes(int pb, int cout) { return tab_off(pb) + (2 * kMid + 2 * cout) * 4 + 32 * pb * 4; }
 }  // namespace tail
 
 __global__ __launch_bounds__(256) void k_pack_tail_weights(const uint4* __restrict__ w2, const uint4* __restrict__ w3,
@@ -63,13 +64,21 @@ __device__ long long g_tail_fine[8 * 64];
 #define TAIL_FINE(i) do { } while (0)
 #endif
 
-template <int NCT>  // column tiles of 256 output channels (cout = 256 * NCT)
-__global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
+// One tile: rows row0 .. row0 + 32*PB - 1 of the compact list of active pixels (M rows exist).
+template <int NCT, int PB>  // NCT column tiles of 256 output channels (cout = 256 * NCT)
+__device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, const int M) {
   using namespace tail;
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int COUT = 256 * NCT;
+  constexpr int kBM = 32 * PB;
+  constexpr int kAStage = a_stage(PB), kAOff = 0, kH2Off = h2_off(PB), kTabOff = tab_off(PB);
   constexpr int kNB = kSl2 + NCT * kKch;  // slices in the weight stream
-  constexpr int kAI = kPB / 2;            // LDS-direct instructions per wave and activation slice (8 rows each)
+  // LDS-direct instructions per wave and activation slice: an instruction of all eight waves covers 64 rows; with an
+  // odd PB the last one is issued by waves 0-3 only
+  constexpr int kAI = (PB + 1) / 2;
+  // Two accumulator sets (the epilogue of a column tile behind the next tile's MFMAs) while the registers allow it:
+  // three pixel blocks keep one set and run the epilogue after its tile
+  constexpr bool DUAL = PB <= 2;
   float* const s_s2 = reinterpret_cast<float*>(smem + kTabOff);
   float* const s_t2 = s_s2 + kMid;
   float* const s_s3 = s_t2 + kMid;
@@ -79,18 +88,13 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l31 = lane & 31, lhi = lane >> 5, l8 = lane >> 3, l7 = lane & 7;
+  const bool lastA = !(PB & 1) || wave < 4;  // this wave takes part in the last activation instruction of a slice
 
-  // ---- which tile: workgroup b takes rows 64b ..; the count is only needed to tell which rows exist, so the index
-  // list entries of this tile are requested together with it (the list's capacity covers every workgroup of the
-  // grid; entries past the count are read but never used) --------------------------------------------------------
   TAIL_STAMP(0);
   const int SS = a.S * a.S;
-  const int row0 = blockIdx.x * kBM;
-  int qsp[kPB / 2];
+  int qsp[kAI];
 #pragma unroll
-  for (int i = 0; i < kPB / 2; ++i) qsp[i] = a.list[min((row0 + 64 * i + 8 * wave + l8) / SS, a.cap_patches - 1)];
-  const int M = *a.count * SS;
-  if (row0 >= M) return;
+  for (int i = 0; i < kAI; ++i) qsp[i] = a.list[min((row0 + 64 * i + 8 * wave + l8) / SS, a.cap_patches - 1)];
   // ---- weight stream: three slices in registers (one in use, two in flight) ------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
@@ -117,6 +121,7 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     voffA[i] = 0; amask[i] = 0;
     const int r = 64 * i + 8 * wave + l8;
     const int rho = row0 + r;
+    if (r >= kBM) continue;
     if (rho < M) {
       const int p = rho / SS, j = rho - p * SS;
       const int q = qsp[i];
@@ -150,6 +155,7 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     const unsigned soff = (unsigned)((ky * a.W + kx) * kMid + kc * 64) * 2u;
 #pragma unroll
     for (int i = 0; i < kAI; ++i) {
+      if (i == kAI - 1 && !lastA) break;
       const unsigned v = (tap < 9 && ((amask[i] >> tap) & 1u)) ? voffA[i] : kOob;  // (slices past the 3x3: zeros)
       dma16(h1rs, v, soff, ldsA + (unsigned)(s & (kARing - 1)) * kAStage + i * 8192);
     }
@@ -166,17 +172,17 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
     for (int kg = 0; kg < 4; ++kg) swz[kg] = (unsigned)l31 * 128u + (((2u * kg + lhi) ^ f) << 4);
   }
 
-  f32x16 acc[kPB];
+  f32x16 acc[PB];
 #pragma unroll
-  for (int t = 0; t < kPB; ++t)
+  for (int t = 0; t < PB; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
-  uint4 fa[2][kPB];  // activation fragments of the pixel blocks, read one K step ahead of their MFMAs
+  uint4 fa[2][PB];  // activation fragments of the pixel blocks, read one K step ahead of their MFMAs
   auto read_frags2 = [&](int buf, int s, int kg) __attribute__((always_inline)) {
     const unsigned char* pa = smem + kAOff + (unsigned)(s & (kARing - 1)) * kAStage + swz[kg];
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) fa[buf][t] = *reinterpret_cast<const uint4*>(pa + t * 4096);
+    for (int t = 0; t < PB; ++t) fa[buf][t] = *reinterpret_cast<const uint4*>(pa + t * 4096);
   };
 
   // ---- the 3x3 -----------------------------------------------------------------------------------------------
@@ -191,7 +197,7 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   // everyone is done with the slice before this one, whose stage is refilled (three slices ahead).
   // Vector-memory operations of a wave in program order, per slice s: A(s+3) x kAI [middle of s], W(s+3) x4 [end
   // of s].  Needed at the barrier of slice s: A(s+1), issued two slices earlier -- W(s+1), A(s+2), W(s+2) are
-  // younger: 8 + kAI loads.  Activation loads past the last slice are issued all the same (they read as zeros
+  // younger: 8 + (this wave's activation instructions per slice) loads.  Activation loads past the last slice are issued all the same (they read as zeros
   // into stages nobody reads any more) so that the count holds to the end.
   auto group2 = [&](int s0) __attribute__((always_inline)) {
 #pragma unroll
@@ -202,10 +208,10 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
       else if (s + 1 < kSl2) read_frags2((g + 1) & 1, s + 1, 0);
       __builtin_amdgcn_sched_barrier(0);  // the next step's fragment reads stay ahead of this step's MFMAs
 #pragma unroll
-      for (int t = 0; t < kPB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
+      for (int t = 0; t < PB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
       __builtin_amdgcn_sched_barrier(0);
       if (kg == 1) {
-        vm_wait<8 + kAI>();  // own part of the activations of slice s+1
+        if (lastA) vm_wait<8 + kAI>(); else vm_wait<8 + kAI - 1>();  // own part of the activations of slice s+1
         wg_barrier();        // everyone's; and everyone is done with slice s-1
         issue_A(s + 3);
       }
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   {
     const int cb = wave * 32;
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) {
+    for (int t = 0; t < PB; ++t) {
       float v[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -255,28 +261,33 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   // Two accumulator sets alternate between column tiles: while tile ct is multiplied into one, the other (tile
   // ct-1) goes through its epilogue -- affine, residual add, activation, rounding, store -- in half-block pieces
   // placed behind the MFMAs of tile ct's first K steps, so the vector ALU works in the shadow of the matrix pipe.
-  int orow[kPB];
+  int orow[PB];        // output row of this lane's pixel in block t (row 0 where the pixel does not exist: reads stay
+  unsigned exists = 0;  // in range, nothing is stored), and whether it exists
 #pragma unroll
-  for (int t = 0; t < kPB; ++t) orow[t] = s_orow[32 * t + l31];
+  for (int t = 0; t < PB; ++t) {
+    const int o = s_orow[32 * t + l31];
+    orow[t] = o < 0 ? 0 : o;
+    exists |= (o >= 0 ? 1u : 0u) << t;
+  }
   const unsigned hrow = kH2Off + (unsigned)l31 * 512u;  // h2 fragment rows: pixel block t at + t * 32 * 512
   const unsigned hx = (unsigned)(l31 & 15);
   auto read_frags3 = [&](int buf, int ks, int kg) __attribute__((always_inline)) {
     const unsigned c = (unsigned)(ks * 8 + 2 * kg) + lhi;
 #pragma unroll
-    for (int t = 0; t < kPB; ++t)
+    for (int t = 0; t < PB; ++t)
       fa[buf][t] = *reinterpret_cast<const uint4*>(smem + hrow + t * (32 * 512) + ((c ^ hx) << 4));
   };
   const float floor_ = a.relu ? 0.f : -__builtin_inff();  // the activation after the add as one max (NaN passes through)
   const __bf16* const resp = reinterpret_cast<const __bf16*>(a.res);
   __bf16* const outp = reinterpret_cast<__bf16*>(a.out);
-  f32x16 acc2[kPB];  // the second accumulator set (odd column tiles)
+  f32x16 acc2[DUAL ? PB : 1];  // the second accumulator set (odd column tiles)
 #pragma unroll
-  for (int t = 0; t < kPB; ++t)
+  for (int t = 0; t < (DUAL ? PB : 1); ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc2[t][e] = 0.f;
-  uint4 res[kPB][2];  // residual of the tile whose epilogue is pending: per pixel block, channels 0-7 / 8-15
+  uint4 res[PB][2];  // residual of the tile whose epilogue is pending: per pixel block, channels 0-7 / 8-15
 #pragma unroll
-  for (int t = 0; t < kPB; ++t) res[t][0] = res[t][1] = make_uint4(0, 0, 0, 0);
+  for (int t = 0; t < PB; ++t) res[t][0] = res[t][1] = make_uint4(0, 0, 0, 0);
 
   // Half a pixel block of the epilogue of column tile ct: accumulator groups h and h+2 of a lane (channels
   // 8h + 4*(lane/32) .. +3 and 16 + 8h + 4*(lane/32) .. +3) become, after four lane swaps, eight consecutive channels.
@@ -307,18 +318,12 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
       const float hi = fmaxf(x[2 * d + 1] + __uint_as_float(rv[d] & 0xffff0000u), floor_);
       pk[d] = pack_bf16(lo, hi);
     }
-    if (orow[t] >= 0)
+    if ((exists >> t) & 1u)
       *reinterpret_cast<uint4*>(outp + (size_t)orow[t] * COUT + cb + lhi * 16 + h * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
   };
-  auto load_residual = [&](int ct) __attribute__((always_inline)) {
-    const int cb = ct * 256 + wave * 32;
-#pragma unroll
-    for (int t = 0; t < kPB; ++t)
-      if (orow[t] >= 0) {
-        const uint4* rp = reinterpret_cast<const uint4*>(resp + (size_t)orow[t] * COUT + cb + lhi * 16);
-        res[t][0] = rp[0];
-        res[t][1] = rp[1];
-      }
+  // The 32 bytes of residual a lane needs for half a pixel block of column tile ct
+  auto load_residual_half = [&](int ct, int t, int h) __attribute__((always_inline)) {
+    res[t][h] = *reinterpret_cast<const uint4*>(resp + (size_t)orow[t] * COUT + ct * 256 + wave * 32 + lhi * 16 + h * 8);
   };
 
   read_frags3(0, 0, 0);
@@ -335,30 +340,72 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
       else if (b + 1 < kNB) read_frags3(nxt, (ks + 1) % kKch, 0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int t = 0; t < kPB; ++t) {
-        if (ct & 1) acc2[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc2[t]);
+      for (int t = 0; t < PB; ++t) {
+        if (DUAL && (ct & 1)) acc2[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc2[t]);
         else acc[t] = mma_bf16(wr[BUF][kg], fa[cur][t], acc[t]);
       }
-      // a piece of the previous tile's epilogue behind these MFMAs (odd steps 1, 3, ... : one half block each)
-      if (ct > 0 && (st & 1) && st / 2 < 2 * kPB) {
+      // Odd steps 1, 3, ...: one half pixel block each.  With two accumulator sets the previous tile's epilogue piece
+      // runs behind these MFMAs; the residual registers it frees are refilled at once with this tile's values, a
+      // whole tile ahead of their use.
+      if ((st & 1) && st / 2 < 2 * PB) {
         const int pi = st / 2, t = pi / 2, h = pi % 2;
-        if (ct & 1) epilogue_half(ct - 1, t, h, acc[t]); else epilogue_half(ct - 1, t, h, acc2[t]);
+        if constexpr (DUAL) {
+          if (ct > 0) { if (ct & 1) epilogue_half(ct - 1, t, h, acc[t]); else epilogue_half(ct - 1, t, h, acc2[t]); }
+        }
+        load_residual_half(ct, t, h);
       }
-      // this tile's residual, requested once the previous tile's has been used up
-      if (st == 4 * kPB) load_residual(ct);
       // the weight register just used is refilled for three slices later
       if (b + kWRing < kNB) wr[BUF][kg] = wsrc[(size_t)(b + kWRing) * kSliceChunks + kg * 64];
       __builtin_amdgcn_sched_barrier(0);
     }
-  }
-  // the last tile's epilogue
+    if constexpr (!DUAL) {  // one accumulator set: the epilogue follows its tile
 #pragma unroll
-  for (int pi = 0; pi < 2 * kPB; ++pi) {
-    const int t = pi / 2, h = pi % 2;
-    if ((NCT - 1) & 1) epilogue_half(NCT - 1, t, h, acc2[t]); else epilogue_half(NCT - 1, t, h, acc[t]);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int pi = 0; pi < 2 * PB; ++pi) {
+        epilogue_half(ct, pi / 2, pi % 2, acc[pi / 2]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+  if constexpr (DUAL) {  // the last tile's epilogue
+#pragma unroll
+    for (int pi = 0; pi < 2 * PB; ++pi) {
+      const int t = pi / 2, h = pi % 2;
+      if ((NCT - 1) & 1) epilogue_half(NCT - 1, t, h, acc2[t]); else epilogue_half(NCT - 1, t, h, acc[t]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   TAIL_STAMP(56);
+}
+
+// The tile height is chosen on the device, where the number of active patches is known.  A workgroup streams all
+// weights whatever its height, and one workgroup fits a compute unit, so the time of a launch is (rounds of
+// workgroups over the compute units) x (time of one tile); tiles of 32 / 64 / 96 pixels take about 3 : 4 : 6 time
+// units (measured; a small tile is bound by its weight stream, a large one by LDS fragment reads + MFMAs).  Every
+// workgroup evaluates the same three candidates and takes the cheapest: a small active set spreads over the whole
+// chip, a large one does not leave a nearly empty last round.
+template <int NCT>
+__global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
+  const int M = *a.count * a.S * a.S;
+  const int t32 = (M + 31) >> 5;
+  int pb = a.pb;
+  if (pb < 1 || pb > tail::kMaxPB) {
+    constexpr int kCost[tail::kMaxPB] = {3, 4, 6};
+    int best = 0x7fffffff;
+    pb = 1;
+#pragma unroll
+    for (int c = 1; c <= tail::kMaxPB; ++c) {
+      const int tiles = (t32 + c - 1) / c;
+      const int cost = ((tiles + a.wg_target - 1) / a.wg_target) * kCost[c - 1];
+      if (cost < best) { best = cost; pb = c; }
+    }
+  }
+  const int row0 = blockIdx.x * 32 * pb;
+  if (row0 >= M) return;
+  switch (pb) {
+    case 1: tail_tile<NCT, 1>(a, row0, M); break;
+    case 2: tail_tile<NCT, 2>(a, row0, M); break;
+    default: tail_tile<NCT, 3>(a, row0, M); break;
+  }
 }
 
 #ifdef LAUD_TAIL_DBG
@@ -378,9 +425,15 @@ bool tail_supported(int dtype, int c_mid, int c_out) {
 }
 size_t tail_packed_bytes(int c_mid, int c_out) { (void)c_mid; return align_up(tail::packed_bytes(c_out), 256); }
 
+static int g_tail_cus[32];  // compute units of device d (written before the device's bit in launch_tail's `done`)
+
 int tail_init_device() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return LAUD_ERR_HIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return LAUD_ERR_HIP;
+  g_tail_cus[dev] = cus;
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             tail::lds_bytes(1024)) == hipSuccess ? LAUD_OK : LAUD_ERR_HIP;
+                             tail::lds_bytes(tail::kMaxPB, 1024)) == hipSuccess ? LAUD_OK : LAUD_ERR_HIP;
 }
 
 int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hipStream_t st) {
@@ -391,19 +444,22 @@ int launch_tail_pack(const void* w2, const void* w3, int c_out, void* packed, hi
   return check_launch();
 }
 
-int launch_tail(const TailArgs& a, long long cap_rows, hipStream_t st) {
+int launch_tail(const TailArgs& args, long long cap_rows, hipStream_t st) {
   static std::atomic<unsigned> done{0};
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return LAUD_ERR_HIP;
-  const unsigned bit = dev >= 0 && dev < 32 ? 1u << dev : 0u;
-  if (!(bit && (done.load(std::memory_order_acquire) & bit))) {
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return LAUD_ERR_HIP;
+  const unsigned bit = 1u << dev;
+  if (!(done.load(std::memory_order_acquire) & bit)) {
     if (tail_init_device() != LAUD_OK) return LAUD_ERR_HIP;
     done.fetch_or(bit, std::memory_order_release);
   }
-  const long long tiles = (cap_rows + tail::kBM - 1) / tail::kBM;
-  const unsigned grid = (unsigned)tiles;
+  TailArgs a = args;
+  a.wg_target = g_tail_cus[dev];
+  // one workgroup per 32 rows of the capacity: enough for the smallest tile height; workgroups past the last tile
+  // of the height chosen on the device leave at once
+  const unsigned grid = (unsigned)((cap_rows + 31) / 32);
   StageScope scope(LAUD_STAGE_CONV2, st);
-  hipLaunchKernelGGL((k_tail<4>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(1024), st, a);
+  hipLaunchKernelGGL((k_tail<4>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(tail::kMaxPB, 1024), st, a);
   return check_launch();
 }
 
