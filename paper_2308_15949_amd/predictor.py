@@ -12,9 +12,11 @@ Here the PE is a compute unit (256 of them), its local memory the LDS, the on-ch
 L2 / Infinity Cache, peak throughput the MFMA rate of the arithmetic type, and the tile candidates
 are the ones the library's kernels are built for.  Host arithmetic only; nothing here touches the GPU.
 The three free constants (local-memory efficiency, per-kernel and per-tile constants) were set once from
-measured latencies (the ratio sweep of the stage-3 block and the granularity curves of the four stages at
-ratio 0.5, batch 128, bf16: 25 points, mean error 6 %, largest 17 %); every other number is a datasheet
-figure or follows from shapes.
+measured latencies of the LDS-staged kernels (the granularity curves of the four stages at ratio 0.5, batch 128,
+bf16); every other number is a datasheet figure or follows from shapes.  The 256-wide bf16 blocks run on
+register-weight kernels (128 x 256 tiles for the first 1x1; 3x3 and last 1x1 as one kernel whose tile moves both
+weight tensors once): they are modelled with their own tile shapes and the nominal local-memory rate, which is
+what their contiguous requests were measured to reach.
 """
 from __future__ import annotations
 
@@ -36,10 +38,12 @@ class Hardware:
     offchip_efficiency: float    # fraction of the off-chip bandwidth a short streaming kernel reaches
     const_s: float               # per-kernel constant (launch + first/last dependent memory round trips)
     tile_const_s: float = 0.0    # per tile a PE works through: the part of a tile's prologue / epilogue nothing hides
+    stream_efficiency: float = 1.0  # the same fraction for kernels that read pre-ordered weights straight into registers
+                                    # and rows straight into local memory (contiguous 1 KB requests: the nominal rate)
     tiles: tuple = field(default=((64, 64), (64, 128), (128, 128)))
 
-    def local_Bps(self) -> float:
-        return self.local_B_per_clk * self.clock_hz * self.local_efficiency
+    def local_Bps(self, streamed: bool = False) -> float:
+        return self.local_B_per_clk * self.clock_hz * (self.stream_efficiency if streamed else self.local_efficiency)
 
     def pe_flops(self, dtype: str) -> float:
         return self.flop_per_clk_pe[dtype] * self.clock_hz
@@ -76,7 +80,7 @@ class KernelPrediction:
 
 
 def _gemm(hw: Hardware, name: str, rows: int, cols: int, k: int, taps: int, eb: int, dtype: str,
-          a_offchip_bytes: float, residual: bool, tile=None) -> KernelPrediction:
+          a_offchip_bytes: float, residual: bool, tile=None, streamed: bool = False) -> KernelPrediction:
     """One tiled implicit GEMM [rows x (taps*k)] x [(taps*k) x cols] (App. A: shape definition, mapping
     of output tiles to PEs, latency estimation).  a_offchip_bytes: distinct activation bytes that come
     from off-chip memory; weights and outputs are added here."""
@@ -91,12 +95,39 @@ def _gemm(hw: Hardware, name: str, rows: int, cols: int, k: int, taps: int, eb: 
         off = a_offchip_bytes + taps * k * cols * eb + rows * cols * eb * (2 if residual else 1)
         kp = KernelPrediction(name, (bm, bn), n_tiles, per_pe, 2.0 * rows * cols * k * taps, off,
                               off / hw.offchip_Bps if rows > 0 else 0.0,
-                              per_pe * tile_bytes / hw.local_Bps(),
+                              per_pe * tile_bytes / hw.local_Bps(streamed),
                               per_pe * tile_flops / hw.pe_flops(dtype),
                               hw.const_s + per_pe * hw.tile_const_s)
         if best is None or kp.total < best.total:
             best = kp
     return best
+
+
+def _fused_tail(hw: Hardware, rows: int, m: int, c_out: int, eb: int, dtype: str, a_offchip_bytes: float) -> KernelPrediction:
+    """3x3 -> last 1x1 -> residual add as ONE kernel (what the library runs for 256-wide bf16 blocks): a tile is bm
+    pixels x all channels of both convolutions, h2 stays in local memory, and a PE moves both weight tensors once
+    per tile whatever its height; the tile height is searched over the kernel's candidates (App. A: tile shape
+    search), as the kernel itself does on the device."""
+    w_bytes = (9 * m * m + m * c_out) * eb
+    flops = 2.0 * rows * (9 * m * m + m * c_out)
+    off = a_offchip_bytes + w_bytes + 2.0 * rows * c_out * eb
+    best = None
+    for bm in (32, 64, 96):
+        n_tiles = math.ceil(rows / bm) if rows > 0 else 0
+        per_pe = math.ceil(n_tiles / hw.n_pe)
+        tile_bytes = w_bytes + bm * 9 * m * eb + 2 * bm * c_out * eb
+        tile_flops = 2.0 * bm * (9 * m * m + m * c_out)
+        kp = KernelPrediction("conv2 + conv3 + scatter-add (one kernel)", (bm, c_out), n_tiles, per_pe, flops, off,
+                              off / hw.offchip_Bps if rows > 0 else 0.0, per_pe * tile_bytes / hw.local_Bps(True),
+                              per_pe * tile_flops / hw.pe_flops(dtype), hw.const_s + per_pe * hw.tile_const_s)
+        if best is None or kp.total < best.total:
+            best = kp
+    return best
+
+
+def fused_shapes(c_in: int, m: int, dtype: str, group_width, se_width: int) -> bool:
+    """Blocks the library runs on its register-weight kernels (first 1x1 with 128 x 256 tiles; 3x3 and last 1x1 fused)."""
+    return dtype == "bf16" and m == 256 and c_in == 1024 and group_width is None and se_width == 0
 
 
 def _stream(hw: Hardware, name: str, nbytes: float) -> KernelPrediction:
@@ -142,17 +173,22 @@ def predict_block(hw: Hardware, paradigm: str, *, n: int, hw_px: int, c_in: int,
     if paradigm == "spatial":
         if r_dil is None:
             r_dil = expected_dilated_ratio(r, S)
+        fused = fused_shapes(c_in, m, dtype, group_width, se_width)
+        tile1 = (128, 256) if fused else None
         if with_masker and fused_masker:
             rows1, a_off = npix, float(npix * c_in * eb)
-            ks.append(_gemm(hw, "conv1 (every pixel) + masker projection", rows1, m, c_in, 1, eb, dtype, a_off, False))
+            ks.append(_gemm(hw, "conv1 (every pixel) + masker projection", rows1, m, c_in, 1, eb, dtype, a_off, False, tile=tile1, streamed=fused))
             ks.append(_stream(hw, "pool + threshold + index list", npix * 4.0))
         else:
             if with_masker:
                 ks.append(_stream(hw, "masker", float(npix * c_in * eb)))
                 ks.append(_stream(hw, "index list", float(npix // (S * S))))
             rows1 = int(round(r_dil * npix))
-            ks.append(_gemm(hw, "conv1 (dilated active set)", rows1, m, c_in, 1, eb, dtype, float(rows1 * c_in * eb), False))
+            ks.append(_gemm(hw, "conv1 (dilated active set)", rows1, m, c_in, 1, eb, dtype, float(rows1 * c_in * eb), False, tile=tile1, streamed=fused))
         rows = int(round(r * npix))
+        if fused:
+            ks.append(_fused_tail(hw, rows, m, c_in, eb, dtype, float(min(r_dil, 1.0) * npix * m * eb)))
+            return {"kernels": ks, "total_s": sum(k.total for k in ks), "flops": sum(k.flops for k in ks)}
         if group_width is None:
             ks.append(_gemm(hw, "conv2 (active patches)", rows, m, m, 9, eb, dtype, float(min(r_dil, 1.0) * npix * m * eb), False))
         else:
