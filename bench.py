@@ -52,7 +52,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-extras", action="store_true", help="skip the short per-entry-point measurements")
-    ap.add_argument("--extras-only", choices=["regnety", "stages"], default=None,
+    ap.add_argument("--extras-only", choices=["regnety", "stages", "bodies"], default=None,
                     help="run only this group of the short measurements (for profiling one group)")
     ap.add_argument("--variant", choices=["fused", "two-call"], default="fused",
                     help="fused: laud_masker_dyn_bottleneck (masker fused into a static conv1); "
@@ -243,6 +243,152 @@ def measure_regnety(t, L, B, D, I):
     return ex
 
 
+def measure_bodies(t, L, B, D, I):
+    """Whole-body runs (configurations 3 and 5 and the widened variants of 3)."""
+    ex = {}
+    # configurations 3 and 5 of the benchmark list: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
+    # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
+    # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.
+    #   config 3: batch 128, spatial maskers at granularity 4-4-2-1 in all stages, every masker's bias
+    #             calibrated to ratio 0.5 on the block's actual input
+    #   config 5: batch 256, a seeded Bernoulli(0.6) keep gate per sample and block (layer skipping: the kept
+    #             samples are compacted, S = H), AND-ed with spatial maskers (S = 2, ratio 0.5) in stage 3
+    def run_body(N, keep_p, spatial_stages, S_set=None, dyn_first=False, graph=True):
+        g = np.random.default_rng(7700)
+        img8 = I.round_to(g.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16)
+        img = D.to_device(img8, I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
+        w7 = D.to_device(I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), I.BF16), I.BF16)
+        s7 = t.from_numpy((1 + 0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
+        t7 = t.from_numpy((0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
+        x0 = t.empty((N, 56, 56, 64), dtype=t.bfloat16, device="cuda")
+        ws_stem = D.workspace(L.stem_workspace(N, 224, 224, 64, I.BF16))
+        ops = [lambda: L.laud_stem(img, N, 224, 224, I.BF16, w7, s7, t7, 64, x0, ws_stem)]
+        ops[0]()
+        cur, c_in, hw = x0, 64, 56
+        held = [img, w7, s7, t7, x0, ws_stem]
+        ndyn, act = 0, []
+        wc = D.workspace(4096)
+        for stage, nblk in ((1, 3), (2, 4), (3, 23), (4, 3)):
+            sg = I.STAGES[stage]
+            m, stride = sg["m"], (1 if stage == 1 else 2)
+            co = 4 * m
+            hw = (hw - 1) // stride + 1
+            spatial = stage in spatial_stages
+            Ss = (S_set[stage - 1] if S_set else sg["S"]) if spatial else hw
+            fin = L.fmap_of(cur)
+            dbp = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage, c_in, m, co, I.BF16, relu_out=True, s3_gain=0.5))
+            gs = np.random.default_rng(7801 + 100 * stage)
+            wsc = D.to_device(I.round_to(gs.standard_normal((co, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), I.BF16), I.BF16)
+            ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
+            tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
+            xs = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
+            if dyn_first:
+                # the first block of the stage dynamic as well: mask on the output grid (granularity S there), the
+                # masker pooling the input to the output patch grid, bias calibrated to ratio 0.5 on the actual input
+                S1 = S_set[stage - 1] if S_set else sg["S"]
+                np1 = N * (hw // S1) ** 2
+                mk1 = t.zeros(np1, dtype=t.uint8, device="cuda")
+                id1 = t.zeros(np1, dtype=t.int32, device="cuda")
+                cn1 = t.zeros(1, dtype=t.int32, device="cuda")
+                lg1 = t.zeros(np1, dtype=t.float32, device="cuda")
+                wm1 = t.from_numpy(I.masker_weights(7850 + 100 * stage, c_in)).cuda()
+                wsm1 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fin, None, stride * S1))
+                wsp = D.workspace(L.dyn_projection_workspace(fin, dbp.desc, stride))
+                L.laud_mask_gen(cur, fin, stride * S1, wm1, 0.0, None, mk1, id1, cn1, None, lg1, wsm1)
+                t.cuda.synchronize()
+                b1 = I.bias_for_ratio(lg1.cpu().numpy(), 0.5)[0]
+                op = (lambda cur=cur, fin=fin, dbp=dbp, wsc=wsc, ssc=ssc, tsc=tsc, stride=stride, xs=xs, wsp=wsp, S1=S1,
+                      wm1=wm1, b1=b1, mk1=mk1, id1=id1, cn1=cn1, wsm1=wsm1: (
+                      L.laud_mask_gen(cur, fin, stride * S1, wm1, b1, None, mk1, id1, cn1, None, None, wsm1),
+                      L.laud_dyn_projection_bottleneck(cur, fin, dbp.desc, wsc, ssc, tsc, stride, S1, id1, cn1, xs, wsp)))
+                op()
+                act.append(float(cn1.item()) / np1)
+                held += [mk1, id1, cn1, lg1, wm1, wsm1]
+            else:
+                wsp = D.workspace(L.static_bottleneck_workspace(fin, dbp.desc, stride))
+                op = (lambda cur=cur, fin=fin, dbp=dbp, wsc=wsc, ssc=ssc, tsc=tsc, stride=stride, xs=xs, wsp=wsp:
+                      L.laud_static_bottleneck(cur, fin, dbp.desc, wsc, ssc, tsc, stride, xs, wsp))
+                op()
+            ops.append(op)
+            held += [dbp, wsc, ssc, tsc, xs, wsp]
+            fxs = L.fmap_of(xs)
+            npatch = N * (hw // Ss) ** 2
+            mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
+            ids = t.zeros(npatch, dtype=t.int32, device="cuda")
+            cn = t.zeros(1, dtype=t.int32, device="cuda")
+            lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
+            wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
+            wsd = None
+            for bidx in range(1, nblk):
+                dbs = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage + bidx, co, m, co, I.BF16, relu_out=True,
+                                                             s3_gain=0.25))
+                if wsd is None:
+                    wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
+                kp = None
+                if keep_p is not None:
+                    kp = t.from_numpy(I.bernoulli_mask(8000 + 100 * stage + bidx, (N,), keep_p)).cuda()
+                    held.append(kp)
+                if spatial:
+                    wm = t.from_numpy(I.masker_weights(7900 + 100 * stage + bidx, co)).cuda()
+                    L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
+                    t.cuda.synchronize()
+                    bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, kp=kp, mk=mk, ids=ids, cn=cn, wsd=wsd:
+                          L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, kp, mk, ids, cn, None, None, xs, wsd))
+                    held.append(wm)
+                else:  # layer skipping only: the gate is the mask, one "patch" per sample
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, kp=kp, ids=ids, cn=cn, wsd=wsd: (
+                          L.laud_layer_skip_compact(kp, N, ids, cn, wc),
+                          L.laud_dyn_bottleneck(xs, fxs, dbs.desc, Ss, ids, cn, xs, wsd)))
+                op()
+                act.append(float(cn.item()) / npatch)
+                ops.append(op)
+                held.append(dbs)
+                ndyn += 1
+            held += [mk, ids, cn, lgs, wsm2, wsd]
+            cur, c_in = xs, co
+        t.cuda.synchronize()
+
+        def body(i):
+            for op in ops:
+                op()
+        us = _p50_us(t, body, iters=5, warm=1)
+        L.laud_stage_timing_enable(True)
+        body(0)
+        t.cuda.synchronize()
+        st_body = L.laud_stage_timing_read()
+        L.laud_stage_timing_enable(False)
+        # the same launches captured once into a HIP graph and replayed (every entry point only enqueues kernels)
+        res = {"p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0)}
+        if graph:
+            gr = t.cuda.CUDAGraph()
+            with t.cuda.graph(gr):
+                body(0)
+            res["hip_graph_replay_p50_ms"] = round(_p50_us(t, lambda i: gr.replay(), iters=5, warm=1) / 1e3, 3)
+            del gr
+        res.update({"dynamic_blocks": ndyn + (4 if dyn_first else 0), "static_blocks": 0 if dyn_first else 4,
+                    "mean_activation_ratio": round(float(np.mean(act)), 3),
+                    "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()}})
+        return res
+
+    ex["config3_resnet101_body_b128"] = dict(run_body(128, None, (1, 2, 3, 4)), note=(
+        "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at activation "
+        "ratio 0.5 each; the stem's kernels carry no stage label"))
+    t.cuda.empty_cache()
+    # config 3 widened (Sec. 3.1 / 3.2: maskers in every block; Sec. 4: the granularity settings S^net of the paper's table)
+    ex["config3_body_b128_dynamic_first_blocks"] = dict(run_body(128, None, (1, 2, 3, 4), dyn_first=True, graph=False), note=(
+        "as config 3, the first block of every stage dynamic too (projection shortcut, mask on the output grid, ratio 0.5)"))
+    t.cuda.empty_cache()
+    for sset in ((4, 4, 7, 1), (8, 4, 7, 1), (1, 1, 1, 1)):
+        ex["config3_body_b128_granularity_" + "".join(str(v) for v in sset)] = run_body(128, None, (1, 2, 3, 4), S_set=sset, graph=False)
+        t.cuda.empty_cache()
+    ex["config5_resnet101_body_b256_layer_skip"] = dict(run_body(256, 0.6, (3,)), note=(
+        "per-sample per-block keep gates Bernoulli(0.6): stages 1, 2, 4 skip whole samples (S = H), stage 3 "
+        "combines the gate with spatial maskers S = 2 at ratio 0.5 of the patches"))
+    t.cuda.empty_cache()
+    return ex
+
+
 def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm, only=None):
     """p50 of single entry points on rotating buffers; bytes and FLOPs are the algorithmic ones."""
     ex = {}
@@ -388,6 +534,14 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
                 ex[f"channel_masker_stage{stage}_b64"] = {"p50_us": round(usm, 1),
                                                           "GB_per_s": round(xbytes_s / usm / 1e3, 0),
                                                           "hbm_frac": round(xbytes_s / usm / 1e3 / PEAK_HBM_GBS, 3)}
+                # config 4 with the masks coming from the channel masker instead of a seeded Bernoulli draw: masker and
+                # channel-skipping block back to back (the mask never leaves the device)
+                def cm_chain(i):
+                    L.laud_channel_masker(xb[i % 4], fxs, wad, bad, hid, wbd, bbd, 4, cmo, None, wsk)
+                    L.laud_channel_skip_conv(xb[i % 4], fxs, dbs.desc, cmo, 4, xb[i % 4], wss)
+                usc = _p50_us(t, cm_chain, iters=12, warm=2)
+                ex[f"channel_masker_plus_skip_stage{stage}_b64"] = {"p50_us": round(usc, 1), "images_per_s": round(N / usc * 1e6, 0),
+                                                                    "kept_fraction": round(float(cmo.float().mean().item()), 3)}
             del xb, xs
     if only == "stages":   # (profiling runs: the masker, the gather and the per-stage blocks only)
         return ex
@@ -507,114 +661,7 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
         ex[f"dyn_first_block_stage{stage}_b128"] = res
         del xs, outs, wsp, wsq
     ex.update(measure_regnety(t, L, B, D, I))
-    # configurations 3 and 5 of the benchmark list: the whole dynamic ResNet-101 body, bf16 -- static stem, per stage one static
-    # projection block (stride 2 in stages 2-4) and 2 / 3 / 22 / 2 dynamic identity blocks; random-init weights
-    # (s3 gain 0.25 so that the residual stream stays O(1)).  Every run starts from the image.
-    #   config 3: batch 128, spatial maskers at granularity 4-4-2-1 in all stages, every masker's bias
-    #             calibrated to ratio 0.5 on the block's actual input
-    #   config 5: batch 256, a seeded Bernoulli(0.6) keep gate per sample and block (layer skipping: the kept
-    #             samples are compacted, S = H), AND-ed with spatial maskers (S = 2, ratio 0.5) in stage 3
-    def run_body(N, keep_p, spatial_stages):
-        g = np.random.default_rng(7700)
-        img8 = I.round_to(g.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16)
-        img = D.to_device(img8, I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
-        w7 = D.to_device(I.round_to(g.standard_normal((64, 7, 7, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / 147)), I.BF16), I.BF16)
-        s7 = t.from_numpy((1 + 0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
-        t7 = t.from_numpy((0.1 * g.standard_normal(64)).astype(np.float32)).cuda()
-        x0 = t.empty((N, 56, 56, 64), dtype=t.bfloat16, device="cuda")
-        ws_stem = D.workspace(L.stem_workspace(N, 224, 224, 64, I.BF16))
-        ops = [lambda: L.laud_stem(img, N, 224, 224, I.BF16, w7, s7, t7, 64, x0, ws_stem)]
-        ops[0]()
-        cur, c_in, hw = x0, 64, 56
-        held = [img, w7, s7, t7, x0, ws_stem]
-        ndyn, act = 0, []
-        wc = D.workspace(4096)
-        for stage, nblk in ((1, 3), (2, 4), (3, 23), (4, 3)):
-            sg = I.STAGES[stage]
-            m, stride = sg["m"], (1 if stage == 1 else 2)
-            co = 4 * m
-            hw = (hw - 1) // stride + 1
-            spatial = stage in spatial_stages
-            Ss = sg["S"] if spatial else hw
-            fin = L.fmap_of(cur)
-            dbp = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage, c_in, m, co, I.BF16, relu_out=True, s3_gain=0.5))
-            gs = np.random.default_rng(7801 + 100 * stage)
-            wsc = D.to_device(I.round_to(gs.standard_normal((co, c_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / c_in)), I.BF16), I.BF16)
-            ssc = t.from_numpy((0.5 * (1 + 0.1 * gs.standard_normal(co))).astype(np.float32)).cuda()
-            tsc = t.from_numpy((0.1 * gs.standard_normal(co)).astype(np.float32)).cuda()
-            xs = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
-            wsp = D.workspace(L.static_bottleneck_workspace(fin, dbp.desc, stride))
-            op = (lambda cur=cur, fin=fin, dbp=dbp, wsc=wsc, ssc=ssc, tsc=tsc, stride=stride, xs=xs, wsp=wsp:
-                  L.laud_static_bottleneck(cur, fin, dbp.desc, wsc, ssc, tsc, stride, xs, wsp))
-            op()
-            ops.append(op)
-            held += [dbp, wsc, ssc, tsc, xs, wsp]
-            fxs = L.fmap_of(xs)
-            npatch = N * (hw // Ss) ** 2
-            mk = t.zeros(npatch, dtype=t.uint8, device="cuda")
-            ids = t.zeros(npatch, dtype=t.int32, device="cuda")
-            cn = t.zeros(1, dtype=t.int32, device="cuda")
-            lgs = t.zeros(npatch, dtype=t.float32, device="cuda")
-            wsm2 = D.workspace(L.workspace_size(B.OP_MASK_GEN, fxs, None, Ss))
-            wsd = None
-            for bidx in range(1, nblk):
-                dbs = D.DeviceBottleneck(I.bottleneck_params(7800 + 100 * stage + bidx, co, m, co, I.BF16, relu_out=True,
-                                                             s3_gain=0.25))
-                if wsd is None:
-                    wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
-                kp = None
-                if keep_p is not None:
-                    kp = t.from_numpy(I.bernoulli_mask(8000 + 100 * stage + bidx, (N,), keep_p)).cuda()
-                    held.append(kp)
-                if spatial:
-                    wm = t.from_numpy(I.masker_weights(7900 + 100 * stage + bidx, co)).cuda()
-                    L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
-                    t.cuda.synchronize()
-                    bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
-                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, kp=kp, mk=mk, ids=ids, cn=cn, wsd=wsd:
-                          L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, kp, mk, ids, cn, None, None, xs, wsd))
-                    held.append(wm)
-                else:  # layer skipping only: the gate is the mask, one "patch" per sample
-                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, kp=kp, ids=ids, cn=cn, wsd=wsd: (
-                          L.laud_layer_skip_compact(kp, N, ids, cn, wc),
-                          L.laud_dyn_bottleneck(xs, fxs, dbs.desc, Ss, ids, cn, xs, wsd)))
-                op()
-                act.append(float(cn.item()) / npatch)
-                ops.append(op)
-                held.append(dbs)
-                ndyn += 1
-            held += [mk, ids, cn, lgs, wsm2, wsd]
-            cur, c_in = xs, co
-        t.cuda.synchronize()
-
-        def body(i):
-            for op in ops:
-                op()
-        us = _p50_us(t, body, iters=5, warm=1)
-        L.laud_stage_timing_enable(True)
-        body(0)
-        t.cuda.synchronize()
-        st_body = L.laud_stage_timing_read()
-        L.laud_stage_timing_enable(False)
-        # the same launches captured once into a HIP graph and replayed (every entry point only enqueues kernels)
-        gr = t.cuda.CUDAGraph()
-        with t.cuda.graph(gr):
-            body(0)
-        us_g = _p50_us(t, lambda i: gr.replay(), iters=5, warm=1)
-        del gr
-        return {"p50_ms": round(us / 1e3, 3), "images_per_s": round(N / us * 1e6, 0),
-                "hip_graph_replay_p50_ms": round(us_g / 1e3, 3), "dynamic_blocks": ndyn,
-                "static_blocks": 4, "mean_activation_ratio": round(float(np.mean(act)), 3),
-                "kernel_ms_by_stage_label": {k: round(v[0], 3) for k, v in st_body.items()}}
-
-    ex["config3_resnet101_body_b128"] = dict(run_body(128, None, (1, 2, 3, 4)), note=(
-        "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at activation "
-        "ratio 0.5 each; the stem's kernels carry no stage label"))
-    t.cuda.empty_cache()
-    ex["config5_resnet101_body_b256_layer_skip"] = dict(run_body(256, 0.6, (3,)), note=(
-        "per-sample per-block keep gates Bernoulli(0.6): stages 1, 2, 4 skip whole samples (S = H), stage 3 "
-        "combines the gate with spatial maskers S = 2 at ratio 0.5 of the patches"))
-    t.cuda.empty_cache()
+    ex.update(measure_bodies(t, L, B, D, I))
     # yardstick: the vendor GEMM library (through torch.matmul) on plain dense GEMMs of the three conv shapes
     # of config 2 at r = 0.5 -- no gather, no masker projection, no residual or scatter; context for the
     # roofline fraction, not part of the path.  Back-to-back launches over rotating cold A operands.
@@ -849,6 +896,8 @@ def main():
         t.cuda.empty_cache()
         if a.extras_only == "regnety":
             extras = measure_regnety(t, L, B, D, I)
+        elif a.extras_only == "bodies":
+            extras = measure_bodies(t, L, B, D, I)
         else:
             extras = measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cnt, wsm, only=a.extras_only)
 

@@ -17,7 +17,11 @@ benchmark times.  The batch holds the eight images three times over:
 
 Layer skipping (the second case): batch 256, a seeded Bernoulli(0.6) keep gate per sample and block; in stages 1,
 2 and 4 the gate is the whole decision (compaction of the kept samples, S = H), in stage 3 it is AND-ed with the
-spatial masker (S = 2, ratio 0.5)."""
+spatial masker (S = 2, ratio 0.5).
+
+Further cases widen config 3: the first block of every stage dynamic as well (projection shortcut, stride 2 in
+stages 2-4, the mask on the output grid, the masker pooling x to the output patch grid; Sec. 3.1 / 3.2), and the
+other granularity settings of the paper's table of S^net choices (4-4-7-1, 8-4-7-1, 1-1-1-1; Sec. 4)."""
 import numpy as np
 import pytest
 
@@ -28,6 +32,10 @@ pytestmark = pytest.mark.gpu
 DT = I.BF16
 TOL = 2e-2
 NS = 8  # sampled images
+# the thresholds must sit in a gap of the oracle's logits at least twice as wide as the float32 logit error bound
+# (2e-5 of the logits' scale); at S = 1 on the 56 x 56 maps eight images give 25088 logits per block, and the widest
+# gap near the median is about 1e-4 of their rms
+GAP = 4e-5
 
 
 def close(got, ref, what):
@@ -49,13 +57,21 @@ def shortcut_params(seed, c_in, c_out):
     return w, (0.5 * (1 + 0.1 * g.standard_normal(c_out))).astype(np.float32), (0.1 * g.standard_normal(c_out)).astype(np.float32)
 
 
-@pytest.mark.parametrize("case", [("config3", 128, None, (1, 2, 3, 4)), ("config5", 256, 0.6, (3,))])
+CASES = [("config3", 128, None, (1, 2, 3, 4), (4, 4, 2, 1), False),
+         ("config5", 256, 0.6, (3,), (4, 4, 2, 1), False),
+         ("config3_dynamic_first_blocks", 128, None, (1, 2, 3, 4), (4, 4, 2, 1), True),
+         ("config3_S4471", 128, None, (1, 2, 3, 4), (4, 4, 7, 1), False),
+         ("config3_S8471", 128, None, (1, 2, 3, 4), (8, 4, 7, 1), False),
+         ("config3_S1111", 128, None, (1, 2, 3, 4), (1, 1, 1, 1), False)]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_resnet101_body_full_size_sampled(case):
     import torch as t
     import paper_2308_15949_amd as L
     from paper_2308_15949_amd import device as D
     B = L.binding
-    name, N, keep_p, spatial_stages = case
+    name, N, keep_p, spatial_stages, S_set, dyn_first = case
     cfg = 3 if keep_p is None else 5
     g = np.random.default_rng(I.seed_for(cfg, 0))
     img = I.round_to(g.standard_normal((N, 224, 224, 3), dtype=np.float32), DT)
@@ -79,7 +95,8 @@ def test_resnet101_body_full_size_sampled(case):
         sg = I.STAGES[stage]
         m, stride, co = sg["m"], (1 if stage == 1 else 2), 4 * sg["m"]
         spatial = stage in spatial_stages
-        # ---- static first block of the stage (projection shortcut, stride on the 3x3) -------------------------
+        # ---- first block of the stage (projection shortcut, stride on the 3x3): static, or dynamic with the mask on
+        # the output grid ----------------------------------------------------------------------------------------
         blk_no += 1
         hb = I.bottleneck_params(I.seed_for(cfg, 0, blk_no), c_in, m, co, DT, relu_out=True, s3_gain=0.5)
         wsc, ssc, tsc = shortcut_params(I.seed_for(cfg, 8, blk_no), c_in, co)
@@ -88,17 +105,44 @@ def test_resnet101_body_full_size_sampled(case):
         db = D.DeviceBottleneck(hb)
         hw = (hw - 1) // stride + 1
         out = t.empty((N, hw, hw, co), dtype=t.bfloat16, device="cuda")
-        print(f"{name} block {blk_no}: stage {stage} static projection block", flush=True)
-        L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, DT), dev(ssc), dev(tsc), stride, out,
-                                 D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride)))
-        t.cuda.synchronize()
-        y_ref = O.projection_bottleneck(x_ref, oparams(hb), wsc, ssc, tsc, stride)
-        worst[f"b{blk_no}"] = close(D.to_host(out[:NS]), y_ref, f"block {blk_no} (static, stage {stage})")
+        if dyn_first:
+            S1 = S_set[stage - 1]
+            print(f"{name} block {blk_no}: stage {stage} dynamic projection block, S = {S1} on the output grid", flush=True)
+            w = I.masker_weights(I.seed_for(cfg, 5, blk_no), c_in)
+            ref0 = O.strided_mask_logits(x_ref, stride, S1, w, 0.0)
+            bias, half_gap = I.bias_for_ratio(ref0, 0.5)
+            assert half_gap > GAP * float(np.sqrt(np.mean(ref0 * ref0))), "threshold not in a gap"
+            ref_mask = O.threshold(ref0 + bias)
+            npatch = N * (hw // S1) ** 2
+            mask1 = t.zeros(npatch, dtype=t.uint8, device="cuda")
+            idx1 = t.zeros(npatch, dtype=t.int32, device="cuda")
+            cnt1 = t.zeros(1, dtype=t.int32, device="cuda")
+            L.laud_mask_gen(xd, fx, stride * S1, dev(w), bias, None, mask1, idx1, cnt1, None, None,
+                            D.workspace(L.workspace_size(B.OP_MASK_GEN, fx, None, stride * S1)))
+            L.laud_dyn_projection_bottleneck(xd, fx, db.desc, D.to_device(wsc, DT), dev(ssc), dev(tsc), stride, S1,
+                                             idx1, cnt1, out, D.workspace(L.dyn_projection_workspace(fx, db.desc, stride)))
+            t.cuda.synchronize()
+            gm = mask1.cpu().numpy().reshape(N, hw // S1, hw // S1)
+            assert np.array_equal(gm[:NS], ref_mask), f"block {blk_no}: mask differs on the teacher-forced images"
+            y_ref = O.dyn_projection_bottleneck(x_ref, oparams(hb), wsc, ssc, tsc, stride, S1, ref_mask)
+            agree = float((gm[NS:2 * NS] == ref_mask).mean())
+            got = D.to_host(out[:2 * NS])
+            rms = float(np.sqrt(np.mean(y_ref * y_ref)))
+            report.append((blk_no, stage, float(gm.mean()), float(ref_mask.mean()), agree,
+                           float(np.sqrt(np.mean((got[NS:] - y_ref) ** 2)) / rms)))
+            del mask1, idx1, cnt1
+        else:
+            print(f"{name} block {blk_no}: stage {stage} static projection block", flush=True)
+            L.laud_static_bottleneck(xd, fx, db.desc, D.to_device(wsc, DT), dev(ssc), dev(tsc), stride, out,
+                                     D.workspace(L.static_bottleneck_workspace(fx, db.desc, stride)))
+            t.cuda.synchronize()
+            y_ref = O.projection_bottleneck(x_ref, oparams(hb), wsc, ssc, tsc, stride)
+        worst[f"b{blk_no}"] = close(D.to_host(out[:NS]), y_ref, f"block {blk_no} (first block of stage {stage})")
         x_ref = I.round_to(y_ref.astype(np.float32), DT)
         xd, c_in = out, co
         del db
         # ---- dynamic identity blocks -----------------------------------------------------------------------
-        S = sg["S"] if spatial else hw
+        S = S_set[stage - 1] if spatial else hw
         fx = L.fmap_of(xd)
         hp = hw // S
         npatch = N * hp * hp
@@ -124,7 +168,7 @@ def test_resnet101_body_full_size_sampled(case):
                 w = I.masker_weights(I.seed_for(cfg, 5, blk_no), co)
                 ref0 = O.mask_logits(x_ref, S, w, 0.0)
                 bias, half_gap = I.bias_for_ratio(ref0, 0.5)
-                assert half_gap > 1e-4 * float(np.sqrt(np.mean(ref0 * ref0))), "threshold not in a gap"
+                assert half_gap > GAP * float(np.sqrt(np.mean(ref0 * ref0))), "threshold not in a gap"
                 ref_mask = O.threshold(ref0 + bias)
                 if keep is not None:
                     ref_mask = ref_mask * keep[:NS, None, None]

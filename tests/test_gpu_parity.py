@@ -576,6 +576,39 @@ def test_config4_channel_skip_full_size_sampled(G, stage):
     assert_close(got, ref, TOL[dt], f"config 4 stage {stage}")
 
 
+@pytest.mark.parametrize("stage", [1, 2, 3, 4])
+def test_config4_masks_from_the_channel_masker_full_size_sampled(G, stage):
+    """Config 4 with the channel mask produced on the device by the channel masker (global average pooling + two-layer
+    MLP, Sec. 3.2) instead of a seeded draw: masker -> channel-skipping block at batch 64, the mask never leaving
+    the device.  The oracle runs its own masker on the sampled images; its decisions are clear of ties, so the GPU
+    must reproduce them exactly, and then the block's output within the tolerance."""
+    t, L, D = G.torch, G.L, G.D
+    sg = I.STAGES[stage]
+    N, H, C, m, dt, Dg = 64, sg["hw"], sg["c_in"], sg["m"], I.BF16, 4
+    xs = I.feature_map(I.seed_for(4, 0, 10 + stage), 4, H, H, C, dt)        # 4 distinct images, tiled to 64
+    x = np.tile(xs, (N // 4, 1, 1, 1))
+    hb = I.bottleneck_params(I.seed_for(4, 1, 10 + stage), C, m, C, dt, relu_out=True)
+    wa, ba, wb, bb, hidden = I.channel_masker_weights(I.seed_for(4, 6, 10 + stage), C, Dg)
+    dev = lambda a: t.from_numpy(a).cuda()
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    cmask = t.full((N, Dg), 9, dtype=t.uint8, device="cuda")
+    L.laud_channel_masker(xd, fx, dev(wa), dev(ba), hidden, dev(wb), dev(bb), Dg, cmask, None,
+                          D.workspace(L.channel_masker_workspace(fx)))
+    L.laud_channel_skip_conv(xd, fx, db.desc, cmask, Dg, xd, D.workspace(L.workspace_size(L.binding.OP_CHANNEL_SKIP, fx, db.desc, Dg)))
+    t.cuda.synchronize()
+    sample = [0, 5, 30, 63]   # the four distinct images
+    lr = O.channel_masker_logits(x[sample], wa, ba, wb, bb)
+    assert (np.abs(lr[..., 0] - lr[..., 1]) > 1e-4 * float(np.sqrt(np.mean(lr * lr)))).all(), "a decision near a tie"
+    ref_mask = O.channel_mask_from_logits(lr)
+    gm = cmask.cpu().numpy()
+    assert np.array_equal(gm[sample], ref_mask)
+    assert np.array_equal(gm, np.tile(gm[:4], (N // 4, 1)))   # copies of an image take the same decisions
+    ref = O.channel_skip_bottleneck(x[sample], oracle_params(hb), ref_mask)
+    assert_close(D.to_host(xd[sample]), ref, TOL[dt], f"config 4 from the channel masker, stage {stage}")
+
+
 def test_config5_layer_gate_and_spatial_full_size_sampled(G):
     """Stage-3 block at batch 256, bf16: per-sample keep gate (0.6) AND spatial mask S = 2 at ratio 0.5."""
     t, L, D = G.torch, G.L, G.D
