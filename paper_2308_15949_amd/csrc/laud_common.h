@@ -180,7 +180,9 @@ struct HeadArgs {
   // sparse form (the gather fused into the first 1x1): rows are pixel ids taken from per-group lists; list == null: dense
   const int32_t* list;   // [ngroups][group_rows] ascending pixel ids of the dilated active set
   const int32_t* counts; // [ngroups] device: valid entries per group
-  int group_rows, tiles_per_group;
+  int group_rows;        // capacity of one group's list
+  int pb;                // tile height in blocks of 32 pixels (2 or 4); 0 = chosen by launch_head (dense rows) or on the device (lists)
+  int wg_target;         // workgroups that fill the device once (its compute units; set by launch_head)
 };
 bool head_supported(int dtype, int c_in, int c_mid);
 int head_init_device();

@@ -1069,7 +1069,6 @@ static int launch_sparse_head(int dtype, const laud_bottleneck* p, const void* x
   h.x = x; h.wpacked = (const char*)(p->packed ? p->packed : wpack) + packed_layout(dtype, p).head;
   h.s1 = p->s1; h.t1 = p->t1; h.h1 = h1; h.m_rows = ngroups; h.K = p->c_in;
   h.list = pix; h.counts = need_counts; h.group_rows = group_rows;
-  h.tiles_per_group = (group_rows + 127) / 128;
   return launch_head(h, st);
 }
 

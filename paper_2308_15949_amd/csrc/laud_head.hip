@@ -2,8 +2,8 @@
 // same reads of x (Sec. 3.4 "Operator fusion for spatial maskers"; App. B item 1), for gfx950: bf16, c_mid = 256,
 // c_in a multiple of 256.  Same construction as the fused conv2 -> conv3 kernel (laud_tail.hip):
 //
-//   * one workgroup = 128 pixels x all 256 mid channels, 8 waves; wave w owns channels 32w .. 32w+31 and keeps its
-//     weight fragments in registers, streamed from the packed copy of w1 (four K slices held / in flight);
+//   * one workgroup = 64 or 128 pixels x all 256 mid channels, 8 waves; wave w owns channels 32w .. 32w+31 and keeps
+//     its weight fragments in registers, streamed from the packed copy of w1 (four K slices held / in flight);
 //   * x reaches LDS with LDS-direct 16-byte loads into a four-stage ring of 128-byte K slices, swizzled on the
 //     global side; one barrier per slice, in its middle; fragments are read one K step ahead of their MFMAs;
 //   * the MFMAs compute the transposed tile, so after one lane swap per register pair a lane holds 16 consecutive
@@ -20,18 +20,20 @@ namespace laud {
 
 namespace head {
 constexpr int kMid = 256;
-constexpr int kPB = 4;                        // 32-pixel blocks per workgroup (and per wave)
-constexpr int kBM = 32 * kPB;
+constexpr int kMaxPB = 4;                     // a workgroup takes PB = 2 or 4 blocks of 32 pixels
 constexpr int kThreads = 512, kWaves = 8;
-constexpr int kAStage = kBM * 128;            // one 128-byte K slice of every pixel row (16 KB)
 constexpr int kARing = 4;
 constexpr int kWRing = 4;                     // weight slices in registers
-constexpr int kAI = kPB / 2;                  // LDS-direct instructions per wave and activation slice (8 rows each)
-constexpr int kTabOff = kARing * kAStage;     // s1, t1 [256] floats, masker weights [K] floats, partial sums [8][kBM]
 constexpr unsigned kOob = 0x80000000u;
 constexpr int kMaxK = 4096;
-// ... then the output rows of the tile (int)
-__host__ __device__ constexpr int lds_bytes(int K) { return kTabOff + 2 * kMid * 4 + K * 4 + kWaves * kBM * 4 + kBM * 4; }
+__host__ __device__ constexpr int a_stage(int pb) { return 32 * pb * 128; }  // one 128-byte K slice of every pixel row
+// behind the activation ring: s1, t1 [256] floats, masker weights [K] floats, partial sums [8][32*pb], then the
+// output rows of the tile (int)
+__host__ __device__ constexpr int tab_off(int pb) { return kARing * a_stage(pb); }
+__host__ __device__ constexpr int lds_bytes(int K, int pb) { return tab_off(pb) + 2 * kMid * 4 + K * 4 + kWaves * 32 * pb * 4 + 32 * pb * 4; }
+// time of one tile of 64 / 128 pixels in the same unit (measured 14-17 and 21-26 us at K = 1024): a workgroup streams
+// all of w1 whatever its height
+constexpr int kCost2 = 2, kCost4 = 3;
 }  // namespace head
 
 // w1 [256][K] in MFMA fragment order: slice b (K chunk of 64), wave w, K step kg, lane l hold the 16 bytes
@@ -46,10 +48,16 @@ __global__ __launch_bounds__(256) void k_pack_head_weights(const uint4* __restri
   if (idx < (K / 64) * tail::kSliceChunks) head_pack_chunk(idx, w1, K, out);
 }
 
-template <bool PROJ>
-__global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
+// One tile of 32*PB rows: rows row0 .. of the dense map, or (listed) of a pixel list with M entries whose entries for
+// this lane's rows (row0 + 64i + 8*wave + lane/8) the caller has already requested.
+template <bool PROJ, int PB>
+__device__ __forceinline__ void head_tile(const HeadArgs& a, const int row0, const int M, const bool listed,
+                                          const int (&pixsp)[PB / 2]) {
   using namespace head;
   extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int kBM = 32 * PB, kAStage = a_stage(PB), kTabOff = tab_off(PB);
+  constexpr int kAI = PB / 2;  // LDS-direct instructions per wave and activation slice (8 rows each)
+  static_assert(PB % 2 == 0, "an activation instruction of all eight waves covers 64 rows");
   float* const s_s1 = reinterpret_cast<float*>(smem + kTabOff);
   float* const s_t1 = s_s1 + kMid;
   float* const s_wm = s_t1 + kMid;
@@ -60,21 +68,6 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l31 = lane & 31, lhi = lane >> 5, l8 = lane >> 3, l7 = lane & 7;
   const int K = a.K, NSL = K / 64;
-  // dense: workgroup b takes rows 128b ..; sparse: the pixel lists are kept per group of samples, workgroup b takes
-  // tile b % tiles_per_group of group b / tiles_per_group (list entries requested together with the group's count)
-  int row0 = blockIdx.x * kBM, M = a.m_rows;
-  const int32_t* listp = nullptr;
-  int pixsp[kAI];
-  if (a.list != nullptr) {
-    const int g = blockIdx.x / a.tiles_per_group;
-    row0 = (blockIdx.x - g * a.tiles_per_group) * kBM;
-    listp = a.list + (size_t)g * a.group_rows;
-#pragma unroll
-    for (int i = 0; i < kAI; ++i) pixsp[i] = listp[min(row0 + 64 * i + 8 * wave + l8, a.group_rows - 1)];
-    M = a.counts[g];
-    if (row0 >= M) return;
-  }
-
   // ---- weight stream: four slices in registers -------------------------------------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
@@ -99,7 +92,7 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
     const int r = 64 * i + 8 * wave + l8;
     const int rho = row0 + r;
     const unsigned c = (unsigned)l7 ^ ((unsigned)(l8 & 7) ^ (wave & 1u));
-    const int pixel = rho < M ? (listp ? pixsp[i] : rho) : -1;
+    const int pixel = rho < M ? (listed ? pixsp[i] : rho) : -1;
     voffA[i] = pixel >= 0 ? (unsigned)pixel * (unsigned)(K * 2) + c * 16u : kOob;
     if (l7 == 0) s_orow[r] = pixel;
   }
@@ -120,19 +113,19 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
 #pragma unroll
     for (int kg = 0; kg < 4; ++kg) swz[kg] = (unsigned)l31 * 128u + (((2u * kg + lhi) ^ f) << 4);
   }
-  f32x16 acc[kPB];
-  float psum[kPB];
+  f32x16 acc[PB];
+  float psum[PB];
 #pragma unroll
-  for (int t = 0; t < kPB; ++t) {
+  for (int t = 0; t < PB; ++t) {
     psum[t] = 0.f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   }
-  uint4 fa[2][kPB];
+  uint4 fa[2][PB];
   auto read_frags = [&](int buf, int s, int kg) __attribute__((always_inline)) {
     const unsigned char* pa = smem + (unsigned)(s & (kARing - 1)) * kAStage + swz[kg];
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) fa[buf][t] = *reinterpret_cast<const uint4*>(pa + t * 4096);
+    for (int t = 0; t < PB; ++t) fa[buf][t] = *reinterpret_cast<const uint4*>(pa + t * 4096);
   };
 
   vm_wait<0>();
@@ -153,14 +146,14 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
       else if (s + 1 < NSL) read_frags((g + 1) & 1, s + 1, 0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int t = 0; t < kPB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
+      for (int t = 0; t < PB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
       if constexpr (PROJ) {
         // this wave's share of the masker projection: K steps q with q % 8 == wave (s0 is a multiple of 4)
         if ((g & 7) == wave) {
           const float4 w0 = *reinterpret_cast<const float4*>(s_wm + s * 64 + kg * 16 + lhi * 8);
           const float4 w1 = *reinterpret_cast<const float4*>(s_wm + s * 64 + kg * 16 + lhi * 8 + 4);
 #pragma unroll
-          for (int t = 0; t < kPB; ++t) {
+          for (int t = 0; t < PB; ++t) {
             const uint4 v = fa[g & 1][t];
             float p = psum[t];
             p += __uint_as_float(v.x << 16) * w0.x; p += __uint_as_float(v.x & 0xffff0000u) * w0.y;
@@ -189,7 +182,7 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
     const int cb = wave * 32;
     __bf16* const outp = reinterpret_cast<__bf16*>(a.h1);
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) {
+    for (int t = 0; t < PB; ++t) {
       float v[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -215,7 +208,7 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   // ---- projection: the two K halves of a pixel sit in lanes l and l+32; then the eight waves' shares -------------
   if constexpr (PROJ) {
 #pragma unroll
-    for (int t = 0; t < kPB; ++t) {
+    for (int t = 0; t < PB; ++t) {
       const float other = __shfl_xor(psum[t], 32, kWave);
       if (lhi == 0) s_part[wave * kBM + 32 * t + l31] = psum[t] + other;
     }
@@ -230,18 +223,77 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   }
 }
 
+// The tile height: dense rows are known on the host (a.pb set); for pixel lists the counts live on the device, and
+// every workgroup takes the same decision from them -- the height with the smaller (rounds of workgroups over the
+// compute units) x (time of one tile), as in the fused conv2 -> conv3 kernel.
+template <bool PROJ>
+__global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
+  using namespace head;
+  int pb = a.pb;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l8 = lane >> 3;
+  if (a.list == nullptr) {
+    const int row0 = blockIdx.x * 32 * pb;
+    if (row0 >= a.m_rows) return;
+    const int none2[1] = {0}, none4[2] = {0, 0};
+    if (pb == 2) head_tile<PROJ, 2>(a, row0, a.m_rows, false, none2);
+    else head_tile<PROJ, 4>(a, row0, a.m_rows, false, none4);
+    return;
+  }
+  if constexpr (!PROJ) {
+    // Pixel lists per group of samples: a.m_rows groups of up to a.group_rows entries.  Workgroup id -> (group =
+    // id % groups, tile = id / groups): consecutive ids (which go round-robin over the XCDs) cycle through the groups
+    // at equal tile index, so the tiles that exist come first and evenly spread, the idle workgroups last.  Group
+    // and tile do not depend on the counts, so the list entries of both candidate heights are requested together
+    // with the counts: one memory round trip before the rows themselves.
+    const int g = blockIdx.x % a.m_rows, tile = blockIdx.x / a.m_rows;
+    const int32_t* const listp = a.list + (size_t)g * a.group_rows;
+    const int cap = a.group_rows - 1;
+    const int r8 = 8 * wv + l8;
+    int p2[1], p4[2];
+    p2[0] = listp[min(tile * 64 + r8, cap)];
+    p4[0] = listp[min(tile * 128 + r8, cap)];
+    p4[1] = listp[min(tile * 128 + 64 + r8, cap)];
+    const int M = a.counts[g];
+    if (pb == 0) {
+      // the height with the smaller (rounds of workgroups over the compute units) x (time of one tile); the counts
+      // are read one per lane and summed across the wave (every wave does the same)
+      int t2 = 0, t4 = 0;
+      for (int g0 = 0; g0 < a.m_rows; g0 += kWave) {
+        const int c = g0 + lane < a.m_rows ? a.counts[g0 + lane] : 0;
+        int v2 = (c + 63) >> 6, v4 = (c + 127) >> 7;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) { v2 += __shfl_xor(v2, d, kWave); v4 += __shfl_xor(v4, d, kWave); }
+        t2 += v2;
+        t4 += v4;
+      }
+      const int c2 = ((t2 + a.wg_target - 1) / a.wg_target) * kCost2, c4 = ((t4 + a.wg_target - 1) / a.wg_target) * kCost4;
+      pb = c2 <= c4 ? 2 : 4;
+    }
+    const int row0 = tile * 32 * pb;
+    if (row0 >= M) return;
+    if (pb == 2) head_tile<false, 2>(a, row0, M, true, p2);
+    else head_tile<false, 4>(a, row0, M, true, p4);
+  }
+}
+
 // ---- host side -----------------------------------------------------------------------------------------------------
 bool head_supported(int dtype, int c_in, int c_mid) {
   return dtype == LAUD_BF16 && c_mid == head::kMid && c_in % 256 == 0 && c_in <= head::kMaxK;
 }
 size_t head_packed_bytes(int c_in) { return align_up((size_t)(c_in / 64) * tail::kSliceChunks * 16, 256); }
 
+static int g_head_cus[32];  // compute units of device d (written before the device's bit in launch_head's `done`)
+
 int head_init_device() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return LAUD_ERR_HIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return LAUD_ERR_HIP;
+  g_head_cus[dev] = cus;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_head<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          head::lds_bytes(head::kMaxK)) != hipSuccess)
+                          head::lds_bytes(head::kMaxK, head::kMaxPB)) != hipSuccess)
     return LAUD_ERR_HIP;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_head<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          head::lds_bytes(head::kMaxK)) != hipSuccess)
+                          head::lds_bytes(head::kMaxK, head::kMaxPB)) != hipSuccess)
     return LAUD_ERR_HIP;
   return LAUD_OK;
 }
@@ -252,22 +304,40 @@ int launch_head_pack(const void* w1, int c_in, void* packed, hipStream_t st) {
   return check_launch();
 }
 
-int launch_head(const HeadArgs& a, hipStream_t st) {
+int launch_head(const HeadArgs& args, hipStream_t st) {
   static std::atomic<unsigned> done{0};
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return LAUD_ERR_HIP;
-  const unsigned bit = dev >= 0 && dev < 32 ? 1u << dev : 0u;
-  if (!(bit && (done.load(std::memory_order_acquire) & bit))) {
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return LAUD_ERR_HIP;
+  const unsigned bit = 1u << dev;
+  if (!(done.load(std::memory_order_acquire) & bit)) {
     if (head_init_device() != LAUD_OK) return LAUD_ERR_HIP;
     done.fetch_or(bit, std::memory_order_release);
   }
-  // dense: m_rows rows; sparse: m_rows = number of groups, each with tiles_per_group tiles
-  const unsigned grid = a.list ? (unsigned)(a.m_rows * a.tiles_per_group) : (unsigned)((a.m_rows + head::kBM - 1) / head::kBM);
+  HeadArgs a = args;
+  a.wg_target = g_head_cus[dev];
+  unsigned grid;
+  int lds_pb = head::kMaxPB;
+  if (a.list == nullptr) {
+    // dense rows: the count is known here; the same rounds x tile-time cost the kernel uses for lists
+    if (a.pb != 2 && a.pb != 4) {
+      const long long t2 = (a.m_rows + 63) / 64, t4 = (a.m_rows + 127) / 128;
+      const long long c2 = ((t2 + a.wg_target - 1) / a.wg_target) * head::kCost2;
+      const long long c4 = ((t4 + a.wg_target - 1) / a.wg_target) * head::kCost4;
+      a.pb = c2 <= c4 ? 2 : 4;
+    }
+    grid = (unsigned)((a.m_rows + 32 * a.pb - 1) / (32 * a.pb));
+    lds_pb = a.pb;
+  } else {
+    // m_rows groups, each with up to group_rows entries: enough workgroups for the smaller tile height
+    if (a.pb != 2 && a.pb != 4) a.pb = 0;
+    const int h = a.pb ? 32 * a.pb : 64;
+    grid = (unsigned)a.m_rows * (unsigned)((a.group_rows + h - 1) / h);
+  }
   StageScope scope(LAUD_STAGE_CONV1, st);
   if (a.wmask)
-    hipLaunchKernelGGL((k_head<true>), dim3(grid), dim3(head::kThreads), head::lds_bytes(a.K), st, a);
+    hipLaunchKernelGGL((k_head<true>), dim3(grid), dim3(head::kThreads), head::lds_bytes(a.K, lds_pb), st, a);
   else
-    hipLaunchKernelGGL((k_head<false>), dim3(grid), dim3(head::kThreads), head::lds_bytes(a.K), st, a);
+    hipLaunchKernelGGL((k_head<false>), dim3(grid), dim3(head::kThreads), head::lds_bytes(a.K, lds_pb), st, a);
   return check_launch();
 }
 
