@@ -157,6 +157,12 @@ struct TailArgs {
   int cout;
   int relu;
   int pb;                // tile height in blocks of 32 pixels (1..3); 0 = chosen on the device from the count
+  // channel skipping (Fig. 2(c)) on whole samples (S = H: a "patch" is a sample, `list` the samples in processing
+  // order): sbits[i] = kept channel groups (bit g) of the i-th sample of the list, cs_group = channels per group (a
+  // multiple of 64).  Input slices of groups no row of a tile keeps are skipped in the 3x3, and h2 is zeroed in the
+  // groups a row drops.  Null: no channel mask.
+  const uint8_t* sbits;
+  int cs_group;
   int wg_target;         // workgroups that fill the device once (its compute units; set by launch_tail)
 };
 
@@ -181,6 +187,10 @@ struct HeadArgs {
   const int32_t* list;   // [ngroups][group_rows] ascending pixel ids of the dilated active set
   const int32_t* counts; // [ngroups] device: valid entries per group
   int group_rows;        // capacity of one group's list
+  // channel skipping: rbits[n] = kept channel groups (bit g) of sample n, hw = pixels per sample, cs_group = channels per
+  // group (a multiple of 32); h1 is written as zero in the groups a row's sample drops.  Null: no channel mask.
+  const uint8_t* rbits;
+  int hw, cs_group;
   int pb;                // tile height in blocks of 32 pixels (2 or 4); 0 = chosen by launch_head (dense rows) or on the device (lists)
   int wg_target;         // workgroups that fill the device once (its compute units; set by launch_head)
 };

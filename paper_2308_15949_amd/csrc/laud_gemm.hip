@@ -931,6 +931,43 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
   return LAUD_OK;
 }
 
+// Channel skipping on the fused kernels: the samples ordered by mask pattern (ascending pattern, ascending sample
+// id inside a pattern; no atomics, so the order is reproducible), so that the rows of a tile share their kept groups
+// and whole input slices can be skipped.  One block; pattern p = sum of (kept group g) << g, D <= 8.
+// perm [N]: sample ids in that order; sbits [N]: their patterns in that order; rbits [N]: patterns by sample id;
+// count: N as a device integer (the kernels read their row count from the device).
+constexpr int kCsSortThreads = 256;
+__global__ __launch_bounds__(kCsSortThreads) void k_cs_sort(const uint8_t* __restrict__ cmask, int N, int D,
+                                                            int32_t* __restrict__ perm, uint8_t* __restrict__ sbits,
+                                                            uint8_t* __restrict__ rbits, int32_t* __restrict__ count) {
+  extern __shared__ unsigned char s_key[];  // [N]
+  __shared__ int s_start[kCsSortThreads];
+  const int tid = threadIdx.x;
+  for (int n = tid; n < N; n += kCsSortThreads) {
+    unsigned key = 0;
+    for (int g = 0; g < D; ++g) key |= (cmask[(size_t)n * D + g] != 0 ? 1u : 0u) << g;
+    s_key[n] = (unsigned char)key;
+    rbits[n] = (uint8_t)key;
+  }
+  __syncthreads();
+  const int npat = 1 << D;
+  int c = 0;  // samples of pattern tid
+  if (tid < npat)
+    for (int n = 0; n < N; ++n) c += s_key[n] == tid ? 1 : 0;
+  s_start[tid] = c;
+  __syncthreads();
+  if (tid == 0) {
+    int acc = 0;
+    for (int q = 0; q < npat; ++q) { const int v = s_start[q]; s_start[q] = acc; acc += v; }
+    *count = N;
+  }
+  __syncthreads();
+  if (tid >= npat) return;
+  int pos = s_start[tid];
+  for (int n = 0; n < N; ++n)
+    if (s_key[n] == tid) { perm[pos] = n; sbits[pos] = (uint8_t)tid; ++pos; }
+}
+
 struct DynWs { size_t need_counts, pix, h1, h2, blocks, wpack, bytes; };
 static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
@@ -948,13 +985,22 @@ static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   return w;
 }
 
-struct CsWs { size_t h1, h2, bytes; };
+// h1, h2: compact scratch activations.  perm / sbits / rbits / cnt: the samples ordered by mask pattern, the patterns
+// in that order and in sample order, and the sample count as a device integer (the fused-kernel path); wpack: room
+// for the re-ordered weights of a block that brings none.
+struct CsWs { size_t h1, h2, perm, sbits, rbits, cnt, wpack, bytes; };
 static CsWs cs_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
   CsWs w;
   w.h1 = 0;
   w.h2 = align_up(npix * c_mid * eb, 256);
-  w.bytes = 2 * w.h2;
+  w.perm = 2 * w.h2;
+  w.sbits = w.perm + align_up((size_t)fx.N * 4, 256);
+  w.rbits = w.sbits + align_up((size_t)fx.N, 256);
+  w.cnt = w.rbits + align_up((size_t)fx.N, 256);
+  w.wpack = w.cnt + 256;
+  w.bytes = w.wpack + (head_supported(fx.dtype, fx.C, c_mid) ? head_packed_bytes(fx.C) : 0) +
+            (tail_supported(fx.dtype, c_mid, fx.C) ? tail_packed_bytes(c_mid, fx.C) : 0);
   return w;
 }
 
@@ -1522,6 +1568,34 @@ extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bo
   void* h1 = (char*)ws + L.h1;
   void* h2 = (char*)ws + L.h2;
   const long long hw = (long long)fx.H * fx.W;
+
+  // 256-wide bf16 blocks with groups of whole 64-channel slices: the register-weight first 1x1 on every pixel (h1 zeroed
+  // in the groups a sample drops) and the fused 3x3 -> last 1x1 kernel over the samples ordered by mask pattern, which
+  // skips the input slices of groups no row of a tile keeps and zeroes h2 in the groups a row drops.
+  const int G = p->c_mid / D;
+  if (tail_wanted(fx.dtype, p, nullptr) && head_wanted(fx.dtype, p) && D <= 8 && G % 64 == 0 && fx.H == fx.W &&
+      fx.N <= 4096) {
+    char* wsb = (char*)ws;
+    int32_t* perm = (int32_t*)(wsb + L.perm);
+    uint8_t* sbits = (uint8_t*)(wsb + L.sbits);
+    uint8_t* rbits = (uint8_t*)(wsb + L.rbits);
+    int32_t* cnt = (int32_t*)(wsb + L.cnt);
+    hipLaunchKernelGGL(k_cs_sort, dim3(1), dim3(kCsSortThreads), (size_t)fx.N, st, cmask, fx.N, D, perm, sbits, rbits, cnt);
+    if ((rc = check_launch()) != LAUD_OK) return rc;
+    if (!p->packed && (rc = pack_weights_into(fx.dtype, p, wsb + L.wpack, true, true, st)) != LAUD_OK) return rc;
+    const char* packed = (const char*)(p->packed ? p->packed : wsb + L.wpack);
+    const PackedLayout PL = packed_layout(fx.dtype, p);
+    HeadArgs h{};
+    h.x = x; h.wpacked = packed + PL.head; h.s1 = p->s1; h.t1 = p->t1; h.h1 = h1;
+    h.m_rows = (int)(fx.N * hw); h.K = p->c_in; h.rbits = rbits; h.hw = (int)hw; h.cs_group = G;
+    if ((rc = launch_head(h, st)) != LAUD_OK) return rc;  // (stage timing books the two kernels as conv1 / conv2)
+    TailArgs t{};
+    t.h1 = h1; t.wpacked = packed + PL.tail; t.s2 = p->s2; t.t2 = p->t2; t.s3 = p->s3; t.t3 = p->t3;
+    t.res = x; t.out = out; t.count = cnt; t.list = perm; t.cap_patches = fx.N;
+    t.H = fx.H; t.W = fx.W; t.S = fx.H; t.stride = 1; t.Ho = fx.H; t.Wo = fx.W; t.cout = p->c_out;
+    t.relu = p->relu_out ? 1 : 0; t.sbits = sbits; t.cs_group = G;
+    return launch_tail(t, fx.N * hw, st);
+  }
 
   GemmArgs a{};
   a.H = fx.H; a.W = fx.W; a.S = 1; a.D = D; a.G = p->c_mid / D; a.cmask = cmask;

@@ -68,6 +68,18 @@ __device__ __forceinline__ void head_tile(const HeadArgs& a, const int row0, con
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l31 = lane & 31, lhi = lane >> 5, l8 = lane >> 3, l7 = lane & 7;
   const int K = a.K, NSL = K / 64;
+  // Channel skipping (dense rows only): the mask multiplies the 3x3's input, so h1 is stored as zero in the groups a
+  // row's sample drops.  Bit t: the row of pixel block t this lane stores keeps the group of this wave's 32 channels.
+  unsigned hkeep = ~0u;
+  if (a.rbits != nullptr && !listed) {
+    hkeep = 0;
+#pragma unroll
+    for (int t = 0; t < PB; ++t) {
+      const int n = min(row0 + 32 * t + l31, M - 1) / a.hw;
+      hkeep |= (((unsigned)a.rbits[n] >> ((wave * 32) / a.cs_group)) & 1u) << t;
+    }
+  }
+
   // ---- weight stream: four slices in registers -------------------------------------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
@@ -193,10 +205,14 @@ __device__ __forceinline__ void head_tile(const HeadArgs& a, const int row0, con
         v[4 * g + 2] = fmaxf(acc[t][4 * g + 2] * sc.z + sh.z, 0.f);
         v[4 * g + 3] = fmaxf(acc[t][4 * g + 3] * sc.w + sh.w, 0.f);
       }
+      const int pixel = s_orow[32 * t + l31];
+      if (!((hkeep >> t) & 1u)) {  // channel skipping: the row's sample drops the group of this wave's channels
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = 0.f;
+      }
       to_consecutive_channels(v);
       const uint4 c0 = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[8], v[9]), pack_bf16(v[10], v[11]));
       const uint4 c1 = make_uint4(pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]), pack_bf16(v[12], v[13]), pack_bf16(v[14], v[15]));
-      const int pixel = s_orow[32 * t + l31];
       if (pixel >= 0) {
         uint4* dst = reinterpret_cast<uint4*>(outp + (size_t)pixel * kMid + cb + lhi * 16);
         dst[0] = c0;

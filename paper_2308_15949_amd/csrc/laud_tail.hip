@@ -65,7 +65,7 @@ __device__ long long g_tail_fine[8 * 64];
 #endif
 
 // One tile: rows row0 .. row0 + 32*PB - 1 of the compact list of active pixels (M rows exist).
-template <int NCT, int PB>  // NCT column tiles of 256 output channels (cout = 256 * NCT)
+template <int NCT, int PB, bool CS>  // NCT column tiles of 256 output channels (cout = 256 * NCT); CS: channel mask
 __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, const int M) {
   using namespace tail;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -95,11 +95,48 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
   int qsp[kAI];
 #pragma unroll
   for (int i = 0; i < kAI; ++i) qsp[i] = a.list[min((row0 + 64 * i + 8 * wave + l8) / SS, a.cap_patches - 1)];
+  // ---- channel skipping: which input slices of the 3x3 this tile needs ---------------------------------------------
+  // The tile's rows belong to the list entries (samples) row0/SS .. (row0+kBM-1)/SS; a K chunk (64 input channels) is
+  // needed if any of them keeps the chunk's group.  n2 = slices of the 3x3 that are multiplied (9 taps x kept
+  // chunks, tap-major); position i of that sequence is slice sid(i) of the packed stream, and the stream goes on
+  // into the last 1x1 (all of it: h2 is zero where a row drops a group) behind position n2.
+  int n2 = kSl2;
+  unsigned kcpack = 0xe4u;  // kept K chunks, two bits each (0, 1, 2, 3)
+  int nkc = kKch;
+  if constexpr (CS) {
+    const int e0 = row0 / SS, e1 = min(row0 + kBM - 1, M - 1) / SS;
+    unsigned u = 0;
+    for (int e = e0; e <= e1; ++e) u |= a.sbits[e];
+    kcpack = 0; nkc = 0;
+#pragma unroll
+    for (int kc = 0; kc < kKch; ++kc)
+      if ((u >> ((kc * 64) / a.cs_group)) & 1u) { kcpack |= (unsigned)kc << (2 * nkc); ++nkc; }
+    n2 = 9 * nkc;
+  }
+  auto sid = [&](int i) __attribute__((always_inline)) -> int {  // packed-stream slice at position i
+    if constexpr (!CS) return i;
+    if (i >= n2) return kSl2 + (i - n2);
+    const int tap = i / nkc, j = i - tap * nkc;
+    return tap * kKch + (int)((kcpack >> (2 * j)) & 3u);
+  };
+
+  // ... and, per pixel block t of this lane's rows, whether the row keeps the group of this wave's 32 channels (bit t)
+  unsigned hkeep = ~0u;
+  if constexpr (CS) {
+    hkeep = 0;
+#pragma unroll
+    for (int t = 0; t < PB; ++t) {
+      const int e = min(row0 + 32 * t + l31, M - 1) / SS;
+      hkeep |= (((unsigned)a.sbits[e] >> ((wave * 32) / a.cs_group)) & 1u) << t;
+    }
+  }
+
   // ---- weight stream: three slices in registers (one in use, two in flight) ------------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
   u32x4 wr[kWRing][4];
-  auto load_W = [&](int buf, int b) __attribute__((always_inline)) {
+  auto load_W = [&](int buf, int i) __attribute__((always_inline)) {  // position i of the slice sequence
+    const int b = sid(i);
 #pragma unroll
     for (int kg = 0; kg < 4; ++kg) wr[buf][kg] = wsrc[(size_t)b * kSliceChunks + kg * 64];
   };
@@ -149,14 +186,15 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
   const __amdgpu_buffer_rsrc_t h1rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(reinterpret_cast<const char*>(a.h1)) - ashift, 0, (int)kOob, 0x00020000);
   const unsigned ldsA = kAOff + wave * 1024;
-  auto issue_A = [&](int s) __attribute__((always_inline)) {
-    const int tap = s / kKch, kc = s - tap * kKch;
+  auto issue_A = [&](int s) __attribute__((always_inline)) {  // position s of the slice sequence -> ring stage s % 4
+    const int b = s < n2 ? sid(s) : kSl2;
+    const int tap = b / kKch, kc = b - tap * kKch;
     const int ky = tap / 3, kx = tap - ky * 3;
     const unsigned soff = (unsigned)((ky * a.W + kx) * kMid + kc * 64) * 2u;
 #pragma unroll
     for (int i = 0; i < kAI; ++i) {
       if (i == kAI - 1 && !lastA) break;
-      const unsigned v = (tap < 9 && ((amask[i] >> tap) & 1u)) ? voffA[i] : kOob;  // (slices past the 3x3: zeros)
+      const unsigned v = (tap < 9 && ((amask[i] >> tap) & 1u)) ? voffA[i] : kOob;  // (positions past the 3x3: zeros)
       dma16(h1rs, v, soff, ldsA + (unsigned)(s & (kARing - 1)) * kAStage + i * 8192);
     }
   };
@@ -205,7 +243,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
       const int s = s0 + g / 4, kg = g % 4;
       if (kg == 0) TAIL_STAMP(2 + s);
       if (kg < 3) read_frags2((g + 1) & 1, s, kg + 1);
-      else if (s + 1 < kSl2) read_frags2((g + 1) & 1, s + 1, 0);
+      else if (s + 1 < n2) read_frags2((g + 1) & 1, s + 1, 0);
       __builtin_amdgcn_sched_barrier(0);  // the next step's fragment reads stay ahead of this step's MFMAs
 #pragma unroll
       for (int t = 0; t < PB; ++t) acc[t] = mma_bf16(wr[g / 4][kg], fa[g & 1][t], acc[t]);
@@ -221,7 +259,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
       }
     }
   };
-  for (int s = 0; s < kSl2; s += 3) group2(s);
+  for (int s = 0; s < n2; s += 3) group2(s);
 
   // ---- h2 = relu(s2 * acc + t2) -> LDS -------------------------------------------------------------------------
   TAIL_STAMP(38);
@@ -238,6 +276,12 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
         v[4 * g + 1] = fmaxf(acc[t][4 * g + 1] * sc.y + sh.y, 0.f);
         v[4 * g + 2] = fmaxf(acc[t][4 * g + 2] * sc.z + sh.z, 0.f);
         v[4 * g + 3] = fmaxf(acc[t][4 * g + 3] * sc.w + sh.w, 0.f);
+      }
+      if constexpr (CS) {  // the mask multiplies the 3x3's output: a row that drops this wave's group stores zeros
+        if (!((hkeep >> t) & 1u)) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) v[e] = 0.f;
+        }
       }
       to_consecutive_channels(v);
       const uint4 c0 = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[8], v[9]), pack_bf16(v[10], v[11]));
@@ -383,7 +427,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
 // units (measured; a small tile is bound by its weight stream, a large one by LDS fragment reads + MFMAs).  Every
 // workgroup evaluates the same three candidates and takes the cheapest: a small active set spreads over the whole
 // chip, a large one does not leave a nearly empty last round.
-template <int NCT>
+template <int NCT, bool CS>
 __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const int M = *a.count * a.S * a.S;
   const int t32 = (M + 31) >> 5;
@@ -402,9 +446,9 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const int row0 = blockIdx.x * 32 * pb;
   if (row0 >= M) return;
   switch (pb) {
-    case 1: tail_tile<NCT, 1>(a, row0, M); break;
-    case 2: tail_tile<NCT, 2>(a, row0, M); break;
-    default: tail_tile<NCT, 3>(a, row0, M); break;
+    case 1: tail_tile<NCT, 1, CS>(a, row0, M); break;
+    case 2: tail_tile<NCT, 2, CS>(a, row0, M); break;
+    default: tail_tile<NCT, 3, CS>(a, row0, M); break;
   }
 }
 
@@ -432,7 +476,10 @@ int tail_init_device() {
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return LAUD_ERR_HIP;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return LAUD_ERR_HIP;
   g_tail_cus[dev] = cus;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail<4, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          tail::lds_bytes(tail::kMaxPB, 1024)) != hipSuccess)
+    return LAUD_ERR_HIP;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail<4, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              tail::lds_bytes(tail::kMaxPB, 1024)) == hipSuccess ? LAUD_OK : LAUD_ERR_HIP;
 }
 
@@ -459,7 +506,10 @@ int launch_tail(const TailArgs& args, long long cap_rows, hipStream_t st) {
   // of the height chosen on the device leave at once
   const unsigned grid = (unsigned)((cap_rows + 31) / 32);
   StageScope scope(LAUD_STAGE_CONV2, st);
-  hipLaunchKernelGGL((k_tail<4>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(tail::kMaxPB, 1024), st, a);
+  if (a.sbits)
+    hipLaunchKernelGGL((k_tail<4, true>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(tail::kMaxPB, 1024), st, a);
+  else
+    hipLaunchKernelGGL((k_tail<4, false>), dim3(grid), dim3(tail::kThreads), tail::lds_bytes(tail::kMaxPB, 1024), st, a);
   return check_launch();
 }
 

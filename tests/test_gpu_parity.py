@@ -377,6 +377,10 @@ CS_CASES = [
     (3, 14, 14, 256, 96, 16, I.BF16, True),  # G = 6 in bf16: element-wise, not a power of two, ragged kept widths
     (4, 7, 7, 64, 32, 8, I.BF16, True),      # G = 4 in bf16: gathered in 8-byte units
     (4, 14, 14, 256, 128, 64, I.BF16, True),  # G = 2 in bf16 over several K slices: 4-byte units
+    (37, 14, 14, 1024, 256, 4, I.BF16, True),  # fused-kernel path (samples ordered by pattern): tiles across samples and patterns
+    (9, 14, 14, 1024, 256, 2, I.BF16, False),  # ... G = 128
+    (5, 14, 14, 1024, 256, 1, I.BF16, True),   # ... one group: all or nothing per sample
+    (70, 7, 7, 1024, 256, 4, I.BF16, True),    # ... 49-pixel samples: several samples per tile
 ]
 
 
