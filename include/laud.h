@@ -234,6 +234,8 @@ int laud_dyn_group_se_bottleneck(const void* x, laud_fmap fx, const laud_bottlen
  * sample_offsets / logits outputs (same meaning, same optional NULLs) and the same `out`; logits
  * differ from laud_mask_gen's only in float32 summation order.  It pays off when the dilated
  * activation ratio is close to 1 (small S); c_in <= 4096.  Workspace: as LAUD_OP_DYN_BOTTLENECK.
+ * With a layer gate (`keep`) and logits == NULL the first 1x1 and the projection are evaluated on the kept samples
+ * only (the gates are compacted first); with logits wanted they cover every sample, gated ones included.
  */
 int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const laud_bottleneck* p, int S,
                                const float* w, float bias, const uint8_t* keep,

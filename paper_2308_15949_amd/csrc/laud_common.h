@@ -187,6 +187,11 @@ struct HeadArgs {
   const int32_t* list;   // [ngroups][group_rows] ascending pixel ids of the dilated active set
   const int32_t* counts; // [ngroups] device: valid entries per group
   int group_rows;        // capacity of one group's list
+  // rows = the pixels of listed samples (layer gate ahead of a spatially static first 1x1): slist [scap] ascending kept
+  // sample ids, *scount of them valid (device), hw pixels per sample; m_rows = scap * hw is the capacity.  Null: all rows.
+  const int32_t* slist;
+  const int32_t* scount;
+  int scap;
   // channel skipping: rbits[n] = kept channel groups (bit g) of sample n, hw = pixels per sample, cs_group = channels per
   // group (a multiple of 32); h1 is written as zero in the groups a row's sample drops.  Null: no channel mask.
   const uint8_t* rbits;

@@ -968,12 +968,13 @@ __global__ __launch_bounds__(kCsSortThreads) void k_cs_sort(const uint8_t* __res
     if (s_key[n] == tid) { perm[pos] = n; sbits[pos] = (uint8_t)tid; ++pos; }
 }
 
-struct DynWs { size_t need_counts, pix, h1, h2, blocks, wpack, bytes; };
+struct DynWs { size_t need_counts, scnt, pix, h1, h2, blocks, wpack, bytes; };
 static DynWs dyn_ws_layout(const laud_fmap& fx, int c_mid) {
   const size_t npix = (size_t)fx.N * fx.H * fx.W, eb = elem_bytes(fx.dtype);
   DynWs w;
   size_t o = 0;
-  w.need_counts = o; o += align_up((size_t)fx.N * 4, 256);
+  w.need_counts = o; o += align_up((size_t)fx.N * 4, 256);  // (fused-masker variant: the kept-sample list of a layer gate)
+  w.scnt = o;        o += 256;                               // ... and its length
   w.pix = o;         o += align_up(npix * 4, 256);
   w.h1 = o;          o += align_up(npix * c_mid * eb, 256);
   w.h2 = o;          o += align_up(npix * c_mid * eb, 256);
@@ -1248,6 +1249,14 @@ extern "C" int laud_masker_dyn_bottleneck(const void* x, laud_fmap fx, const lau
     HeadArgs h{};
     h.x = x; h.wpacked = (const char*)(p->packed ? p->packed : wsb + L.wpack) + packed_layout(fx.dtype, p).head;
     h.s1 = p->s1; h.t1 = p->t1; h.h1 = h1; h.m_rows = (int)npix; h.K = p->c_in; h.wmask = w; h.proj = proj;
+    if (keep != nullptr && logits == nullptr) {
+      // layer gate: the first 1x1 (and the projection) run on the kept samples only -- ordered compaction of the
+      // gates, then rows = pixels of the listed samples.  (With `logits` wanted every sample's projection is needed.)
+      int32_t* slist = (int32_t*)(wsb + L.need_counts);
+      int32_t* scount = (int32_t*)(wsb + L.scnt);
+      if ((rc = launch_compact(keep, fx.N, slist, scount, nullptr, 1, (int32_t*)(wsb + L.blocks), st)) != LAUD_OK) return rc;
+      h.slist = slist; h.scount = scount; h.scap = fx.N; h.hw = fx.H * fx.W;
+    }
     if ((rc = launch_head(h, st)) != LAUD_OK) return rc;
   } else {
     attach_tail_pack(a, fx.dtype, p, nullptr, wsb + L.wpack);

@@ -247,6 +247,29 @@ __global__ __launch_bounds__(head::kThreads) void k_head(const HeadArgs a) {
   using namespace head;
   int pb = a.pb;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, l8 = lane >> 3;
+  if (a.slist != nullptr) {
+    // Rows = the pixels of the kept samples, in list order: row -> (slot = row / hw, pixel of sample slist[slot]).  The
+    // count lives on the device, so the height is decided here (as for pixel lists), and the sample ids of this lane's
+    // rows are requested for both candidate heights together with the count.
+    const int r8 = 8 * wv + l8;
+    auto pix_of = [&](int row) __attribute__((always_inline)) {
+      const int slot = row / a.hw;
+      return a.slist[min(slot, a.scap - 1)] * a.hw + (row - slot * a.hw);
+    };
+    const int p2[1] = {pix_of((int)blockIdx.x * 64 + r8)};
+    const int p4[2] = {pix_of((int)blockIdx.x * 128 + r8), pix_of((int)blockIdx.x * 128 + 64 + r8)};
+    const int M = *a.scount * a.hw;
+    if (pb == 0) {
+      const int t2 = (M + 63) >> 6, t4 = (M + 127) >> 7;
+      const int c2 = ((t2 + a.wg_target - 1) / a.wg_target) * kCost2, c4 = ((t4 + a.wg_target - 1) / a.wg_target) * kCost4;
+      pb = c2 <= c4 ? 2 : 4;
+    }
+    const int row0 = blockIdx.x * 32 * pb;
+    if (row0 >= M) return;
+    if (pb == 2) head_tile<PROJ, 2>(a, row0, M, true, p2);
+    else head_tile<PROJ, 4>(a, row0, M, true, p4);
+    return;
+  }
   if (a.list == nullptr) {
     const int row0 = blockIdx.x * 32 * pb;
     if (row0 >= a.m_rows) return;
@@ -333,7 +356,11 @@ int launch_head(const HeadArgs& args, hipStream_t st) {
   a.wg_target = g_head_cus[dev];
   unsigned grid;
   int lds_pb = head::kMaxPB;
-  if (a.list == nullptr) {
+  if (a.slist != nullptr) {
+    // pixels of listed samples: capacity m_rows = scap * hw rows, the count is on the device
+    if (a.pb != 2 && a.pb != 4) a.pb = 0;
+    grid = (unsigned)((a.m_rows + (a.pb == 4 ? 127 : 63)) / (a.pb == 4 ? 128 : 64));
+  } else if (a.list == nullptr) {
     // dense rows: the count is known here; the same rounds x tile-time cost the kernel uses for lists
     if (a.pb != 2 && a.pb != 4) {
       const long long t2 = (a.m_rows + 63) / 64, t4 = (a.m_rows + 127) / 128;

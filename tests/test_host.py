@@ -59,7 +59,8 @@ def test_workspace_sizes(lib):
     assert packed == 256 * 1024 * 2 + (256 * 9 * 256 + 1024 * 256) * 2
     assert dyn >= 2 * npix * 256 * 2 + npix * 4 + packed and dyn < 2 * npix * 256 * 2 + npix * 4 + packed + 8192  # + small counters
     assert L.packed_weights_size(p, B.F32) == 0 and L.packed_weights_size(_bn(256, 64, 256), B.BF16) == 0
-    assert L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4) == 2 * npix * 256 * 2
+    cs = L.workspace_size(B.OP_CHANNEL_SKIP, fx, p, 4)   # h1 + h2, the sample order of the fused-kernel path, packed weights
+    assert 2 * npix * 256 * 2 + packed <= cs < 2 * npix * 256 * 2 + packed + 8192
     assert L.workspace_size(B.OP_MASK_GEN, fx, None, 2) == 256
     assert L.workspace_size(B.OP_COMPACT, fx, None, 300001) >= 4 * 74
     assert L.workspace_size(B.OP_GATHER, fx, None, 2) == 0
