@@ -458,6 +458,45 @@ def test_config2_full_size_sampled(G, r, fused):
     assert_close(got[up], ref[up], TOL[dt], "config 2 sampled images")
 
 
+@pytest.mark.parametrize("N,r,fused", [(44, 1.0, False), (44, 0.97, True), (86, 1.0, True), (86, 0.9, False), (67, 0.33, True)])
+def test_register_weight_kernels_every_tile_height_exhaustive(G, N, r, fused):
+    """The 256-wide bf16 block at sizes that make the kernels pick each of their tile heights (the fused 3x3 -> 1x1
+    kernel: 32 / 64 / 96 pixels from the active count -- 44 images all active give 270 blocks of 32 pixels, more than
+    the compute units, hence 64-pixel tiles with a ragged last one; 86 images 96-pixel tiles; the first 1x1: 64 or
+    128 pixels), compared on EVERY image, with ragged last tiles and partly active batches."""
+    t, L, D = G.torch, G.L, G.D
+    H, C, m, S, dt = 14, 1024, 256, 2, I.BF16
+    x = I.feature_map(4400 + N, N, H, H, C, dt)
+    hb = I.bottleneck_params(4401 + N, C, m, C, dt, relu_out=True)
+    w = I.masker_weights(4402 + N, C)
+    ref0 = O.mask_logits(x, S, w, 0.0)
+    bias, half_gap = I.bias_for_ratio(ref0, r)
+    ref_mask = O.threshold(ref0 + bias)
+    xd = D.to_device(x, dt)
+    fx = L.fmap_of(xd)
+    db = D.DeviceBottleneck(hb)
+    npatch = N * 49
+    mask = t.zeros(npatch, dtype=t.uint8, device="cuda")
+    idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+    cnt = t.zeros(1, dtype=t.int32, device="cuda")
+    ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+    ws.fill_(0xFF)
+    wd = t.from_numpy(w).cuda()
+    if fused:
+        L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, wd, bias, None, mask, idx, cnt, None, None, xd, ws)
+    else:
+        L.laud_mask_gen(xd, fx, S, wd, bias, None, mask, idx, cnt, None, None, D.workspace(4096))
+        L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
+    t.cuda.synchronize()
+    assert np.array_equal(mask.cpu().numpy().reshape(ref_mask.shape), ref_mask)
+    assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(ref_mask))
+    got = D.to_host(xd)
+    ref = O.dyn_bottleneck(x, oracle_params(hb), S, ref_mask)
+    up = O.upsample_mask(ref_mask, S).astype(bool)
+    assert np.array_equal(got[~up], x[~up])
+    assert_close(got[up], ref[up], TOL[dt], f"N = {N}, r = {r}")
+
+
 # ------------------------------------------------------------------------------------------
 # masker fused into the first 1x1 (laud_masker_dyn_bottleneck)
 # ------------------------------------------------------------------------------------------
