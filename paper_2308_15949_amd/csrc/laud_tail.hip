@@ -66,7 +66,7 @@ __device__ long long g_tail_fine[8 * 64];
 
 // One tile: rows row0 .. row0 + 32*PB - 1 of the compact list of active pixels (M rows exist).
 template <int NCT, int PB, bool CS>  // NCT column tiles of 256 output channels (cout = 256 * NCT); CS: channel mask
-__device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, const int M, const int (&qsp)[(PB + 1) / 2]) {
+__device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, const int M) {
   using namespace tail;
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int COUT = 256 * NCT;
@@ -92,6 +92,9 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
 
   TAIL_STAMP(0);
   const int SS = a.S * a.S;
+  int qsp[(PB + 1) / 2];
+#pragma unroll
+  for (int i = 0; i < (PB + 1) / 2; ++i) qsp[i] = a.list[min((row0 + 64 * i + 8 * wave + l8) / SS, a.cap_patches - 1)];
   // ---- channel skipping: which input slices of the 3x3 this tile needs ---------------------------------------------
   // The tile's rows belong to the list entries (samples) row0/SS .. (row0+kBM-1)/SS; a K chunk (64 input channels) is
   // needed if any of them keeps the chunk's group.  n2 = slices of the 3x3 that are multiplied (9 taps x kept
@@ -427,16 +430,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
 template <int NCT, bool CS>
 __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   using namespace tail;
-  // The index-list entries of this lane's activation rows are requested together with the count, for each of the
-  // three candidate tile heights (row = first row of the tile + 64 i + 8 wave + lane / 8; entries past the count are
-  // read -- the list's capacity covers them -- but never used): the tile's rows then cost one memory round trip
-  // after the count, not two.
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int SS = a.S * a.S, rr = 8 * wave + (lane >> 3), cap = a.cap_patches - 1;
-  const int b32 = blockIdx.x * 32;
-  const int q1[1] = {a.list[min((b32 + rr) / SS, cap)]};
-  const int q2[1] = {a.list[min((2 * b32 + rr) / SS, cap)]};
-  const int q3[2] = {a.list[min((3 * b32 + rr) / SS, cap)], a.list[min((3 * b32 + 64 + rr) / SS, cap)]};
+  const int SS = a.S * a.S, b32 = blockIdx.x * 32;
   const int M = *a.count * SS;
   const int t32 = (M + 31) >> 5;
   int pb = a.pb;
@@ -454,9 +448,9 @@ __global__ __launch_bounds__(tail::kThreads) void k_tail(const TailArgs a) {
   const int row0 = b32 * pb;
   if (row0 >= M) return;
   switch (pb) {
-    case 1: tail_tile<NCT, 1, CS>(a, row0, M, q1); break;
-    case 2: tail_tile<NCT, 2, CS>(a, row0, M, q2); break;
-    default: tail_tile<NCT, 3, CS>(a, row0, M, q3); break;
+    case 1: tail_tile<NCT, 1, CS>(a, row0, M); break;
+    case 2: tail_tile<NCT, 2, CS>(a, row0, M); break;
+    default: tail_tile<NCT, 3, CS>(a, row0, M); break;
   }
 }
 
