@@ -932,40 +932,61 @@ static int validate_block(const void* x, const laud_fmap& fx, const laud_bottlen
 }
 
 // Channel skipping on the fused kernels: the samples ordered by mask pattern (ascending pattern, ascending sample
-// id inside a pattern; no atomics, so the order is reproducible), so that the rows of a tile share their kept groups
-// and whole input slices can be skipped.  One block; pattern p = sum of (kept group g) << g, D <= 8.
+// id inside a pattern; ballots and prefix counts, no atomics, so the order is reproducible), so that the rows of a
+// tile share their kept groups and whole input slices can be skipped.  One block of four waves; pattern p = sum of
+// (kept group g) << g, D <= 4 (16 patterns), N <= 4096 (sixteen rounds of 256 samples, one sample per thread).
 // perm [N]: sample ids in that order; sbits [N]: their patterns in that order; rbits [N]: patterns by sample id;
 // count: N as a device integer (the kernels read their row count from the device).
-constexpr int kCsSortThreads = 256;
+constexpr int kCsSortThreads = 256, kCsSortPatterns = 16, kCsSortMaxN = 4096;
 __global__ __launch_bounds__(kCsSortThreads) void k_cs_sort(const uint8_t* __restrict__ cmask, int N, int D,
                                                             int32_t* __restrict__ perm, uint8_t* __restrict__ sbits,
                                                             uint8_t* __restrict__ rbits, int32_t* __restrict__ count) {
-  extern __shared__ unsigned char s_key[];  // [N]
-  __shared__ int s_start[kCsSortThreads];
-  const int tid = threadIdx.x;
-  for (int n = tid; n < N; n += kCsSortThreads) {
+  constexpr int kSlots = kCsSortMaxN / kWave;      // (round, wave) pairs
+  __shared__ int s_cnt[kCsSortPatterns][kSlots];   // samples of pattern p in slot (round * 4 + wave); then their base
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int rounds = (N + kCsSortThreads - 1) / kCsSortThreads;
+  for (int r = 0; r < rounds; ++r) {
+    const int n = r * kCsSortThreads + tid;
     unsigned key = 0;
-    for (int g = 0; g < D; ++g) key |= (cmask[(size_t)n * D + g] != 0 ? 1u : 0u) << g;
-    s_key[n] = (unsigned char)key;
-    rbits[n] = (uint8_t)key;
+    if (n < N) {
+      for (int g = 0; g < D; ++g) key |= (cmask[(size_t)n * D + g] != 0 ? 1u : 0u) << g;
+      rbits[n] = (uint8_t)key;
+    }
+#pragma unroll
+    for (int p = 0; p < kCsSortPatterns; ++p) {
+      const unsigned long long b = __ballot(n < N && key == (unsigned)p);
+      if (lane == 0) s_cnt[p][r * 4 + wave] = __popcll(b);
+    }
   }
   __syncthreads();
-  const int npat = 1 << D;
-  int c = 0;  // samples of pattern tid
-  if (tid < npat)
-    for (int n = 0; n < N; ++n) c += s_key[n] == tid ? 1 : 0;
-  s_start[tid] = c;
+  // exclusive prefix over (pattern major, slot minor): thread p sums its pattern's slots, thread 0 the patterns
+  __shared__ int s_tot[kCsSortPatterns];
+  const int nslots = rounds * 4;
+  if (tid < kCsSortPatterns) {
+    int acc = 0;
+    for (int q = 0; q < nslots; ++q) { const int v = s_cnt[tid][q]; s_cnt[tid][q] = acc; acc += v; }
+    s_tot[tid] = acc;
+  }
   __syncthreads();
   if (tid == 0) {
     int acc = 0;
-    for (int q = 0; q < npat; ++q) { const int v = s_start[q]; s_start[q] = acc; acc += v; }
+    for (int p = 0; p < kCsSortPatterns; ++p) { const int v = s_tot[p]; s_tot[p] = acc; acc += v; }
     *count = N;
   }
   __syncthreads();
-  if (tid >= npat) return;
-  int pos = s_start[tid];
-  for (int n = 0; n < N; ++n)
-    if (s_key[n] == tid) { perm[pos] = n; sbits[pos] = (uint8_t)tid; ++pos; }
+  for (int r = 0; r < rounds; ++r) {
+    const int n = r * kCsSortThreads + tid;
+    unsigned key = 0;
+    if (n < N)
+      for (int g = 0; g < D; ++g) key |= (cmask[(size_t)n * D + g] != 0 ? 1u : 0u) << g;
+    int pos = 0;
+#pragma unroll
+    for (int p = 0; p < kCsSortPatterns; ++p) {
+      const unsigned long long b = __ballot(n < N && key == (unsigned)p);
+      if (key == (unsigned)p) pos = s_tot[p] + s_cnt[p][r * 4 + wave] + ballot_prefix(b);
+    }
+    if (n < N) { perm[pos] = n; sbits[pos] = (uint8_t)key; }
+  }
 }
 
 struct DynWs { size_t need_counts, scnt, pix, h1, h2, blocks, wpack, bytes; };
@@ -1582,14 +1603,14 @@ extern "C" int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bo
   // in the groups a sample drops) and the fused 3x3 -> last 1x1 kernel over the samples ordered by mask pattern, which
   // skips the input slices of groups no row of a tile keeps and zeroes h2 in the groups a row drops.
   const int G = p->c_mid / D;
-  if (tail_wanted(fx.dtype, p, nullptr) && head_wanted(fx.dtype, p) && D <= 8 && G % 64 == 0 && fx.H == fx.W &&
-      fx.N <= 4096) {
+  if (tail_wanted(fx.dtype, p, nullptr) && head_wanted(fx.dtype, p) && D <= 4 && G % 64 == 0 && fx.H == fx.W &&
+      fx.N <= kCsSortMaxN) {
     char* wsb = (char*)ws;
     int32_t* perm = (int32_t*)(wsb + L.perm);
     uint8_t* sbits = (uint8_t*)(wsb + L.sbits);
     uint8_t* rbits = (uint8_t*)(wsb + L.rbits);
     int32_t* cnt = (int32_t*)(wsb + L.cnt);
-    hipLaunchKernelGGL(k_cs_sort, dim3(1), dim3(kCsSortThreads), (size_t)fx.N, st, cmask, fx.N, D, perm, sbits, rbits, cnt);
+    hipLaunchKernelGGL(k_cs_sort, dim3(1), dim3(kCsSortThreads), 0, st, cmask, fx.N, D, perm, sbits, rbits, cnt);
     if ((rc = check_launch()) != LAUD_OK) return rc;
     if (!p->packed && (rc = pack_weights_into(fx.dtype, p, wsb + L.wpack, true, true, st)) != LAUD_OK) return rc;
     const char* packed = (const char*)(p->packed ? p->packed : wsb + L.wpack);

@@ -381,6 +381,7 @@ CS_CASES = [
     (9, 14, 14, 1024, 256, 2, I.BF16, False),  # ... G = 128
     (5, 14, 14, 1024, 256, 1, I.BF16, True),   # ... one group: all or nothing per sample
     (70, 7, 7, 1024, 256, 4, I.BF16, True),    # ... 49-pixel samples: several samples per tile
+    (300, 7, 7, 1024, 256, 4, I.BF16, False),  # ... more samples than one round of the pattern sort
 ]
 
 
