@@ -580,6 +580,41 @@ def measure_extras(t, L, B, D, I, bufs, x_master, fx, wd, bias, S, mask, idx, cn
             res[f"{kind}_r{int(ratio * 100):03d}"] = {"p50_us": round(us, 1), "ratio": round(float(mk_h.mean()), 3),
                                                       "dilated_ratio": round(float(dil.mean()), 3)}
     ex["mask_structure_config2_two_call_block"] = res
+    # which entry point for which (S, ratio): masker fused into a first 1x1 on every pixel against masker + first 1x1 on the
+    # dilated active set (stage-3 block, batch 128, masker included in both; bias calibrated per S and ratio)
+    wm = t.from_numpy(I.masker_weights(7460, sg["c_in"])).cuda()
+    cross = {}
+    for S_ in (2, 7, 14):
+        npatch_ = N * (sg["hw"] // S_) ** 2
+        mk_ = t.zeros(npatch_, dtype=t.uint8, device="cuda")
+        ids_ = t.zeros(npatch_, dtype=t.int32, device="cuda")
+        cn_ = t.zeros(1, dtype=t.int32, device="cuda")
+        lg_ = t.zeros(npatch_, dtype=t.float32, device="cuda")
+        wsm_ = D.workspace(max(L.workspace_size(B.OP_MASK_GEN, fxs, None, S_), 256))
+        wsd_ = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, S_))
+        L.laud_mask_gen(xs, fxs, S_, wm, 0.0, None, mk_, ids_, cn_, None, lg_, wsm_)
+        t.cuda.synchronize()
+        lgh = lg_.cpu().numpy()
+        row = {}
+        for ratio in (0.1, 0.25, 0.5):
+            b_ = I.bias_for_ratio(lgh, ratio)[0]
+
+            def fused_(i):
+                L.laud_masker_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, S_, wm, b_, None, mk_, ids_, cn_, None, None, xb[i % 4], wsd_)
+
+            def twocall_(i):
+                L.laud_mask_gen(xb[i % 4], fxs, S_, wm, b_, None, mk_, ids_, cn_, None, None, wsm_)
+                L.laud_dyn_bottleneck(xb[i % 4], fxs, dbs.desc, S_, ids_, cn_, xb[i % 4], wsd_)
+            cur_ = [0]
+
+            def fresh_():   # (untimed) the block works in place: every launch gets the pristine input again
+                xb[cur_[0] % 4].copy_(xs)
+            row[f"r{int(ratio * 100):03d}"] = {
+                "fused_p50_us": round(_p50_us(t, lambda i: (cur_.__setitem__(0, i + 1), fused_(i)), iters=12, warm=2, prep=fresh_), 1),
+                "two_call_p50_us": round(_p50_us(t, lambda i: (cur_.__setitem__(0, i + 1), twocall_(i)), iters=12, warm=2, prep=fresh_), 1)}
+        cross[f"S{S_}"] = row
+        del wsd_, wsm_
+    ex["entry_point_crossover_stage3_b128"] = cross
     del xb, xs, wsd
     # operator-fusion ablation in the manner of the paper's Tab. 1 (masker + block, p50 per step):
     #   unfused    = laud_mask_gen, then gather / convs on gathered tiles / scatter-add as separate kernels

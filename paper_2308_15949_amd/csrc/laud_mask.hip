@@ -261,6 +261,28 @@ __global__ __launch_bounds__(kCompactThreads) void k_pool_compact_s2(PoolArgs pa
   }
 }
 
+// The same in one launch for any S when one block holds all patches (coarse granularities: S = 7 on a 14 x 14 map
+// gives 512 patches for 128 images): one patch per thread, decision by pooled_decision (so the masks are those of
+// the two-launch path, bit for bit), ordered compaction with one ballot and one scan of the wave counts.
+__global__ __launch_bounds__(kCompactThreads) void k_pool_compact_one_block(PoolArgs pa, int n, uint8_t* __restrict__ mask,
+                                                                            int32_t* __restrict__ idx,
+                                                                            int32_t* __restrict__ count,
+                                                                            int32_t* __restrict__ sample_offsets,
+                                                                            int per_sample) {
+  __shared__ int scan[kCompactThreads / kWave];
+  const int q = threadIdx.x;
+  const bool on = q < n ? pooled_decision(pa, q, mask) : false;
+  const unsigned long long bal = __ballot(on);
+  int tot;
+  const int pos = scan_wave_counts(__popcll(bal), kCompactThreads / kWave, scan, &tot) + ballot_prefix(bal);
+  if (sample_offsets && q < n && (q % per_sample) == 0) sample_offsets[q / per_sample] = pos;
+  if (on) idx[pos] = q;
+  if (q == 0) {
+    *count = tot;
+    if (sample_offsets) sample_offsets[n / per_sample] = tot;
+  }
+}
+
 // Ordered compaction of up to 64 x 4096 entries in ONE launch of several blocks: block b owns entries
 // [4096 b, 4096 b + 4096) and first counts the set entries of all blocks before it by itself (one 4-byte load
 // per thread and preceding block, eight in flight) instead of waiting for anybody: no second launch, no
@@ -362,6 +384,12 @@ int launch_pool_compact(const float* proj, int N, int H, int W, int S, float bia
     StageScope scope(LAUD_STAGE_COMPACT, stream);
     hipLaunchKernelGGL(k_pool_compact_s2, dim3((npatch + kCompactThreads - 1) / kCompactThreads), dim3(kCompactThreads), 0,
                        stream, pa, npatch, mask, idx, count, sample_offsets, pps);
+    return check_launch();
+  }
+  if (npatch > 0 && npatch <= kCompactThreads) {
+    StageScope scope(LAUD_STAGE_COMPACT, stream);
+    hipLaunchKernelGGL(k_pool_compact_one_block, dim3(1), dim3(kCompactThreads), 0, stream, pa, npatch, mask, idx, count,
+                       sample_offsets, pps);
     return check_launch();
   }
   // One thread per patch over a wide grid: the S*S projection reads of a patch are independent, and a
