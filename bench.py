@@ -372,7 +372,7 @@ def measure_bodies(t, L, B, D, I):
         return res
 
     ex["config3_resnet101_body_b128"] = dict(run_body(128, None, (1, 2, 3, 4)), note=(
-        "stem (im2col + GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at activation "
+        "stem (7x7 implicit GEMM + max pool) + 4 projection blocks + 29 dynamic identity blocks at activation "
         "ratio 0.5 each; the stem's kernels carry no stage label"))
     t.cuda.empty_cache()
     # config 3 widened (Sec. 3.1 / 3.2: maskers in every block; Sec. 4: the granularity settings S^net of the paper's table)
