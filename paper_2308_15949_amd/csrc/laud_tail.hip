@@ -11,15 +11,19 @@
 //   * Operands reach LDS with LDS-direct 16-byte buffer loads (no VGPR staging, no ds_write): a wave instruction
 //     drops 64 x 16 bytes = 8 rows of a 128-byte K slice.  Bank conflicts are avoided by an XOR swizzle of the 16-byte
 //     chunk position applied on the global side: chunk c of row r lies at position c ^ (r&7) ^ ((r>>3)&1).
-//   * Rings: 4 activation stages (4 KB per 32 pixels each), 3 weight stages (32 KB each, in registers).  One barrier per slice, placed in the
-//     middle of the slice's MFMAs; fragments of the next K step (also across slices) are read before the current
-//     step's MFMAs are issued.
+//   * Rings: 4 activation stages (4 KB per 32 pixels each), 3 weight stages (32 KB each, in registers).  One barrier
+//     per slice, placed in the middle of the slice's MFMAs; fragments of the next K step (also across slices) are
+//     read before the current step's MFMAs are issued.
 //   * The MFMAs compute the transposed tile (weights as the first operand): a lane then holds, for one pixel,
 //     4 x 4 consecutive channels; one v_permlane32_swap per register pair turns that into 16 consecutive channels
 //     per lane, so h2 goes to LDS, and the result to memory, in 16-byte pieces without an LDS transpose.
 //   * h2 (pixels x 256 bf16) sits behind the activation ring in LDS; the last 1x1 streams w3 through the
 //     same weight ring (no barrier at all in that phase), reads the residual 32 bytes per lane and pixel, adds,
 //     applies the activation, rounds and stores.
+//
+// Channel skipping (Fig. 2(c)) rides on the same kernel (template flag CS): the "patches" are whole samples in
+// mask-pattern order, the 3x3 leaves out the 64-channel input slices whose group no row of the tile keeps, and h2 is
+// stored as zero in the groups a row drops.
 //
 // Vector-memory counter discipline: the LDS-direct loads are issued from inline assembly, so the compiler does
 // not know them.  Every wait for them is an explicit s_waitcnt vmcnt(n), n = number of LOADS this wave issued
