@@ -697,6 +697,49 @@ def test_config5_layer_gate_and_spatial_full_size_sampled(G):
         assert_close(got[up], ref[up], TOL[dt], "config 5 stage-3 block")
 
 
+@pytest.mark.parametrize("gate", ["none_kept", "one_kept", "last_only", "random", "all_kept"])
+def test_fused_masker_block_with_layer_gate_runs_first_1x1_on_kept_samples(G, gate):
+    """With a layer gate and no logits wanted the fused-masker block compacts the gates and evaluates the first 1x1 on
+    the kept samples only; with logits wanted it covers every sample.  Both must give the oracle's result, the same
+    masks and indices, and bit-identical outputs -- for empty, single-sample, ragged and full gates."""
+    t, L, D = G.torch, G.L, G.D
+    N, H, C, m, S, dt = 21, 14, 1024, 256, 2, I.BF16
+    x = I.feature_map(5600, N, H, H, C, dt)
+    hb = I.bottleneck_params(5601, C, m, C, dt, relu_out=True)
+    w = I.masker_weights(5602, C)
+    keep = {"none_kept": np.zeros(N, np.uint8), "one_kept": np.eye(1, N, 7, dtype=np.uint8)[0],
+            "last_only": np.eye(1, N, N - 1, dtype=np.uint8)[0], "random": I.bernoulli_mask(5603, (N,), 0.6),
+            "all_kept": np.ones(N, np.uint8)}[gate]
+    ref0 = O.mask_logits(x, S, w, 0.0)
+    bias, _ = I.bias_for_ratio(ref0, 0.5)
+    ref_mask = O.threshold(ref0 + bias) * keep[:, None, None]
+    ref = O.layer_skip_bottleneck(x, oracle_params(hb), keep, S, O.threshold(ref0 + bias))
+    db = D.DeviceBottleneck(hb)
+    npatch = N * 49
+    outs = []
+    for want_logits in (False, True):
+        xd = D.to_device(x, dt)
+        fx = L.fmap_of(xd)
+        mask = t.full((npatch,), 7, dtype=t.uint8, device="cuda")
+        idx = t.zeros(npatch, dtype=t.int32, device="cuda")
+        cnt = t.full((1,), -1, dtype=t.int32, device="cuda")
+        lg = t.zeros(npatch, dtype=t.float32, device="cuda") if want_logits else None
+        ws = D.workspace(L.workspace_size(L.binding.OP_DYN_BOTTLENECK, fx, db.desc, S))
+        ws.fill_(0xFF)   # NaN patterns: a projection or an h1 row read without having been written shows up
+        L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, t.from_numpy(w).cuda(), bias, t.from_numpy(keep).cuda(), mask, idx,
+                                     cnt, None, lg, xd, ws)
+        t.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().reshape(ref_mask.shape), ref_mask)
+        assert np.array_equal(idx.cpu().numpy()[: int(cnt.item())], O.compact(ref_mask))
+        got = D.to_host(xd)
+        up = O.upsample_mask(ref_mask, S).astype(bool)
+        assert np.array_equal(got[~up], x[~up])
+        if up.any():
+            assert_close(got[up], ref[up], TOL[dt], f"gate {gate}")
+        outs.append(got)
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_chain_of_dynamic_blocks_in_place(G):
     """Three consecutive stage-3 identity blocks (each with its own masker and weights) applied in place,
     as in the body of the network.  The oracle runs its own chain from the same seeded input (float64, nothing
