@@ -260,9 +260,14 @@ int laud_dyn_bottleneck_unfused(const void* x, laud_fmap fx, const laud_bottlene
 /*
  * Channel-skipping bottleneck (Fig. 2(c); Sec. 3.1-3.2).  cmask is [N][D] bytes; group g of
  * sample n covers mid channels [g*G, (g+1)*G), G = c_mid / D.  The mask multiplies the input
- * and the output of the 3x3 conv; dropped channels are never computed (the weight gather is
- * fused into the convs).  out = act(x + s3*conv1x1(h2 masked; w3) + t3) on every pixel; with
- * all groups dropped out = act(x + t3).  out may be the same pointer as x.
+ * and the output of the 3x3 conv.  Two schedules, same result: in general the kept-channel weight
+ * gather is fused into the three convs and dropped channels are never computed (one set of tiles per
+ * sample); for bf16 blocks with c_mid = 256, c_out = 1024, groups of whole 64-channel slices (D <= 4),
+ * square maps and N <= 4096 the samples are ordered by mask pattern, the first 1x1 stores zeros in the
+ * dropped groups of h1, and the fused 3x3 -> last 1x1 kernel skips every 64-channel input slice that no
+ * row of a tile keeps and stores zeros in the dropped groups of h2 (p->packed is used when given).
+ * out = act(x + s3*conv1x1(h2 masked; w3) + t3) on every pixel; with all groups dropped
+ * out = act(x + t3).  out may be the same pointer as x.  Workspace: LAUD_OP_CHANNEL_SKIP.
  */
 int laud_channel_skip_conv(const void* x, laud_fmap fx, const laud_bottleneck* p,
                            const uint8_t* cmask, int D, void* out,
