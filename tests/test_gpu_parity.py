@@ -509,6 +509,8 @@ FUSED_CASES = [
     (3, 7, 7, 2048, 512, 1, I.BF16, True),
     (2, 28, 28, 512, 128, 4, I.BF16, True),
     (5, 14, 14, 64, 32, 14, I.F32, True),      # S = H: the masker is a layer gate
+    (6, 14, 14, 1024, 256, 7, I.BF16, True),   # coarse patches on the 256-wide block: masker + sparse first 1x1 inside
+    (6, 28, 28, 512, 128, 7, I.BF16, False),   # ... on the generic kernels
     (40, 28, 28, 16, 8, 1, I.BF16, False),     # 31360 patches: still the one-launch compaction
     (44, 28, 28, 16, 8, 1, I.BF16, False),     # 34496 patches: pooled mask kernel + block compaction
 ]
