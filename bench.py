@@ -253,7 +253,7 @@ def measure_bodies(t, L, B, D, I):
     #             calibrated to ratio 0.5 on the block's actual input
     #   config 5: batch 256, a seeded Bernoulli(0.6) keep gate per sample and block (layer skipping: the kept
     #             samples are compacted, S = H), AND-ed with spatial maskers (S = 2, ratio 0.5) in stage 3
-    def run_body(N, keep_p, spatial_stages, S_set=None, dyn_first=False, graph=True):
+    def run_body(N, keep_p, spatial_stages, S_set=None, dyn_first=False, graph=True, layer_masker=False):
         g = np.random.default_rng(7700)
         img8 = I.round_to(g.standard_normal((8, 224, 224, 3), dtype=np.float32), I.BF16)
         img = D.to_device(img8, I.BF16).repeat(N // 8, 1, 1, 1).contiguous()
@@ -324,8 +324,23 @@ def measure_bodies(t, L, B, D, I):
                                                              s3_gain=0.25))
                 if wsd is None:
                     wsd = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fxs, dbs.desc, Ss))
-                kp = None
-                if keep_p is not None:
+                kp, gate_op = None, None
+                if keep_p is not None and layer_masker:
+                    # the gate comes from the layer masker (the spatial masker at S = feature size: one decision per
+                    # sample), bias calibrated to the keep ratio on the block's actual input; it stays on the device
+                    wl = t.from_numpy(I.masker_weights(8050 + 100 * stage + bidx, co)).cuda()
+                    kp = t.zeros(N, dtype=t.uint8, device="cuda")
+                    gid = t.zeros(N, dtype=t.int32, device="cuda")
+                    gcn = t.zeros(1, dtype=t.int32, device="cuda")
+                    glg = t.zeros(N, dtype=t.float32, device="cuda")
+                    wsl = D.workspace(max(L.workspace_size(B.OP_MASK_GEN, fxs, None, hw), 256))
+                    L.laud_mask_gen(xs, fxs, hw, wl, 0.0, None, kp, gid, gcn, None, glg, wsl)
+                    t.cuda.synchronize()
+                    bl = I.bias_for_ratio(glg.cpu().numpy(), keep_p)[0]
+                    gate_op = (lambda xs=xs, fxs=fxs, hw=hw, wl=wl, bl=bl, kp=kp, gid=gid, gcn=gcn, wsl=wsl:
+                               L.laud_mask_gen(xs, fxs, hw, wl, bl, None, kp, gid, gcn, None, None, wsl))
+                    held += [wl, kp, gid, gcn, glg, wsl]
+                elif keep_p is not None:
                     kp = t.from_numpy(I.bernoulli_mask(8000 + 100 * stage + bidx, (N,), keep_p)).cuda()
                     held.append(kp)
                 if spatial:
@@ -333,15 +348,19 @@ def measure_bodies(t, L, B, D, I):
                     L.laud_mask_gen(xs, fxs, Ss, wm, 0.0, None, mk, ids, cn, None, lgs, wsm2)
                     t.cuda.synchronize()
                     bb = I.bias_for_ratio(lgs.cpu().numpy(), 0.5)[0]
-                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, kp=kp, mk=mk, ids=ids, cn=cn, wsd=wsd:
-                          L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, kp, mk, ids, cn, None, None, xs, wsd))
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, wm=wm, bb=bb, kp=kp, mk=mk, ids=ids, cn=cn, wsd=wsd, gate_op=gate_op: (
+                          gate_op() if gate_op else None,
+                          L.laud_masker_dyn_bottleneck(xs, fxs, dbs.desc, Ss, wm, bb, kp, mk, ids, cn, None, None, xs, wsd)))
                     held.append(wm)
+                elif gate_op is not None:  # layer skipping alone, gates from the layer masker: its index list is the block's
+                    op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, gid=gid, gcn=gcn, cn=cn, wsd=wsd, gate_op=gate_op: (
+                          gate_op(), L.laud_dyn_bottleneck(xs, fxs, dbs.desc, Ss, gid, gcn, xs, wsd)))
                 else:  # layer skipping only: the gate is the mask, one "patch" per sample
                     op = (lambda xs=xs, fxs=fxs, dbs=dbs, Ss=Ss, kp=kp, ids=ids, cn=cn, wsd=wsd: (
                           L.laud_layer_skip_compact(kp, N, ids, cn, wc),
                           L.laud_dyn_bottleneck(xs, fxs, dbs.desc, Ss, ids, cn, xs, wsd)))
                 op()
-                act.append(float(cn.item()) / npatch)
+                act.append(float((gcn if (gate_op is not None and not spatial) else cn).item()) / npatch)
                 ops.append(op)
                 held.append(dbs)
                 ndyn += 1
@@ -382,6 +401,10 @@ def measure_bodies(t, L, B, D, I):
     for sset in ((4, 4, 7, 1), (8, 4, 7, 1), (1, 1, 1, 1)):
         ex["config3_body_b128_granularity_" + "".join(str(v) for v in sset)] = run_body(128, None, (1, 2, 3, 4), S_set=sset, graph=False)
         t.cuda.empty_cache()
+    ex["config5_body_b256_gates_from_layer_masker"] = dict(run_body(256, 0.6, (3,), graph=False, layer_masker=True), note=(
+        "as config 5, the keep gates produced on the device by the layer masker (spatial masker at S = feature size, bias "
+        "calibrated to keep 0.6 on the block's input) instead of a seeded draw"))
+    t.cuda.empty_cache()
     ex["config5_resnet101_body_b256_layer_skip"] = dict(run_body(256, 0.6, (3,)), note=(
         "per-sample per-block keep gates Bernoulli(0.6): stages 1, 2, 4 skip whole samples (S = H), stage 3 "
         "combines the gate with spatial maskers S = 2 at ratio 0.5 of the patches"))

@@ -62,7 +62,10 @@ CASES = [("config3", 128, None, (1, 2, 3, 4), (4, 4, 2, 1), False),
          ("config3_dynamic_first_blocks", 128, None, (1, 2, 3, 4), (4, 4, 2, 1), True),
          ("config3_S4471", 128, None, (1, 2, 3, 4), (4, 4, 7, 1), False),
          ("config3_S8471", 128, None, (1, 2, 3, 4), (8, 4, 7, 1), False),
-         ("config3_S1111", 128, None, (1, 2, 3, 4), (1, 1, 1, 1), False)]
+         ("config3_S1111", 128, None, (1, 2, 3, 4), (1, 1, 1, 1), False),
+         # config 5 with the keep gates produced on the device by the layer masker (the spatial masker at S = feature size,
+         # Sec. 3.2) instead of a seeded draw; the gate stays on the device and feeds the block directly
+         ("config5_layer_masker", 256, -0.6, (3,), (4, 4, 2, 1), False)]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
@@ -73,6 +76,8 @@ def test_resnet101_body_full_size_sampled(case):
     B = L.binding
     name, N, keep_p, spatial_stages, S_set, dyn_first = case
     cfg = 3 if keep_p is None else 5
+    layer_masker = keep_p is not None and keep_p < 0   # (a negative keep ratio marks the layer-masker case)
+    keep_p = abs(keep_p) if keep_p is not None else None
     g = np.random.default_rng(I.seed_for(cfg, 0))
     img = I.round_to(g.standard_normal((N, 224, 224, 3), dtype=np.float32), DT)
     img[NS:2 * NS] = img[:NS]   # the free-running copies
@@ -158,11 +163,31 @@ def test_resnet101_body_full_size_sampled(case):
             if ws is None:
                 ws = D.workspace(L.workspace_size(B.OP_DYN_BOTTLENECK, fx, db.desc, S))
             keep = None
-            if keep_p is not None:
+            if keep_p is not None and not layer_masker:
                 keep = I.bernoulli_mask(I.seed_for(cfg, 7, blk_no), (N,), keep_p)
                 keep[NS:2 * NS] = keep[:NS]
             xd[:NS] = D.to_device(x_ref, DT)
             gpu_in = D.to_host(xd[:2 * NS])
+            keep_d = dev(keep) if keep is not None else None
+            gate_idx = gate_cnt = None
+            if layer_masker:
+                # the oracle's gate of the eight images: its own layer-masker logits on its own input, the threshold in a
+                # gap; the GPU decides all 256 samples on the device, and must agree on the teacher-forced ones
+                wl = I.masker_weights(I.seed_for(cfg, 6, blk_no), co)
+                gl = O.mask_logits(x_ref, hw, wl, 0.0).reshape(NS)
+                order = np.sort(gl)
+                k = int(round((1 - keep_p) * NS))
+                bias_l = -float(order[k - 1] + order[k]) / 2 if 0 < k < NS else 0.0
+                assert k == 0 or k == NS or order[k] - order[k - 1] > 2 * GAP * float(np.sqrt(np.mean(gl * gl)))
+                ref_keep = O.threshold(gl + bias_l).astype(np.uint8)
+                keep_d = t.zeros(N, dtype=t.uint8, device="cuda")
+                gate_idx = t.zeros(N, dtype=t.int32, device="cuda")
+                gate_cnt = t.zeros(1, dtype=t.int32, device="cuda")
+                L.laud_mask_gen(xd, fx, hw, dev(wl), bias_l, None, keep_d, gate_idx, gate_cnt, None, None,
+                                D.workspace(max(L.workspace_size(B.OP_MASK_GEN, fx, None, hw), 256)))
+                t.cuda.synchronize()
+                keep = keep_d.cpu().numpy()
+                assert np.array_equal(keep[:NS], ref_keep), f"block {blk_no}: layer gate differs on the teacher-forced images"
             print(f"{name} block {blk_no}: stage {stage} dynamic block, S = {S}", flush=True)
             if spatial:
                 w = I.masker_weights(I.seed_for(cfg, 5, blk_no), co)
@@ -172,18 +197,23 @@ def test_resnet101_body_full_size_sampled(case):
                 ref_mask = O.threshold(ref0 + bias)
                 if keep is not None:
                     ref_mask = ref_mask * keep[:NS, None, None]
-                L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, dev(w), bias, dev(keep) if keep is not None else None,
-                                             mask, idx, cnt, None, None, xd, ws)
+                L.laud_masker_dyn_bottleneck(xd, fx, db.desc, S, dev(w), bias, keep_d, mask, idx, cnt, None, None, xd, ws)
                 t.cuda.synchronize()
                 gm = mask.cpu().numpy().reshape(N, hp, hp)
             else:   # layer skipping alone: the gate is the mask, one "patch" per sample
                 ref_mask = keep[:NS].reshape(NS, 1, 1)
-                L.laud_layer_skip_compact(dev(keep), N, idx, cnt, wc)
-                L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
-                t.cuda.synchronize()
+                if layer_masker:   # the masker's own index list is the block's
+                    L.laud_dyn_bottleneck(xd, fx, db.desc, S, gate_idx, gate_cnt, xd, ws)
+                    t.cuda.synchronize()
+                    c = int(gate_cnt.item())
+                    assert np.array_equal(gate_idx.cpu().numpy()[:c], O.compact(keep))
+                else:
+                    L.laud_layer_skip_compact(dev(keep), N, idx, cnt, wc)
+                    L.laud_dyn_bottleneck(xd, fx, db.desc, S, idx, cnt, xd, ws)
+                    t.cuda.synchronize()
+                    c = int(cnt.item())
+                    assert np.array_equal(idx.cpu().numpy()[:c], O.compact(keep))
                 gm = keep.reshape(N, 1, 1)
-                c = int(cnt.item())
-                assert np.array_equal(idx.cpu().numpy()[:c], O.compact(keep))
             y_ref = O.dyn_bottleneck(x_ref, p, S, ref_mask)
             got = D.to_host(xd[:2 * NS])
             # teacher-forced slots: exact masks, per-element parity, inactive pixels untouched
