@@ -11,7 +11,7 @@
 //   * Operands reach LDS with LDS-direct 16-byte buffer loads (no VGPR staging, no ds_write): a wave instruction
 //     drops 64 x 16 bytes = 8 rows of a 128-byte K slice.  Bank conflicts are avoided by an XOR swizzle of the 16-byte
 //     chunk position applied on the global side: chunk c of row r lies at position c ^ (r&7) ^ ((r>>3)&1).
-//   * Rings: 4 activation stages (4 KB per 32 pixels each), 3 weight stages (32 KB each, in registers).  One barrier
+//   * Rings: 4 activation stages (4 KB per 32 pixels each), 4 weight stages (32 KB each, in registers).  One barrier
 //     per slice, placed in the middle of the slice's MFMAs; fragments of the next K step (also across slices) are
 //     read before the current step's MFMAs are issued.
 //   * The MFMAs compute the transposed tile (weights as the first operand): a lane then holds, for one pixel,
@@ -42,7 +42,7 @@ namespace tail {
 // pixels, see k_tail); the LDS layout depends on it.
 constexpr int kMaxPB = 3;
 constexpr int kARing = 4;
-constexpr int kWRing = 3;                     // weight slices held / in flight in registers
+constexpr int kWRing = 3;                     // weight slices held / in flight in registers (4 without a channel mask)
 constexpr unsigned kOob = 0x80000000u;        // offset outside every descriptor: reads as zero
 __host__ __device__ constexpr int a_stage(int pb) { return 32 * pb * 128; }        // one 128-byte K slice of every pixel row
 __host__ __device__ constexpr int h2_off(int pb) { return kARing * a_stage(pb); }  // h2 tile: 32*pb pixels x 512 bytes
@@ -135,17 +135,22 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
     }
   }
 
-  // ---- weight stream: three slices in registers (one in use, two in flight) ------------------------------------
+  // ---- weight stream: a ring of slices in registers (one in use, the others in flight) ------------------------------
   typedef const __attribute__((address_space(1))) u32x4* gptr16;
   const gptr16 wsrc = (gptr16)a.wpacked + wave * 256 + lane;
-  u32x4 wr[kWRing][4];
+  // Weight slices held / in flight in registers: four (every compute unit streams the same 1.7 MB at once, which keeps
+  // the L2 at its bandwidth limit and its latency high: 37.3 against 38.3 us per launch with three); three with a
+  // channel mask, whose slice sequences have 9, 18, 27 or 36 entries.
+  constexpr int WR = CS ? kWRing : 4;
+  static_assert(kSl2 % WR == 0, "the slice groups of the 3x3 must end where the last 1x1 starts");
+  u32x4 wr[WR][4];
   auto load_W = [&](int buf, int i) __attribute__((always_inline)) {  // position i of the slice sequence
     const int b = sid(i);
 #pragma unroll
     for (int kg = 0; kg < 4; ++kg) wr[buf][kg] = wsrc[(size_t)b * kSliceChunks + kg * 64];
   };
 #pragma unroll
-  for (int b = 0; b < kWRing; ++b) load_W(b, b);
+  for (int b = 0; b < WR; ++b) load_W(b, b);
 
   // ---- per-channel affine tables --------------------------------------------------------------------------------
   for (int i = tid; i < kMid; i += kThreads) { s_s2[i] = a.s2[i]; s_t2[i] = a.t2[i]; }
@@ -234,7 +239,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
   TAIL_STAMP(1);
   read_frags2(0, 0, 0);
 
-  // Three slices = twelve K steps with static register indices (weight buffer g/4, fragment buffer g%2).
+  // WR slices = 4 WR K steps with static register indices (weight buffer g/4, fragment buffer g%2).
   // One barrier per slice, in its middle: behind it everyone's activations of the next slice have landed and
   // everyone is done with the slice before this one, whose stage is refilled (three slices ahead).
   // Vector-memory operations of a wave in program order, per slice s: A(s+3) x kAI [middle of s], W(s+3) x4 [end
@@ -243,7 +248,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
   // into stages nobody reads any more) so that the count holds to the end.
   auto group2 = [&](int s0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int g = 0; g < 12; ++g) {
+    for (int g = 0; g < 4 * WR; ++g) {
       const int s = s0 + g / 4, kg = g % 4;
       if (kg == 0) TAIL_STAMP(2 + s);
       if (kg < 3) read_frags2((g + 1) & 1, s, kg + 1);
@@ -258,12 +263,12 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
         issue_A(s + 3);
       }
       if (kg == 3) {
-        load_W(g / 4, s + kWRing);  // (the stream continues into the last 1x1)
+        load_W(g / 4, s + WR);  // (the stream continues into the last 1x1)
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
-  for (int s = 0; s < n2; s += 3) group2(s);
+  for (int s = 0; s < n2; s += WR) group2(s);
 
   // ---- h2 = relu(s2 * acc + t2) -> LDS -------------------------------------------------------------------------
   TAIL_STAMP(38);
@@ -381,7 +386,7 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
     for (int st = 0; st < 4 * kKch; ++st) {
       const int ks = st / 4, kg = st % 4;
       const int b = kSl2 + ct * kKch + ks;
-      const int BUF = b % kWRing;
+      const int BUF = b % WR;
       if (kg == 0) TAIL_STAMP(40 + ct * kKch + ks);
       const int cur = st & 1, nxt = cur ^ 1;
       if (kg < 3) read_frags3(nxt, ks, kg + 1);
@@ -402,8 +407,8 @@ __device__ __forceinline__ void tail_tile(const TailArgs& a, const int row0, con
         }
         load_residual_half(ct, t, h);
       }
-      // the weight register just used is refilled for three slices later
-      if (b + kWRing < kNB) wr[BUF][kg] = wsrc[(size_t)(b + kWRing) * kSliceChunks + kg * 64];
+      // the weight register just used is refilled for one ring length later
+      if (b + WR < kNB) wr[BUF][kg] = wsrc[(size_t)(b + WR) * kSliceChunks + kg * 64];
       __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (!DUAL) {  // one accumulator set: the epilogue follows its tile
