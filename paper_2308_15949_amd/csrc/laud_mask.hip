@@ -435,22 +435,39 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
     const int cpr = C / EPC;          // chunks per pixel row
     const int total = S * S * cpr;    // chunks per patch
     // Eight (then four) 16-byte loads of x are put in flight before any of them is consumed: the kernel is a pure
-    // stream over x and what bounds it is the number of bytes in flight per CU.
-    auto chunk_ptr = [&](int c) -> const uint4* {
-      const int j = c / cpr, cv = c - j * cpr;
-      const int dy = j / S, dx = j - dy * S;
-      const size_t pix = ((size_t)n * H + (py * S + dy)) * W + (px * S + dx);
-      return reinterpret_cast<const uint4*>(x + pix * C + (size_t)cv * EPC);
+    // stream over x and what bounds it is the number of bytes in flight per CU.  A thread's chunks are TEAM apart;
+    // their position (pixel of the patch, chunk inside the pixel) is advanced incrementally -- one division at the
+    // start instead of four per load, which at eight loads per lane delayed the last request of a wave by
+    // about a thousand instructions.
+    const size_t pix0 = ((size_t)n * H + (size_t)py * S) * W + (size_t)px * S;  // first pixel of the patch
+    int cv, dy, dx;  // position of the next chunk: chunk column inside the pixel, pixel row / column inside the patch
+    {
+      const int j = tl / cpr;
+      cv = tl - j * cpr;
+      dy = j / S;
+      dx = j - dy * S;
+    }
+    auto next_ptr = [&](int& cv_out) -> const uint4* {
+      // chunks past the end of the patch (the last, partial round of a team) re-read the patch's last chunk
+      const bool in = dy < S;
+      const int ddy = in ? dy : S - 1, ddx = in ? dx : S - 1, ccv = in ? cv : cpr - 1;
+      cv_out = ccv;
+      const uint4* p = reinterpret_cast<const uint4*>(x + (pix0 + (size_t)ddy * W + ddx) * C + (size_t)ccv * EPC);
+      cv += TEAM;
+      while (cv >= cpr) {
+        cv -= cpr;
+        if (++dx == S) { dx = 0; ++dy; }
+      }
+      return p;
     };
-    auto dot = [&](const uint4& raw, int c) -> float {
-      const int cv = c % cpr;
+    auto dot = [&](const uint4& raw, int cvv) -> float {
       float4 w0, w1 = make_float4(0.f, 0.f, 0.f, 0.f);
       if constexpr (WLDS) {
-        const float4* wp = reinterpret_cast<const float4*>(s_w + cv * EPC);
+        const float4* wp = reinterpret_cast<const float4*>(s_w + cvv * EPC);
         w0 = wp[0];
         if constexpr (EPC == 8) w1 = wp[1];
       } else {
-        const float4* wp = reinterpret_cast<const float4*>(w + cv * EPC);
+        const float4* wp = reinterpret_cast<const float4*>(w + cvv * EPC);
         w0 = wp[0];
         if constexpr (EPC == 8) w1 = wp[1];
       }
@@ -467,34 +484,40 @@ __global__ __launch_bounds__(256) void k_mask_logits(const ET* __restrict__ x, i
     // The first eight loads of x are issued before the block fetches the weights, so the two
     // far-memory latencies overlap instead of adding up (the kernel lives for only a few of them).
     uint4 first[8];
+    int fcv[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) first[u] = *chunk_ptr(min(tl + u * TEAM, total - 1));
+    for (int u = 0; u < 8; ++u) first[u] = *next_ptr(fcv[u]);
     if constexpr (WLDS) {
       for (int k = threadIdx.x; k < C; k += 256) s_w[k] = w[k];
       __syncthreads();
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int cc = tl + u * TEAM;
-      const float d = dot(first[u], min(cc, total - 1));
-      acc += cc < total ? d : 0.f;
+      const float d = dot(first[u], fcv[u]);
+      acc += tl + u * TEAM < total ? d : 0.f;
     }
     int c = tl + 8 * TEAM;
     for (; c + 7 * TEAM < total; c += 8 * TEAM) {
       uint4 r[8];
+      int rcv[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) r[u] = *chunk_ptr(c + u * TEAM);
+      for (int u = 0; u < 8; ++u) r[u] = *next_ptr(rcv[u]);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc += dot(r[u], c + u * TEAM);
+      for (int u = 0; u < 8; ++u) acc += dot(r[u], rcv[u]);
     }
     for (; c + 3 * TEAM < total; c += 4 * TEAM) {
       uint4 r[4];
+      int rcv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) r[u] = *chunk_ptr(c + u * TEAM);
+      for (int u = 0; u < 4; ++u) r[u] = *next_ptr(rcv[u]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc += dot(r[u], c + u * TEAM);
+      for (int u = 0; u < 4; ++u) acc += dot(r[u], rcv[u]);
     }
-    for (; c < total; c += TEAM) acc += dot(*chunk_ptr(c), c);
+    for (; c < total; c += TEAM) {
+      int cvv;
+      const uint4 r = *next_ptr(cvv);
+      acc += dot(r, cvv);
+    }
   }
   acc = wave_sum(acc);
   if constexpr (TEAM > kWave) {
